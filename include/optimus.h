@@ -1,0 +1,258 @@
+/*
+ * optimus.h — C ABI of the per-device hot path of the 2D (SUMMA) transformer
+ * scheme of arXiv 2104.05343, for one AMD MI355X (gfx950).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Pointers.  Every tensor pointer is a DEVICE pointer owned by the caller; the
+ *   library neither frees nor retains it.  `stream` is a hipStream_t passed as
+ *   void* (NULL = the default stream).  Calls validate their arguments on the
+ *   host, enqueue kernels on `stream` and return without synchronising.
+ *   `optimus_layer_cfg` / `optimus_layer_tensors` structs are HOST memory.
+ * Grid.  The method distributes every matrix over a q x q device mesh
+ *   (Section 2.4): a logical row-major matrix T[R x C] is cut evenly into q*q
+ *   sub-blocks, block (r, c) belonging to device (r, c).  This library keeps
+ *   all q*q blocks resident on one GPU in BLOCK-MAJOR storage: block (r, c)
+ *   starts at element (r*q + c) * (R/q) * (C/q) and is itself row-major with
+ *   leading dimension C/q — the contiguous panel a broadcast would deliver.
+ *   Vectors of length C (biases, LayerNorm affine) are stored whole; device
+ *   column j uses elements j*C/q .. (j+1)*C/q-1.
+ * Coordinates.  (i, j) names the device whose share is computed.  i = j =
+ *   OPTIMUS_ALL (-1) computes the share of every device in one call ("grid
+ *   mode"); mixing -1 with a real coordinate is OPTIMUS_ECOORD.  With explicit
+ *   (i, j) a call reads only the peer blocks that device would receive and
+ *   writes only that device's output block(s).
+ * dtype.  OPTIMUS_FP32: fp32 storage, fp32 FMA accumulation.  OPTIMUS_BF16:
+ *   bf16 storage (round-to-nearest-even on store), fp32 accumulation on the
+ *   matrix cores; statistics, soft-max sums, weight and bias gradients stay
+ *   fp32.
+ * Errors.  Return value 0 = OK, otherwise one of the OPTIMUS_E* codes below;
+ *   on any error nothing has been enqueued.  No exceptions, no global state
+ *   apart from a per-process cache of device properties.
+ * Determinism.  No floating-point atomics: the same call on the same inputs
+ *   gives bitwise identical output.
+ */
+#ifndef OPTIMUS_H_
+#define OPTIMUS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  OPTIMUS_OK = 0,
+  OPTIMUS_EINVAL = 1,     /* null pointer or bad enum value                          */
+  OPTIMUS_ESHAPE = 2,     /* size <= 0 or not divisible as the partition requires    */
+  OPTIMUS_ECOORD = 3,     /* i or j outside [0, q) and not the OPTIMUS_ALL wildcard  */
+  OPTIMUS_EDTYPE = 4,     /* dtype not supported by this entry point                 */
+  OPTIMUS_EWORKSPACE = 5, /* workspace missing or smaller than the query says        */
+  OPTIMUS_EHIP = 6        /* the HIP runtime refused a launch                        */
+};
+
+enum { OPTIMUS_FP32 = 0, OPTIMUS_BF16 = 1 };
+enum { OPTIMUS_FORM_AB = 0, OPTIMUS_FORM_ABT = 1, OPTIMUS_FORM_ATB = 2 };
+#define OPTIMUS_ALL (-1)
+
+/* Human-readable name of an error code (static string, never NULL). */
+const char* optimus_error_string(int code);
+/* ABI version of this header (bumped when a signature changes). */
+int optimus_abi_version(void);
+
+/* ---- block addressing (Section 2.4: "evenly partitioned into q x q sub-blocks") ----
+ * Convert between a row-major logical matrix [R x C] and block-major storage.
+ * src and dst are distinct device buffers of R*C elements of elem_bytes (2 or 4)
+ * bytes each.  Pure data movement: bit-exact.  ESHAPE unless q | R and q | C. */
+int optimus_pack_blocks(const void* src_rowmajor, void* dst_blockmajor, int64_t R, int64_t C,
+                        int q, int elem_bytes, void* stream);
+int optimus_unpack_blocks(const void* src_blockmajor, void* dst_rowmajor, int64_t R, int64_t C,
+                          int q, int elem_bytes, void* stream);
+
+/* ---- the three SUMMA products (Section 2.4, Algorithms 1-3, Eq. 1-3) ----
+ * (M, N) is always the logical OUTPUT shape and K the logical contraction
+ * length; all three must be positive multiples of q.  A, B, C are block-major.
+ * Device (i, j) ends up holding (owner view of Algorithms 1-3; the per-step
+ * broadcasts become reads of resident peer blocks, the row/column reduce of
+ * Algorithms 2-3 becomes the sum over l inside one accumulator):
+ *   optimus_summa_ab :  C_ij = sum_l A_il   * B_lj      A[M x K], B[K x N]
+ *   optimus_summa_abt:  C_ij = sum_l A_il   * (B_jl)^T  A[M x K], B[N x K]
+ *   optimus_summa_atb:  C_ij = sum_l (A_li)^T * B_lj    A[K x M], B[K x N]
+ * The q panel steps are fused into one k-loop; C is written once.  C must not
+ * alias A or B.
+ * ws / ws_bytes: optional device scratch (may be NULL / 0).  When it is at
+ * least optimus_summa_workspace_bytes(...) the library may split the panel
+ * loop of skinny outputs over several workgroups and combine the fp32 partial
+ * tiles in a fixed order (still deterministic); without it no split is used. */
+int optimus_summa_ab(const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N,
+                     int q, int i, int j, int dtype, void* ws, size_t ws_bytes, void* stream);
+int optimus_summa_abt(const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N,
+                      int q, int i, int j, int dtype, void* ws, size_t ws_bytes, void* stream);
+int optimus_summa_atb(const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N,
+                      int q, int i, int j, int dtype, void* ws, size_t ws_bytes, void* stream);
+size_t optimus_summa_workspace_bytes(int form, int64_t M, int64_t K, int64_t N, int q, int i, int j,
+                                     int dtype);
+
+/* Epilogue applied to the accumulator of a SUMMA product before the single
+ * store of C_ij (Section 3.2.1: non-linearities are applied locally per
+ * block; Section 3.2.2: bias-add uses the column slice of a row-0 parameter).
+ * In order:  t = acc;  t += bias[j-slice];  if pre_act: pre_act_ij = t;
+ * if act == 1: t = GeLU(t) (exact, x*Phi(x));  if gelu_grad_of: t *= GeLU'(gelu_grad_of_ij);
+ * if residual: t += residual_ij;  C_ij = t.
+ * bias is fp32 [N]; pre_act, gelu_grad_of, residual are block-major [M x N]
+ * in the call's dtype.  out_fp32 != 0 stores C as fp32 even for bf16 inputs
+ * (weight gradients).  Any pointer may be NULL to skip its step. */
+typedef struct {
+  const float* bias;
+  void* pre_act;
+  int act;
+  const void* gelu_grad_of;
+  const void* residual;
+  int out_fp32;
+} optimus_epilogue;
+
+/* form: OPTIMUS_FORM_*.  epi may be NULL (plain product). */
+int optimus_summa_ex(int form, const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N,
+                     int q, int i, int j, int dtype, const optimus_epilogue* epi, void* ws,
+                     size_t ws_bytes, void* stream);
+
+/* Bias gradient (Section 3.2.2, bias-add backward): device (i, j)'s partial
+ * = column sums of its block dY_ij; the reduce up the column to row 0 is the
+ * sum over i of these partials.  dY block-major [M x N]; out fp32
+ * [q][q][N/q], entry (i, j) written. */
+int optimus_bias_grad(const void* dY, float* dbias_part, int64_t M, int64_t N, int q, int i, int j,
+                      int dtype, void* stream);
+
+/* ---- 2D LayerNorm (Section 3.2.2) ----
+ * X block-major [M x H]; a row's H entries are spread over the q devices of
+ * grid row i.  stats is fp32 [q][q][M/q][2]: entry (i, l) holds what device
+ * (i, l) contributes to the row all-reduce, (sum x, sum x^2) per local row in
+ * forward and (sum xhat*g, sum g) with g = dy*gamma in backward.
+ *
+ * optimus_layernorm2d_stats(i, l): writes device (i, l)'s forward partial only.
+ * optimus_layernorm2d(i, j): computes its own partial (and stores it in
+ *   stats[i][j]), adds the q-1 peer partials already in stats[i][*], then
+ *   xhat = (x - E[x]) * rstd, rstd = 1/sqrt(max(E[x^2]-E[x]^2, 0) + eps),
+ *   y = gamma_j*xhat + beta_j.  Writes Y_ij, xhat_ij (same dtype as X) and
+ *   rstd (fp32 [q][q][M/q], entry (i, j)).  In grid mode all partials are
+ *   produced first, so no prior _stats call is needed.
+ * optimus_layernorm2d_bwd(i, j): dX_ij = rstd*(g - xhat*mean(xhat*g) - mean(g))
+ *   [+ dres_ij if dres != NULL: gradient arriving over the residual branch],
+ *   with the two means taken over the whole row via `stats` exactly as in
+ *   forward; dgamma_part/dbeta_part fp32 [q][q][H/q]: column sums of dy*xhat
+ *   and dy over the block's rows (entry (i, j) written).
+ * gamma, beta: fp32 [H]. */
+int optimus_layernorm2d_stats(const void* X, float* stats, int64_t M, int64_t H, int q, int i, int l,
+                              int dtype, void* stream);
+int optimus_layernorm2d(const void* X, const float* gamma, const float* beta, void* Y, void* xhat,
+                        float* rstd, float* stats, int64_t M, int64_t H, int q, int i, int j,
+                        float eps, int dtype, void* stream);
+int optimus_layernorm2d_bwd_stats(const void* dY, const void* xhat, const float* gamma, float* stats,
+                                  int64_t M, int64_t H, int q, int i, int l, int dtype, void* stream);
+int optimus_layernorm2d_bwd(const void* dY, const void* xhat, const float* rstd, const float* gamma,
+                            const void* dres, void* dX, float* dgamma_part, float* dbeta_part,
+                            float* stats, int64_t M, int64_t H, int q, int i, int j, int dtype,
+                            void* stream);
+
+/* ---- head-partitioned attention on the device's blocks (Sections 2.1, 3.2.1) ----
+ * Device (i, j) holds n/q heads of b/q whole sequences.  qkv is block-major
+ * [b*s x 3h] (rows sequence-major: row = seq*s + t; columns head-major:
+ * head*3d + {0:Q,1:K,2:V}*d + e with d = h/n), so block (i, j) contains Q, K,
+ * V of heads j*n/q.. of sequences i*b/q...  For every local (sequence, head):
+ * S = Q K^T / sqrt(d), causal mask if causal != 0, P = softmax rows (fp32),
+ * O = P V.  probs: [q][q][(b/q)*(n/q)][s][s] in the call's dtype (entries above
+ * the diagonal are exact zeros when causal); attn: block-major [b*s x h].
+ * Backward: dV = P^T dO, dP = dO V^T, dS = P*(dP - rowsum(dP*P)),
+ * dQ = dS K / sqrt(d), dK = dS^T Q / sqrt(d); d_qkv has qkv's layout.
+ * ws must hold optimus_attention_workspace_bytes(...) bytes. bf16 only.
+ * Requires q | b, q | n, n | h, d % 8 == 0, s % 8 == 0. */
+int optimus_attention_fwd(const void* qkv, void* probs, void* attn, int b, int s, int h, int n, int q,
+                          int i, int j, int causal, int dtype, void* ws, size_t ws_bytes, void* stream);
+int optimus_attention_bwd(const void* qkv, const void* probs, const void* d_attn, void* d_qkv, int b,
+                          int s, int h, int n, int q, int i, int j, int causal, int dtype, void* ws,
+                          size_t ws_bytes, void* stream);
+size_t optimus_attention_workspace_bytes(int b, int s, int h, int n, int q);
+
+/* ---- one transformer layer on device (i, j) (Section 3.2; Eq. 1) ----
+ * Wiring: a1 = LN1(x); qkv = a1 Wqkv + b; attn = local attention;
+ * h_mid = x + attn Wo + b; a2 = LN2(h_mid); pre = a2 W1 + b; g = GeLU(pre);
+ * out = h_mid + g W2 + b.  Backward follows Eq. 1 for every linear layer
+ * (dX = dY W^T by the AB^T product, dW = X^T dY by the A^T B product), uses the
+ * saved activations (no recomputation) and no dropout.
+ * Every matrix is block-major over the q x q grid; vectors are fp32 and whole.
+ * In grid mode (i = j = -1) each stage runs for all q*q devices before the
+ * next starts, filling every block of every tensor.  With explicit (i, j) only
+ * that device's blocks are recomputed; peers' blocks of the previous stage must
+ * be resident (left by a grid-mode call on the same tensors). */
+typedef struct {
+  int b, s, h, n, q;
+  float eps;
+  int causal;
+  int dtype; /* OPTIMUS_BF16 only */
+} optimus_layer_cfg;
+
+typedef struct {
+  /* inputs / parameters */
+  const void* x;      /* [M x h]  */
+  const float* ln1_g; const float* ln1_b;  /* [h] */
+  const void* w_qkv;  /* [h x 3h] */
+  const float* b_qkv; /* [3h]     */
+  const void* w_o;    /* [h x h]  */
+  const float* b_o;   /* [h]      */
+  const float* ln2_g; const float* ln2_b;  /* [h] */
+  const void* w1;     /* [h x 4h] */
+  const float* b1;    /* [4h]     */
+  const void* w2;     /* [4h x h] */
+  const float* b2;    /* [h]      */
+  /* forward tensors, written by optimus_layer_fwd, read by optimus_layer_bwd */
+  void* ln1_out; void* xhat1; float* rstd1; float* stats1; /* [M x h], [M x h], [q][q][M/q], [q][q][M/q][2] */
+  void* qkv;      /* [M x 3h] */
+  void* probs;    /* [q][q][(b/q)(n/q)][s][s] */
+  void* attn;     /* [M x h]  */
+  void* h_mid;    /* [M x h]  */
+  void* ln2_out; void* xhat2; float* rstd2; float* stats2;
+  void* pre_gelu; /* [M x 4h] */
+  void* gelu;     /* [M x 4h] */
+  void* out;      /* [M x h]  */
+  /* backward: input gradient, activation gradients (resident for peers), outputs */
+  const void* d_out;  /* [M x h] */
+  void* d_pre_gelu;   /* [M x 4h] */
+  void* d_ln2_out;    /* [M x h]  */
+  void* d_h_mid;      /* [M x h]  */
+  void* d_attn;       /* [M x h]  */
+  void* d_qkv;        /* [M x 3h] */
+  void* d_ln1_out;    /* [M x h]  */
+  void* d_x;          /* [M x h]  */
+  float* bstats1; float* bstats2; /* [q][q][M/q][2] backward LayerNorm partials */
+  float* d_w_qkv; float* d_w_o; float* d_w1; float* d_w2;         /* fp32, block-major, weight shapes */
+  float* d_b_qkv; float* d_b_o; float* d_b1; float* d_b2;         /* fp32 partials [q][q][N/q]        */
+  float* d_ln1_g; float* d_ln1_b; float* d_ln2_g; float* d_ln2_b; /* fp32 partials [q][q][h/q]        */
+} optimus_layer_tensors;
+
+/* Scratch bytes optimus_layer_fwd / _bwd need in `ws` (attention scores and
+ * their gradients for one device, plus split-k partial tiles). */
+size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg);
+int optimus_layer_fwd(const optimus_layer_cfg* cfg, const optimus_layer_tensors* t, int i, int j,
+                      void* ws, size_t ws_bytes, void* stream);
+int optimus_layer_bwd(const optimus_layer_cfg* cfg, const optimus_layer_tensors* t, int i, int j,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---- flop accounting (Table 1) ----
+ * optimus_gemm_flops: 2*(M/q)*K*(N/q), one device's share of one product.
+ * optimus_layer_flops: one device's share of a layer; what = 0 forward,
+ * 1 backward without recomputation.  Attention is counted densely (non-causal)
+ * so that forward equals 2*(12 b s h^2 + 2 b s^2 h)/q^2. */
+int64_t optimus_gemm_flops(int64_t M, int64_t K, int64_t N, int q);
+int64_t optimus_layer_flops(const optimus_layer_cfg* cfg, int what);
+
+/* ---- tuning hook for benchmark sweeps (no effect on results beyond summation order) ----
+ * Force the matrix-core tile variant used by bf16 products: 0 = 256x256 (4 waves), 1 = 256x128,
+ * 2 = 128x256, 3 = 128x128, 4 = 256x256 (8 waves), 5 = bounds-checked 128x128; -1 = automatic.
+ * A variant whose tile does not divide the block falls back to the automatic choice. */
+void optimus_debug_set_gemm_variant(int v);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPTIMUS_H_ */

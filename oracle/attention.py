@@ -32,11 +32,13 @@ def head_forward(Q, K, V, causal=True):
     return P @ V, P
 
 
-def head_backward(Q, K, V, P, dO):
+def head_backward(Q, K, V, P, dO, store=None):
     """Gradients for one (sequence, head).
 
     dV = P^T dO; dP = dO V^T; dS = P * (dP - rowsum(dP * P));
     dQ = dS K / sqrt(d); dK = dS^T Q / sqrt(d).
+    ``store`` (optional) is applied to dS, the one intermediate of this step that the
+    device keeps in its storage precision before the last two products.
     """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
@@ -47,6 +49,8 @@ def head_backward(Q, K, V, P, dO):
     dV = P.T @ dO
     dP = dO @ V.T
     dS = P * (dP - (dP * P).sum(axis=1, keepdims=True))
+    if store is not None:
+        dS = store("d_scores", dS)
     dQ = dS @ K / np.sqrt(d)
     dK = dS.T @ Q / np.sqrt(d)
     return dQ, dK, dV
@@ -61,8 +65,10 @@ def split_qkv(qkv, b, s, n, seq, head):
     return (qkv[rows, c0:c0 + d], qkv[rows, c0 + d:c0 + 2 * d], qkv[rows, c0 + 2 * d:c0 + 3 * d])
 
 
-def forward(qkv, b, s, n, causal=True, keep_probs=True):
-    """qkv [b*s, 3h] -> attn [b*s, h] (heads concatenated) and probs [b, n, s, s]."""
+def forward(qkv, b, s, n, causal=True, keep_probs=True, store=None):
+    """qkv [b*s, 3h] -> attn [b*s, h] (heads concatenated) and probs [b, n, s, s].
+    With ``store``, P is passed through it before the P V product (the device multiplies the
+    probabilities it saved)."""
     qkv = np.asarray(qkv, dtype=np.float64)
     h = qkv.shape[1] // 3
     d = h // n
@@ -72,14 +78,18 @@ def forward(qkv, b, s, n, causal=True, keep_probs=True):
         for head in range(n):
             Q, K, V = split_qkv(qkv, b, s, n, seq, head)
             O, P = head_forward(Q, K, V, causal)
+            if store is not None:
+                P = store("probs", P)
+                O = P @ np.asarray(V, dtype=np.float64)
             out[seq * s:(seq + 1) * s, head * d:(head + 1) * d] = O
             if keep_probs:
                 probs[seq, head] = P
     return out, probs
 
 
-def backward(qkv, d_attn, b, s, n, causal=True):
-    """d_attn [b*s, h] -> d_qkv [b*s, 3h] (probabilities are recomputed in fp64)."""
+def backward(qkv, d_attn, b, s, n, causal=True, probs=None, store=None):
+    """d_attn [b*s, h] -> d_qkv [b*s, 3h].  Probabilities are recomputed in fp64 unless the saved
+    ones ([b, n, s, s]) are passed in."""
     qkv = np.asarray(qkv, dtype=np.float64)
     d_attn = np.asarray(d_attn, dtype=np.float64)
     h = qkv.shape[1] // 3
@@ -88,9 +98,9 @@ def backward(qkv, d_attn, b, s, n, causal=True):
     for seq in range(b):
         for head in range(n):
             Q, K, V = split_qkv(qkv, b, s, n, seq, head)
-            _, P = head_forward(Q, K, V, causal)
+            P = probs[seq, head] if probs is not None else head_forward(Q, K, V, causal)[1]
             dO = d_attn[seq * s:(seq + 1) * s, head * d:(head + 1) * d]
-            dQ, dK, dV = head_backward(Q, K, V, P, dO)
+            dQ, dK, dV = head_backward(Q, K, V, P, dO, store)
             rows = slice(seq * s, (seq + 1) * s)
             c0 = head * 3 * d
             d_qkv[rows, c0:c0 + d] = dQ

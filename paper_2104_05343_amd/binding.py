@@ -1,0 +1,247 @@
+"""Thin ctypes binding of liboptimus.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors used purely as device-memory handles (``data_ptr()``); the stream is torch's
+current HIP stream unless one is passed.  Nothing here computes.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "liboptimus.so")
+
+OK, EINVAL, ESHAPE, ECOORD, EDTYPE, EWORKSPACE, EHIP = range(7)
+FP32, BF16 = 0, 1
+FORM_AB, FORM_ABT, FORM_ATB = 0, 1, 2
+ALL = -1
+FORMS = {"ab": FORM_AB, "abt": FORM_ABT, "atb": FORM_ATB}
+
+
+class OptimusError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: error {code}: {error_string(code)}")
+
+
+class Epilogue(C.Structure):
+    _fields_ = [("bias", C.c_void_p), ("pre_act", C.c_void_p), ("act", C.c_int),
+                ("gelu_grad_of", C.c_void_p), ("residual", C.c_void_p), ("out_fp32", C.c_int)]
+
+
+class LayerCfg(C.Structure):
+    _fields_ = [("b", C.c_int), ("s", C.c_int), ("h", C.c_int), ("n", C.c_int), ("q", C.c_int),
+                ("eps", C.c_float), ("causal", C.c_int), ("dtype", C.c_int)]
+
+
+LAYER_TENSOR_FIELDS = [
+    "x", "ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2",
+    "ln1_out", "xhat1", "rstd1", "stats1", "qkv", "probs", "attn", "h_mid",
+    "ln2_out", "xhat2", "rstd2", "stats2", "pre_gelu", "gelu", "out",
+    "d_out", "d_pre_gelu", "d_ln2_out", "d_h_mid", "d_attn", "d_qkv", "d_ln1_out", "d_x",
+    "bstats1", "bstats2", "d_w_qkv", "d_w_o", "d_w1", "d_w2", "d_b_qkv", "d_b_o", "d_b1", "d_b2",
+    "d_ln1_g", "d_ln1_b", "d_ln2_g", "d_ln2_b",
+]
+
+
+class LayerTensors(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in LAYER_TENSOR_FIELDS]
+
+
+_lib = None
+
+_I64, _INT, _P, _SZ, _F = C.c_int64, C.c_int, C.c_void_p, C.c_size_t, C.c_float
+_SUMMA_ARGS = [_P, _P, _P, _I64, _I64, _I64, _INT, _INT, _INT, _INT, _P, _SZ, _P]
+SIGNATURES = {
+    "optimus_error_string": (C.c_char_p, [_INT]),
+    "optimus_abi_version": (_INT, []),
+    "optimus_pack_blocks": (_INT, [_P, _P, _I64, _I64, _INT, _INT, _P]),
+    "optimus_unpack_blocks": (_INT, [_P, _P, _I64, _I64, _INT, _INT, _P]),
+    "optimus_summa_ab": (_INT, _SUMMA_ARGS),
+    "optimus_summa_abt": (_INT, _SUMMA_ARGS),
+    "optimus_summa_atb": (_INT, _SUMMA_ARGS),
+    "optimus_summa_workspace_bytes": (_SZ, [_INT, _I64, _I64, _I64, _INT, _INT, _INT, _INT]),
+    "optimus_summa_ex": (_INT, [_INT, _P, _P, _P, _I64, _I64, _I64, _INT, _INT, _INT, _INT, C.POINTER(Epilogue), _P, _SZ, _P]),
+    "optimus_bias_grad": (_INT, [_P, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
+    "optimus_layernorm2d_stats": (_INT, [_P, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
+    "optimus_layernorm2d": (_INT, [_P, _P, _P, _P, _P, _P, _P, _I64, _I64, _INT, _INT, _INT, _F, _INT, _P]),
+    "optimus_layernorm2d_bwd_stats": (_INT, [_P, _P, _P, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
+    "optimus_layernorm2d_bwd": (_INT, [_P, _P, _P, _P, _P, _P, _P, _P, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
+    "optimus_attention_fwd": (_INT, [_P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
+    "optimus_attention_bwd": (_INT, [_P, _P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
+    "optimus_attention_workspace_bytes": (_SZ, [_INT, _INT, _INT, _INT, _INT]),
+    "optimus_layer_workspace_bytes": (_SZ, [C.POINTER(LayerCfg)]),
+    "optimus_layer_fwd": (_INT, [C.POINTER(LayerCfg), C.POINTER(LayerTensors), _INT, _INT, _P, _SZ, _P]),
+    "optimus_layer_bwd": (_INT, [C.POINTER(LayerCfg), C.POINTER(LayerTensors), _INT, _INT, _P, _SZ, _P]),
+    "optimus_gemm_flops": (_I64, [_I64, _I64, _I64, _INT]),
+    "optimus_layer_flops": (_I64, [C.POINTER(LayerCfg), _INT]),
+    "optimus_debug_set_gemm_variant": (None, [_INT]),
+}
+
+
+def lib():
+    """Load liboptimus.so (once).  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not found: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise OptimusError(rc, where)
+
+
+def error_string(code: int) -> str:
+    return lib().optimus_error_string(code).decode()
+
+
+def abi_version() -> int:
+    return lib().optimus_abi_version()
+
+
+def pack_blocks(src, dst, R, C_, q, elem_bytes, stream=None):
+    _check(lib().optimus_pack_blocks(_ptr(src), _ptr(dst), R, C_, q, elem_bytes, _stream(stream)), "optimus_pack_blocks")
+
+
+def unpack_blocks(src, dst, R, C_, q, elem_bytes, stream=None):
+    _check(lib().optimus_unpack_blocks(_ptr(src), _ptr(dst), R, C_, q, elem_bytes, _stream(stream)), "optimus_unpack_blocks")
+
+
+def _summa(name, A, B, Cm, M, K, N, q, i, j, dtype, ws, stream):
+    p, n = _ws(ws)
+    _check(getattr(lib(), name)(_ptr(A), _ptr(B), _ptr(Cm), M, K, N, q, i, j, dtype, p, n, _stream(stream)), name)
+
+
+def summa_ab(A, B, Cm, M, K, N, q, i, j, dtype, ws=None, stream=None):
+    _summa("optimus_summa_ab", A, B, Cm, M, K, N, q, i, j, dtype, ws, stream)
+
+
+def summa_abt(A, B, Cm, M, K, N, q, i, j, dtype, ws=None, stream=None):
+    _summa("optimus_summa_abt", A, B, Cm, M, K, N, q, i, j, dtype, ws, stream)
+
+
+def summa_atb(A, B, Cm, M, K, N, q, i, j, dtype, ws=None, stream=None):
+    _summa("optimus_summa_atb", A, B, Cm, M, K, N, q, i, j, dtype, ws, stream)
+
+
+def summa(form, *args, **kw):
+    return {"ab": summa_ab, "abt": summa_abt, "atb": summa_atb}[form](*args, **kw)
+
+
+def summa_workspace_bytes(form, M, K, N, q, i, j, dtype) -> int:
+    return lib().optimus_summa_workspace_bytes(FORMS[form] if isinstance(form, str) else form, M, K, N, q, i, j, dtype)
+
+
+def summa_ex(form, A, B, Cm, M, K, N, q, i, j, dtype, bias=None, pre_act=None, act=0, gelu_grad_of=None,
+             residual=None, out_fp32=False, ws=None, stream=None):
+    e = Epilogue(_ptr(bias), _ptr(pre_act), act, _ptr(gelu_grad_of), _ptr(residual), 1 if out_fp32 else 0)
+    p, n = _ws(ws)
+    f = FORMS[form] if isinstance(form, str) else form
+    _check(lib().optimus_summa_ex(f, _ptr(A), _ptr(B), _ptr(Cm), M, K, N, q, i, j, dtype, C.byref(e), p, n, _stream(stream)),
+           "optimus_summa_ex")
+
+
+def bias_grad(dY, dbias_part, M, N, q, i, j, dtype, stream=None):
+    _check(lib().optimus_bias_grad(_ptr(dY), _ptr(dbias_part), M, N, q, i, j, dtype, _stream(stream)), "optimus_bias_grad")
+
+
+def layernorm2d_stats(X, stats, M, H, q, i, l, dtype, stream=None):
+    _check(lib().optimus_layernorm2d_stats(_ptr(X), _ptr(stats), M, H, q, i, l, dtype, _stream(stream)), "optimus_layernorm2d_stats")
+
+
+def layernorm2d(X, gamma, beta, Y, xhat, rstd, stats, M, H, q, i, j, eps, dtype, stream=None):
+    _check(lib().optimus_layernorm2d(_ptr(X), _ptr(gamma), _ptr(beta), _ptr(Y), _ptr(xhat), _ptr(rstd), _ptr(stats), M, H, q, i, j,
+                                     eps, dtype, _stream(stream)), "optimus_layernorm2d")
+
+
+def layernorm2d_bwd_stats(dY, xhat, gamma, stats, M, H, q, i, l, dtype, stream=None):
+    _check(lib().optimus_layernorm2d_bwd_stats(_ptr(dY), _ptr(xhat), _ptr(gamma), _ptr(stats), M, H, q, i, l, dtype, _stream(stream)),
+           "optimus_layernorm2d_bwd_stats")
+
+
+def layernorm2d_bwd(dY, xhat, rstd, gamma, dres, dX, dgamma_part, dbeta_part, stats, M, H, q, i, j, dtype, stream=None):
+    _check(lib().optimus_layernorm2d_bwd(_ptr(dY), _ptr(xhat), _ptr(rstd), _ptr(gamma), _ptr(dres), _ptr(dX), _ptr(dgamma_part),
+                                         _ptr(dbeta_part), _ptr(stats), M, H, q, i, j, dtype, _stream(stream)),
+           "optimus_layernorm2d_bwd")
+
+
+def attention_workspace_bytes(b, s, h, n, q) -> int:
+    return lib().optimus_attention_workspace_bytes(b, s, h, n, q)
+
+
+def attention_fwd(qkv, probs, attn, b, s, h, n, q, i, j, causal, dtype, ws, stream=None):
+    p, nb = _ws(ws)
+    _check(lib().optimus_attention_fwd(_ptr(qkv), _ptr(probs), _ptr(attn), b, s, h, n, q, i, j, int(causal), dtype, p, nb,
+                                       _stream(stream)), "optimus_attention_fwd")
+
+
+def attention_bwd(qkv, probs, d_attn, d_qkv, b, s, h, n, q, i, j, causal, dtype, ws, stream=None):
+    p, nb = _ws(ws)
+    _check(lib().optimus_attention_bwd(_ptr(qkv), _ptr(probs), _ptr(d_attn), _ptr(d_qkv), b, s, h, n, q, i, j, int(causal), dtype,
+                                       p, nb, _stream(stream)), "optimus_attention_bwd")
+
+
+def layer_workspace_bytes(cfg: LayerCfg) -> int:
+    return lib().optimus_layer_workspace_bytes(C.byref(cfg))
+
+
+def make_layer_tensors(tensors: dict) -> LayerTensors:
+    """tensors: name -> torch tensor (or None) for every field of optimus_layer_tensors."""
+    t = LayerTensors()
+    for name in LAYER_TENSOR_FIELDS:
+        setattr(t, name, _ptr(tensors.get(name)))
+    return t
+
+
+def layer_fwd(cfg: LayerCfg, t: LayerTensors, i, j, ws, stream=None):
+    p, nb = _ws(ws)
+    _check(lib().optimus_layer_fwd(C.byref(cfg), C.byref(t), i, j, p, nb, _stream(stream)), "optimus_layer_fwd")
+
+
+def layer_bwd(cfg: LayerCfg, t: LayerTensors, i, j, ws, stream=None):
+    p, nb = _ws(ws)
+    _check(lib().optimus_layer_bwd(C.byref(cfg), C.byref(t), i, j, p, nb, _stream(stream)), "optimus_layer_bwd")
+
+
+def gemm_flops(M, K, N, q) -> int:
+    return lib().optimus_gemm_flops(M, K, N, q)
+
+
+def layer_flops(cfg: LayerCfg, what: int) -> int:
+    return lib().optimus_layer_flops(C.byref(cfg), what)
+
+
+def debug_set_gemm_variant(v: int):
+    lib().optimus_debug_set_gemm_variant(v)

@@ -1,0 +1,549 @@
+// C ABI of the library: argument validation, block addressing on the q x q grid, and the composition of the
+// kernels into the paper's operations (Algorithms 1-3, Section 3.2).  Every entry point validates first and
+// enqueues nothing on error.
+#include <math.h>
+
+#include "common.hpp"
+
+using namespace optimus;
+
+namespace {
+
+inline hipStream_t as_stream(void* s) { return (hipStream_t)s; }
+
+int check_coords(int q, int i, int j) {
+  if (q <= 0) return OPTIMUS_ESHAPE;
+  if (i == OPTIMUS_ALL && j == OPTIMUS_ALL) return OPTIMUS_OK;
+  if (i < 0 || j < 0 || i >= q || j >= q) return OPTIMUS_ECOORD;
+  return OPTIMUS_OK;
+}
+inline bool is_grid(int i, int j) { return i == OPTIMUS_ALL && j == OPTIMUS_ALL; }
+inline size_t esize(int dtype) { return dtype == OPTIMUS_BF16 ? 2 : 4; }
+inline const void* off(const void* p, long long elems, size_t es) { return p ? (const char*)p + elems * (long long)es : nullptr; }
+inline void* off(void* p, long long elems, size_t es) { return p ? (char*)p + elems * (long long)es : nullptr; }
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int check_mkn(int64_t M, int64_t K, int64_t N, int q) {
+  if (q <= 0 || M <= 0 || K <= 0 || N <= 0) return OPTIMUS_ESHAPE;
+  if (M % q || K % q || N % q) return OPTIMUS_ESHAPE;
+  if (M / q > 0x7fffffff || K / q > 0x7fffffff || N / q > 0x7fffffff) return OPTIMUS_ESHAPE;
+  return OPTIMUS_OK;
+}
+
+// Owner-view descriptor of one SUMMA product for device (i, j), or for the whole grid.
+//   AB : C_ij = sum_l A_il B_lj ;  ABT: C_ij = sum_l A_il (B_jl)^T ;  ATB: C_ij = sum_l (A_li)^T B_lj
+GemmDesc summa_desc(int form, const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N, int q, int i, int j,
+                    int dtype, const optimus_epilogue* epi) {
+  GemmDesc d = {};
+  const int Mb = (int)(M / q), Nb = (int)(N / q), Kp = (int)(K / q);
+  d.Mb = Mb; d.Nb = Nb; d.Kp = Kp; d.nl = q; d.dtype = dtype;
+  const long long blkA = (long long)Mb * Kp, blkB = (long long)Kp * Nb, blkC = (long long)Mb * Nb;
+  if (form == OPTIMUS_FORM_ATB) { d.a_kcontig = 0; d.lda = Mb; d.sAl = q * blkA; d.sA1 = blkA; d.sA0 = 0; }
+  else { d.a_kcontig = 1; d.lda = Kp; d.sAl = blkA; d.sA1 = q * blkA; d.sA0 = 0; }
+  if (form == OPTIMUS_FORM_ABT) { d.b_kcontig = 1; d.ldb = Kp; d.sBl = blkB; d.sB0 = q * blkB; d.sB1 = 0; }
+  else { d.b_kcontig = 0; d.ldb = Nb; d.sBl = q * blkB; d.sB0 = blkB; d.sB1 = 0; }
+  d.ldc = Nb; d.sC1 = q * blkC; d.sC0 = blkC;
+  d.alpha = 1.0f;
+  d.splits = 1;
+  const size_t es = esize(dtype);
+  const bool out32 = epi && epi->out_fp32 && dtype == OPTIMUS_BF16;
+  d.out_fp32 = out32 ? 1 : 0;
+  const size_t ces = out32 ? 4 : es;
+  const float* bias = epi ? epi->bias : nullptr;
+  void* pre = epi ? epi->pre_act : nullptr;
+  const void* gg = epi ? epi->gelu_grad_of : nullptr;
+  const void* res = epi ? epi->residual : nullptr;
+  d.act = epi ? epi->act : 0;
+  d.sBias0 = Nb;
+  if (is_grid(i, j)) {
+    d.nz1 = q; d.nz0 = q;
+    d.A = A; d.B = B; d.C = C;
+    d.bias = bias; d.pre_act = pre; d.gelu_grad_of = gg; d.residual = res;
+  } else {
+    d.nz1 = 1; d.nz0 = 1;
+    d.A = off(A, i * d.sA1 + j * d.sA0, es);
+    d.B = off(B, i * d.sB1 + j * d.sB0, es);
+    const long long co = i * d.sC1 + j * d.sC0;
+    d.C = off(C, co, ces);
+    d.bias = bias ? bias + (long long)j * Nb : nullptr;
+    d.pre_act = off(pre, co, es);
+    d.gelu_grad_of = off(gg, co, es);
+    d.residual = off(res, co, es);
+  }
+  return d;
+}
+
+int run_summa(int form, const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N, int q, int i, int j, int dtype,
+              const optimus_epilogue* epi, void* ws, size_t ws_bytes, void* stream) {
+  if (!A || !B || !C) return OPTIMUS_EINVAL;
+  if (form < 0 || form > 2) return OPTIMUS_EINVAL;
+  if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  int rc = check_mkn(M, K, N, q);
+  if (rc) return rc;
+  rc = check_coords(q, i, j);
+  if (rc) return rc;
+  if (epi && (epi->act < 0 || epi->act > 1)) return OPTIMUS_EINVAL;
+  GemmDesc d = summa_desc(form, A, B, C, M, K, N, q, i, j, dtype, epi);
+  if (gemm_mfma_supported(d)) {
+    int s = gemm_pick_splits(d);
+    if (s > 1 && ws && ws_bytes >= gemm_partials_bytes(d, s)) {
+      d.splits = s;
+      d.partials = (float*)ws;
+    }
+  }
+  return launch_gemm(d, as_stream(stream));
+}
+
+struct AttnDims {
+  int nb, nh, d, s, ld, ldo;
+  long long blk_qkv, blk_attn, blk_probs, nmat;
+};
+int attn_dims(int b, int s, int h, int n, int q, AttnDims* a) {
+  if (q <= 0 || b <= 0 || s <= 0 || h <= 0 || n <= 0) return OPTIMUS_ESHAPE;
+  if (b % q || n % q || h % n) return OPTIMUS_ESHAPE;
+  a->nb = b / q; a->nh = n / q; a->d = h / n; a->s = s;
+  if (a->d % 8 || s % 8 || s > 4096) return OPTIMUS_ESHAPE;
+  a->ld = 3 * h / q; a->ldo = h / q;
+  a->blk_qkv = (long long)a->nb * s * a->ld;
+  a->blk_attn = (long long)a->nb * s * a->ldo;
+  a->nmat = (long long)a->nb * a->nh;
+  a->blk_probs = a->nmat * s * s;
+  return OPTIMUS_OK;
+}
+size_t attn_ws_bytes(const AttnDims& a) {
+  return align256((size_t)a.blk_probs * 4) + align256((size_t)a.blk_probs * 2);
+}
+
+GemmDesc attn_base_desc(const AttnDims& a) {
+  GemmDesc d = {};
+  d.dtype = OPTIMUS_BF16; d.nl = 1; d.nz1 = a.nb; d.nz0 = a.nh; d.alpha = 1.0f; d.splits = 1;
+  return d;
+}
+
+int attention_fwd_device(const bf16_t* qkv_blk, bf16_t* probs_blk, bf16_t* attn_blk, const AttnDims& a, int causal, void* ws,
+                         hipStream_t st) {
+  float* scores = (float*)ws;
+  const long long ss = (long long)a.s * a.s;
+  const float scale = 1.0f / sqrtf((float)a.d);
+  // S = Q K^T / sqrt(d)
+  GemmDesc g = attn_base_desc(a);
+  g.A = qkv_blk; g.B = qkv_blk + a.d; g.C = scores;
+  g.Mb = a.s; g.Nb = a.s; g.Kp = a.d;
+  g.a_kcontig = 1; g.b_kcontig = 1; g.lda = a.ld; g.ldb = a.ld; g.ldc = a.s;
+  g.sA1 = (long long)a.s * a.ld; g.sA0 = 3 * a.d; g.sB1 = g.sA1; g.sB0 = g.sA0;
+  g.sC1 = a.nh * ss; g.sC0 = ss;
+  g.alpha = scale; g.out_fp32 = 1; g.skip_upper = causal;
+  int rc = launch_gemm(g, st);
+  if (rc) return rc;
+  rc = launch_softmax_fwd(scores, probs_blk, (int)a.nmat, a.s, causal, st);
+  if (rc) return rc;
+  // O = P V
+  GemmDesc o = attn_base_desc(a);
+  o.A = probs_blk; o.B = qkv_blk + 2 * a.d; o.C = attn_blk;
+  o.Mb = a.s; o.Nb = a.d; o.Kp = a.s;
+  o.a_kcontig = 1; o.b_kcontig = 0; o.lda = a.s; o.ldb = a.ld; o.ldc = a.ldo;
+  o.sA1 = a.nh * ss; o.sA0 = ss; o.sB1 = (long long)a.s * a.ld; o.sB0 = 3 * a.d;
+  o.sC1 = (long long)a.s * a.ldo; o.sC0 = a.d;
+  o.k_hi_diag = causal;
+  return launch_gemm(o, st);
+}
+
+int attention_bwd_device(const bf16_t* qkv_blk, const bf16_t* probs_blk, const bf16_t* dattn_blk, bf16_t* dqkv_blk,
+                         const AttnDims& a, int causal, void* ws, hipStream_t st) {
+  float* dP = (float*)ws;
+  bf16_t* dS = (bf16_t*)((char*)ws + align256((size_t)a.blk_probs * 4));
+  const long long ss = (long long)a.s * a.s;
+  const float scale = 1.0f / sqrtf((float)a.d);
+  const long long q1 = (long long)a.s * a.ld, q0 = 3 * a.d;      // (sequence, head) strides inside a qkv block
+  const long long o1 = (long long)a.s * a.ldo, o0 = a.d;         // inside an attn block
+  const long long p1 = a.nh * ss, p0 = ss;                       // inside probs / scratch
+  int rc;
+  {  // dV = P^T dO   (contraction over query position t >= key position u)
+    GemmDesc g = attn_base_desc(a);
+    g.A = probs_blk; g.B = dattn_blk; g.C = dqkv_blk + 2 * a.d;
+    g.Mb = a.s; g.Nb = a.d; g.Kp = a.s;
+    g.a_kcontig = 0; g.b_kcontig = 0; g.lda = a.s; g.ldb = a.ldo; g.ldc = a.ld;
+    g.sA1 = p1; g.sA0 = p0; g.sB1 = o1; g.sB0 = o0; g.sC1 = q1; g.sC0 = q0;
+    g.k_lo_diag = causal;
+    if ((rc = launch_gemm(g, st))) return rc;
+  }
+  {  // dP = dO V^T
+    GemmDesc g = attn_base_desc(a);
+    g.A = dattn_blk; g.B = qkv_blk + 2 * a.d; g.C = dP;
+    g.Mb = a.s; g.Nb = a.s; g.Kp = a.d;
+    g.a_kcontig = 1; g.b_kcontig = 1; g.lda = a.ldo; g.ldb = a.ld; g.ldc = a.s;
+    g.sA1 = o1; g.sA0 = o0; g.sB1 = q1; g.sB0 = q0; g.sC1 = p1; g.sC0 = p0;
+    g.out_fp32 = 1; g.skip_upper = causal;
+    if ((rc = launch_gemm(g, st))) return rc;
+  }
+  if ((rc = launch_softmax_bwd(dP, probs_blk, dS, (int)a.nmat, a.s, causal, st))) return rc;
+  {  // dQ = dS K / sqrt(d)
+    GemmDesc g = attn_base_desc(a);
+    g.A = dS; g.B = qkv_blk + a.d; g.C = dqkv_blk;
+    g.Mb = a.s; g.Nb = a.d; g.Kp = a.s;
+    g.a_kcontig = 1; g.b_kcontig = 0; g.lda = a.s; g.ldb = a.ld; g.ldc = a.ld;
+    g.sA1 = p1; g.sA0 = p0; g.sB1 = q1; g.sB0 = q0; g.sC1 = q1; g.sC0 = q0;
+    g.alpha = scale; g.k_hi_diag = causal;
+    if ((rc = launch_gemm(g, st))) return rc;
+  }
+  {  // dK = dS^T Q / sqrt(d)
+    GemmDesc g = attn_base_desc(a);
+    g.A = dS; g.B = qkv_blk; g.C = dqkv_blk + a.d;
+    g.Mb = a.s; g.Nb = a.d; g.Kp = a.s;
+    g.a_kcontig = 0; g.b_kcontig = 0; g.lda = a.s; g.ldb = a.ld; g.ldc = a.ld;
+    g.sA1 = p1; g.sA0 = p0; g.sB1 = q1; g.sB0 = q0; g.sC1 = q1; g.sC0 = q0;
+    g.alpha = scale; g.k_lo_diag = causal;
+    if ((rc = launch_gemm(g, st))) return rc;
+  }
+  return OPTIMUS_OK;
+}
+
+int run_attention(bool bwd, const void* qkv, const void* probs_in, void* probs_out, const void* d_attn, void* out, int b, int s,
+                  int h, int n, int q, int i, int j, int causal, int dtype, void* ws, size_t ws_bytes, void* stream) {
+  if (dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  AttnDims a;
+  int rc = attn_dims(b, s, h, n, q, &a);
+  if (rc) return rc;
+  if ((rc = check_coords(q, i, j))) return rc;
+  if (!ws || ws_bytes < attn_ws_bytes(a)) return OPTIMUS_EWORKSPACE;
+  const int i0 = is_grid(i, j) ? 0 : i, i1 = is_grid(i, j) ? q : i + 1;
+  const int j0 = is_grid(i, j) ? 0 : j, j1 = is_grid(i, j) ? q : j + 1;
+  for (int di = i0; di < i1; ++di)
+    for (int dj = j0; dj < j1; ++dj) {
+      const long long dev = (long long)di * q + dj;
+      const bf16_t* qb = (const bf16_t*)qkv + dev * a.blk_qkv;
+      if (!bwd)
+        rc = attention_fwd_device(qb, (bf16_t*)probs_out + dev * a.blk_probs, (bf16_t*)out + dev * a.blk_attn, a, causal, ws,
+                                  as_stream(stream));
+      else
+        rc = attention_bwd_device(qb, (const bf16_t*)probs_in + dev * a.blk_probs, (const bf16_t*)d_attn + dev * a.blk_attn,
+                                  (bf16_t*)out + dev * a.blk_qkv, a, causal, ws, as_stream(stream));
+      if (rc) return rc;
+    }
+  return OPTIMUS_OK;
+}
+
+int ln_desc(int64_t M, int64_t H, int q, int i, int j, int dtype, float eps, LnDesc* d) {
+  if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  if (q <= 0 || M <= 0 || H <= 0 || M % q || H % q) return OPTIMUS_ESHAPE;
+  if (M / q > 0x7fffffff / 4 || H > 0x7fffffff) return OPTIMUS_ESHAPE;
+  int rc = check_coords(q, i, j);
+  if (rc) return rc;
+  d->rows = (int)(M / q); d->cols = (int)(H / q); d->H = (int)H; d->q = q; d->dtype = dtype; d->eps = eps;
+  if (is_grid(i, j)) { d->i0 = 0; d->ni = q; d->j0 = 0; d->nj = q; }
+  else { d->i0 = i; d->ni = 1; d->j0 = j; d->nj = 1; }
+  return OPTIMUS_OK;
+}
+
+int ln_forward(const void* X, const float* gamma, const float* beta, void* Y, void* xhat, float* rstd, float* stats,
+               const LnDesc& d, bool grid, hipStream_t st) {
+  if (grid) {
+    int rc = launch_ln_stats(X, stats, d, st);
+    if (rc) return rc;
+    return launch_ln_apply(X, gamma, beta, Y, xhat, rstd, stats, d, true, st);
+  }
+  return launch_ln_apply(X, gamma, beta, Y, xhat, rstd, stats, d, false, st);
+}
+int ln_backward(const void* dY, const void* xhat, const float* rstd, const float* gamma, const void* dres, void* dX,
+                float* dgamma_part, float* dbeta_part, float* stats, const LnDesc& d, bool grid, hipStream_t st) {
+  int rc;
+  if (grid) {
+    if ((rc = launch_ln_bwd_stats(dY, xhat, gamma, stats, d, st))) return rc;
+    rc = launch_ln_bwd_apply(dY, xhat, rstd, gamma, dres, dX, stats, d, true, st);
+  } else {
+    rc = launch_ln_bwd_apply(dY, xhat, rstd, gamma, dres, dX, stats, d, false, st);
+  }
+  if (rc) return rc;
+  if (dgamma_part && dbeta_part) rc = launch_ln_param_grads(dY, xhat, dgamma_part, dbeta_part, d, st);
+  return rc;
+}
+
+int layer_check(const optimus_layer_cfg* c, int i, int j, AttnDims* a) {
+  if (!c) return OPTIMUS_EINVAL;
+  if (c->dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  int rc = attn_dims(c->b, c->s, c->h, c->n, c->q, a);
+  if (rc) return rc;
+  if (c->h % c->q) return OPTIMUS_ESHAPE;
+  if ((long long)c->b * c->s > 0x7fffffffLL) return OPTIMUS_ESHAPE;
+  return check_coords(c->q, i, j);
+}
+
+struct LayerGemm { int form; int64_t M, K, N; };
+// the twelve SUMMA products of a layer (forward 4, backward 8), logical output shapes
+void layer_gemms(const optimus_layer_cfg* c, LayerGemm out[12]) {
+  const int64_t M = (int64_t)c->b * c->s, h = c->h;
+  out[0] = {OPTIMUS_FORM_AB, M, h, 3 * h};      // qkv
+  out[1] = {OPTIMUS_FORM_AB, M, h, h};          // dense
+  out[2] = {OPTIMUS_FORM_AB, M, h, 4 * h};      // h -> 4h
+  out[3] = {OPTIMUS_FORM_AB, M, 4 * h, h};      // 4h -> h
+  out[4] = {OPTIMUS_FORM_ABT, M, h, 4 * h};     // d_gelu = d_out W2^T
+  out[5] = {OPTIMUS_FORM_ATB, 4 * h, M, h};     // dW2 = gelu^T d_out
+  out[6] = {OPTIMUS_FORM_ABT, M, 4 * h, h};     // d_ln2_out = d_pre W1^T
+  out[7] = {OPTIMUS_FORM_ATB, h, M, 4 * h};     // dW1 = ln2_out^T d_pre
+  out[8] = {OPTIMUS_FORM_ABT, M, h, h};         // d_attn = d_h_mid Wo^T
+  out[9] = {OPTIMUS_FORM_ATB, h, M, h};         // dWo = attn^T d_h_mid
+  out[10] = {OPTIMUS_FORM_ABT, M, 3 * h, h};    // d_ln1_out = d_qkv Wqkv^T
+  out[11] = {OPTIMUS_FORM_ATB, h, M, 3 * h};    // dWqkv = ln1_out^T d_qkv
+}
+
+size_t layer_gemm_ws(const optimus_layer_cfg* c) {
+  LayerGemm g[12];
+  layer_gemms(c, g);
+  size_t mx = 0;
+  for (int k = 0; k < 12; ++k)
+    for (int grid = 0; grid < 2; ++grid) {
+      size_t b = optimus_summa_workspace_bytes(g[k].form, g[k].M, g[k].K, g[k].N, c->q, grid ? -1 : 0, grid ? -1 : 0, c->dtype);
+      if (b > mx) mx = b;
+    }
+  return align256(mx);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* optimus_error_string(int code) {
+  switch (code) {
+    case OPTIMUS_OK: return "ok";
+    case OPTIMUS_EINVAL: return "invalid argument (null pointer or bad enum)";
+    case OPTIMUS_ESHAPE: return "bad shape (non-positive, not divisible by the grid, or beyond a documented limit)";
+    case OPTIMUS_ECOORD: return "device coordinates outside the q x q grid";
+    case OPTIMUS_EDTYPE: return "dtype not supported by this entry point";
+    case OPTIMUS_EWORKSPACE: return "workspace missing or too small";
+    case OPTIMUS_EHIP: return "HIP runtime error at launch";
+    default: return "unknown error code";
+  }
+}
+
+int optimus_abi_version(void) { return 1; }
+
+int optimus_pack_blocks(const void* src, void* dst, int64_t R, int64_t C, int q, int elem_bytes, void* stream) {
+  if (!src || !dst || src == dst) return OPTIMUS_EINVAL;
+  if (elem_bytes != 2 && elem_bytes != 4) return OPTIMUS_EDTYPE;
+  if (q <= 0 || R <= 0 || C <= 0 || R % q || C % q) return OPTIMUS_ESHAPE;
+  return launch_pack(src, dst, R, C, q, elem_bytes, false, as_stream(stream));
+}
+int optimus_unpack_blocks(const void* src, void* dst, int64_t R, int64_t C, int q, int elem_bytes, void* stream) {
+  if (!src || !dst || src == dst) return OPTIMUS_EINVAL;
+  if (elem_bytes != 2 && elem_bytes != 4) return OPTIMUS_EDTYPE;
+  if (q <= 0 || R <= 0 || C <= 0 || R % q || C % q) return OPTIMUS_ESHAPE;
+  return launch_pack(src, dst, R, C, q, elem_bytes, true, as_stream(stream));
+}
+
+int optimus_summa_ab(const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N, int q, int i, int j, int dtype,
+                     void* ws, size_t ws_bytes, void* stream) {
+  return run_summa(OPTIMUS_FORM_AB, A, B, C, M, K, N, q, i, j, dtype, nullptr, ws, ws_bytes, stream);
+}
+int optimus_summa_abt(const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N, int q, int i, int j, int dtype,
+                      void* ws, size_t ws_bytes, void* stream) {
+  return run_summa(OPTIMUS_FORM_ABT, A, B, C, M, K, N, q, i, j, dtype, nullptr, ws, ws_bytes, stream);
+}
+int optimus_summa_atb(const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N, int q, int i, int j, int dtype,
+                      void* ws, size_t ws_bytes, void* stream) {
+  return run_summa(OPTIMUS_FORM_ATB, A, B, C, M, K, N, q, i, j, dtype, nullptr, ws, ws_bytes, stream);
+}
+int optimus_summa_ex(int form, const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N, int q, int i, int j,
+                     int dtype, const optimus_epilogue* epi, void* ws, size_t ws_bytes, void* stream) {
+  return run_summa(form, A, B, C, M, K, N, q, i, j, dtype, epi, ws, ws_bytes, stream);
+}
+
+size_t optimus_summa_workspace_bytes(int form, int64_t M, int64_t K, int64_t N, int q, int i, int j, int dtype) {
+  if (form < 0 || form > 2 || check_mkn(M, K, N, q) || check_coords(q, i, j)) return 0;
+  if (dtype != OPTIMUS_BF16) return 0;
+  // pointers only matter for alignment checks; use an aligned dummy
+  GemmDesc d = summa_desc(form, (const void*)256, (const void*)256, (void*)256, M, K, N, q, i, j, dtype, nullptr);
+  if (!gemm_mfma_supported(d)) return 0;
+  int s = gemm_pick_splits(d);
+  return gemm_partials_bytes(d, s);
+}
+
+int optimus_bias_grad(const void* dY, float* dbias_part, int64_t M, int64_t N, int q, int i, int j, int dtype, void* stream) {
+  if (!dY || !dbias_part) return OPTIMUS_EINVAL;
+  if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  if (q <= 0 || M <= 0 || N <= 0 || M % q || N % q || M / q > 0x7fffffff || N / q > 0x7fffffff) return OPTIMUS_ESHAPE;
+  int rc = check_coords(q, i, j);
+  if (rc) return rc;
+  const int rows = (int)(M / q), cols = (int)(N / q);
+  const long long blk = (long long)rows * cols;
+  if (is_grid(i, j)) return launch_colsum(dY, dbias_part, rows, cols, cols, q * q, blk, cols, dtype, as_stream(stream));
+  const long long dev = (long long)i * q + j;
+  return launch_colsum(off(dY, dev * blk, esize(dtype)), dbias_part + dev * cols, rows, cols, cols, 1, blk, cols, dtype,
+                       as_stream(stream));
+}
+
+int optimus_layernorm2d_stats(const void* X, float* stats, int64_t M, int64_t H, int q, int i, int l, int dtype, void* stream) {
+  if (!X || !stats) return OPTIMUS_EINVAL;
+  LnDesc d;
+  int rc = ln_desc(M, H, q, i, l, dtype, 0.f, &d);
+  if (rc) return rc;
+  return launch_ln_stats(X, stats, d, as_stream(stream));
+}
+int optimus_layernorm2d(const void* X, const float* gamma, const float* beta, void* Y, void* xhat, float* rstd, float* stats,
+                        int64_t M, int64_t H, int q, int i, int j, float eps, int dtype, void* stream) {
+  if (!X || !gamma || !beta || !Y || !xhat || !rstd || !stats) return OPTIMUS_EINVAL;
+  if (!(eps >= 0.f)) return OPTIMUS_EINVAL;
+  LnDesc d;
+  int rc = ln_desc(M, H, q, i, j, dtype, eps, &d);
+  if (rc) return rc;
+  return ln_forward(X, gamma, beta, Y, xhat, rstd, stats, d, is_grid(i, j), as_stream(stream));
+}
+int optimus_layernorm2d_bwd_stats(const void* dY, const void* xhat, const float* gamma, float* stats, int64_t M, int64_t H, int q,
+                                  int i, int l, int dtype, void* stream) {
+  if (!dY || !xhat || !gamma || !stats) return OPTIMUS_EINVAL;
+  LnDesc d;
+  int rc = ln_desc(M, H, q, i, l, dtype, 0.f, &d);
+  if (rc) return rc;
+  return launch_ln_bwd_stats(dY, xhat, gamma, stats, d, as_stream(stream));
+}
+int optimus_layernorm2d_bwd(const void* dY, const void* xhat, const float* rstd, const float* gamma, const void* dres, void* dX,
+                            float* dgamma_part, float* dbeta_part, float* stats, int64_t M, int64_t H, int q, int i, int j,
+                            int dtype, void* stream) {
+  if (!dY || !xhat || !rstd || !gamma || !dX || !stats) return OPTIMUS_EINVAL;
+  if ((dgamma_part == nullptr) != (dbeta_part == nullptr)) return OPTIMUS_EINVAL;
+  LnDesc d;
+  int rc = ln_desc(M, H, q, i, j, dtype, 0.f, &d);
+  if (rc) return rc;
+  return ln_backward(dY, xhat, rstd, gamma, dres, dX, dgamma_part, dbeta_part, stats, d, is_grid(i, j), as_stream(stream));
+}
+
+size_t optimus_attention_workspace_bytes(int b, int s, int h, int n, int q) {
+  AttnDims a;
+  if (attn_dims(b, s, h, n, q, &a)) return 0;
+  return attn_ws_bytes(a);
+}
+int optimus_attention_fwd(const void* qkv, void* probs, void* attn, int b, int s, int h, int n, int q, int i, int j, int causal,
+                          int dtype, void* ws, size_t ws_bytes, void* stream) {
+  if (!qkv || !probs || !attn) return OPTIMUS_EINVAL;
+  return run_attention(false, qkv, nullptr, probs, nullptr, attn, b, s, h, n, q, i, j, causal ? 1 : 0, dtype, ws, ws_bytes, stream);
+}
+int optimus_attention_bwd(const void* qkv, const void* probs, const void* d_attn, void* d_qkv, int b, int s, int h, int n, int q,
+                          int i, int j, int causal, int dtype, void* ws, size_t ws_bytes, void* stream) {
+  if (!qkv || !probs || !d_attn || !d_qkv) return OPTIMUS_EINVAL;
+  return run_attention(true, qkv, probs, nullptr, d_attn, d_qkv, b, s, h, n, q, i, j, causal ? 1 : 0, dtype, ws, ws_bytes, stream);
+}
+
+size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg) {
+  AttnDims a;
+  if (layer_check(cfg, 0, 0, &a)) return 0;
+  return attn_ws_bytes(a) + layer_gemm_ws(cfg);
+}
+
+int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
+                      void* stream) {
+  AttnDims a;
+  int rc = layer_check(c, i, j, &a);
+  if (rc) return rc;
+  if (!t) return OPTIMUS_EINVAL;
+  if (!t->x || !t->ln1_g || !t->ln1_b || !t->w_qkv || !t->b_qkv || !t->w_o || !t->b_o || !t->ln2_g || !t->ln2_b || !t->w1 ||
+      !t->b1 || !t->w2 || !t->b2 || !t->ln1_out || !t->xhat1 || !t->rstd1 || !t->stats1 || !t->qkv || !t->probs || !t->attn ||
+      !t->h_mid || !t->ln2_out || !t->xhat2 || !t->rstd2 || !t->stats2 || !t->pre_gelu || !t->gelu || !t->out)
+    return OPTIMUS_EINVAL;
+  if (!ws || ws_bytes < optimus_layer_workspace_bytes(c)) return OPTIMUS_EWORKSPACE;
+  const int q = c->q, dt = c->dtype;
+  const int64_t M = (int64_t)c->b * c->s, h = c->h;
+  const bool grid = is_grid(i, j);
+  hipStream_t st = as_stream(stream);
+  void* attn_ws = ws;
+  const size_t attn_bytes = attn_ws_bytes(a);
+  void* gemm_ws = (char*)ws + attn_bytes;
+  const size_t gemm_bytes = ws_bytes - attn_bytes;
+  LnDesc ln;
+  if ((rc = ln_desc(M, h, q, i, j, dt, c->eps, &ln))) return rc;
+  // a1 = LN1(x)
+  if ((rc = ln_forward(t->x, t->ln1_g, t->ln1_b, t->ln1_out, t->xhat1, t->rstd1, t->stats1, ln, grid, st))) return rc;
+  // qkv = a1 Wqkv + b
+  optimus_epilogue e = {};
+  e.bias = t->b_qkv;
+  if ((rc = run_summa(OPTIMUS_FORM_AB, t->ln1_out, t->w_qkv, t->qkv, M, h, 3 * h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream))) return rc;
+  // local attention
+  if ((rc = run_attention(false, t->qkv, nullptr, t->probs, nullptr, t->attn, c->b, c->s, c->h, c->n, q, i, j, c->causal ? 1 : 0, dt,
+                          attn_ws, attn_bytes, stream)))
+    return rc;
+  // h_mid = x + attn Wo + b
+  e = {};
+  e.bias = t->b_o; e.residual = t->x;
+  if ((rc = run_summa(OPTIMUS_FORM_AB, t->attn, t->w_o, t->h_mid, M, h, h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream))) return rc;
+  // a2 = LN2(h_mid)
+  if ((rc = ln_forward(t->h_mid, t->ln2_g, t->ln2_b, t->ln2_out, t->xhat2, t->rstd2, t->stats2, ln, grid, st))) return rc;
+  // pre = a2 W1 + b ; g = GeLU(pre)
+  e = {};
+  e.bias = t->b1; e.pre_act = t->pre_gelu; e.act = 1;
+  if ((rc = run_summa(OPTIMUS_FORM_AB, t->ln2_out, t->w1, t->gelu, M, h, 4 * h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream))) return rc;
+  // out = h_mid + g W2 + b
+  e = {};
+  e.bias = t->b2; e.residual = t->h_mid;
+  return run_summa(OPTIMUS_FORM_AB, t->gelu, t->w2, t->out, M, 4 * h, h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream);
+}
+
+int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
+                      void* stream) {
+  AttnDims a;
+  int rc = layer_check(c, i, j, &a);
+  if (rc) return rc;
+  if (!t) return OPTIMUS_EINVAL;
+  if (!t->x || !t->ln1_g || !t->w_qkv || !t->w_o || !t->ln2_g || !t->w1 || !t->w2 || !t->ln1_out || !t->xhat1 || !t->rstd1 ||
+      !t->qkv || !t->probs || !t->attn || !t->ln2_out || !t->xhat2 || !t->rstd2 || !t->pre_gelu || !t->gelu || !t->d_out ||
+      !t->d_pre_gelu || !t->d_ln2_out || !t->d_h_mid || !t->d_attn || !t->d_qkv || !t->d_ln1_out || !t->d_x || !t->bstats1 ||
+      !t->bstats2 || !t->d_w_qkv || !t->d_w_o || !t->d_w1 || !t->d_w2 || !t->d_b_qkv || !t->d_b_o || !t->d_b1 || !t->d_b2 ||
+      !t->d_ln1_g || !t->d_ln1_b || !t->d_ln2_g || !t->d_ln2_b)
+    return OPTIMUS_EINVAL;
+  if (!ws || ws_bytes < optimus_layer_workspace_bytes(c)) return OPTIMUS_EWORKSPACE;
+  const int q = c->q, dt = c->dtype;
+  const int64_t M = (int64_t)c->b * c->s, h = c->h;
+  const bool grid = is_grid(i, j);
+  hipStream_t st = as_stream(stream);
+  void* attn_ws = ws;
+  const size_t attn_bytes = attn_ws_bytes(a);
+  void* gemm_ws = (char*)ws + attn_bytes;
+  const size_t gemm_bytes = ws_bytes - attn_bytes;
+  LnDesc ln;
+  if ((rc = ln_desc(M, h, q, i, j, dt, c->eps, &ln))) return rc;
+  optimus_epilogue e = {};
+  optimus_epilogue e32 = {};
+  e32.out_fp32 = 1;
+#define RUN(...) if ((rc = (__VA_ARGS__))) return rc
+  // ---- out = h_mid + gelu W2 + b2 ----
+  e = {}; e.gelu_grad_of = t->pre_gelu;  // d_pre = (d_out W2^T) * GeLU'(pre)
+  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_out, t->w2, t->d_pre_gelu, M, h, 4 * h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->gelu, t->d_out, t->d_w2, 4 * h, M, h, q, i, j, dt, &e32, gemm_ws, gemm_bytes, stream));
+  RUN(optimus_bias_grad(t->d_out, t->d_b2, M, h, q, i, j, dt, stream));
+  // ---- pre = ln2_out W1 + b1 ----
+  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_pre_gelu, t->w1, t->d_ln2_out, M, 4 * h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln2_out, t->d_pre_gelu, t->d_w1, h, M, 4 * h, q, i, j, dt, &e32, gemm_ws, gemm_bytes, stream));
+  RUN(optimus_bias_grad(t->d_pre_gelu, t->d_b1, M, 4 * h, q, i, j, dt, stream));
+  // ---- LN2 backward, plus the residual branch: d_h_mid = d_out + LN2'(d_ln2_out) ----
+  RUN(ln_backward(t->d_ln2_out, t->xhat2, t->rstd2, t->ln2_g, t->d_out, t->d_h_mid, t->d_ln2_g, t->d_ln2_b, t->bstats2, ln, grid, st));
+  // ---- h_mid = x + attn Wo + bo ----
+  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_h_mid, t->w_o, t->d_attn, M, h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->attn, t->d_h_mid, t->d_w_o, h, M, h, q, i, j, dt, &e32, gemm_ws, gemm_bytes, stream));
+  RUN(optimus_bias_grad(t->d_h_mid, t->d_b_o, M, h, q, i, j, dt, stream));
+  // ---- local attention backward ----
+  RUN(run_attention(true, t->qkv, t->probs, nullptr, t->d_attn, t->d_qkv, c->b, c->s, c->h, c->n, q, i, j, c->causal ? 1 : 0, dt,
+                    attn_ws, attn_bytes, stream));
+  // ---- qkv = ln1_out Wqkv + b ----
+  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_qkv, t->w_qkv, t->d_ln1_out, M, 3 * h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln1_out, t->d_qkv, t->d_w_qkv, h, M, 3 * h, q, i, j, dt, &e32, gemm_ws, gemm_bytes, stream));
+  RUN(optimus_bias_grad(t->d_qkv, t->d_b_qkv, M, 3 * h, q, i, j, dt, stream));
+  // ---- LN1 backward, plus the residual branch: d_x = d_h_mid + LN1'(d_ln1_out) ----
+  RUN(ln_backward(t->d_ln1_out, t->xhat1, t->rstd1, t->ln1_g, t->d_h_mid, t->d_x, t->d_ln1_g, t->d_ln1_b, t->bstats1, ln, grid, st));
+#undef RUN
+  return OPTIMUS_OK;
+}
+
+int64_t optimus_gemm_flops(int64_t M, int64_t K, int64_t N, int q) {
+  if (check_mkn(M, K, N, q)) return -1;
+  return 2 * (M / q) * K * (N / q);
+}
+
+int64_t optimus_layer_flops(const optimus_layer_cfg* c, int what) {
+  AttnDims a;
+  if (layer_check(c, 0, 0, &a) || what < 0 || what > 1) return -1;
+  const int64_t b = c->b, s = c->s, h = c->h, p = (int64_t)c->q * c->q;
+  const int64_t fwd = 2 * (12 * b * s * h * h + 2 * b * s * s * h) / p;
+  return what == 0 ? fwd : 2 * fwd;
+}
+
+// ---- tuning hook used by the benchmark (not part of the method): force a matrix-core tile variant, -1 = automatic ----
+void optimus_debug_set_gemm_variant(int v) { gemm_set_variant(v); }
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Shared host/device declarations of the library's internals (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "optimus.h"
+
+namespace optimus {
+
+typedef unsigned short bf16_t;  // raw bf16 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ unsigned pack2_bf16(float lo, float hi) {
+  return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+}
+
+__device__ __forceinline__ float gelu_exact(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+__device__ __forceinline__ float gelu_grad_exact(float x) {
+  float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752440f));
+  float pdf = 0.39894228040143267794f * __expf(-0.5f * x * x);
+  return cdf + x * pdf;
+}
+
+// One (possibly batched, possibly multi-panel) product  C = alpha * sum_l op(A_l) op(B_l)  + epilogue.
+// All strides are in elements of the operand's own type.  A batch index z in [0, nz1*nz0) is split as
+// z1 = z / nz0, z0 = z % nz0; operand X of batch z starts at X + z1*sX1 + z0*sX0.
+struct GemmDesc {
+  const void* A;
+  const void* B;
+  void* C;
+  int Mb, Nb;   // output block dims
+  int Kp;       // contraction length of one panel
+  int nl;       // number of panels accumulated into one output
+  int lda, ldb, ldc;
+  long long sAl, sBl;  // panel strides
+  int nz0, nz1;
+  long long sA0, sA1, sB0, sB1, sC0, sC1;
+  int a_kcontig;  // 1: A panel stored [Mb][Kp] (k contiguous); 0: stored [Kp][Mb]
+  int b_kcontig;  // 1: B panel stored [Nb][Kp] (k contiguous); 0: stored [Kp][Nb]
+  int dtype;      // OPTIMUS_FP32 / OPTIMUS_BF16 (inputs, and outputs unless out_fp32)
+  // epilogue
+  float alpha;
+  const float* bias;  // fp32, indexed bias[z0*sBias0 + n]
+  long long sBias0;
+  void* pre_act;             // same layout as C (ldc, sC0, sC1), dtype of inputs
+  int act;                   // 1 = GeLU
+  const void* gelu_grad_of;  // same layout as C
+  const void* residual;      // same layout as C
+  int out_fp32;
+  // causal structure of attention products (square s x s score matrices, single panel)
+  int skip_upper;  // 1: output tiles entirely above the diagonal are not computed (left untouched)
+  int k_hi_diag;   // 1: contraction limited to k < (last row of the tile)+1
+  int k_lo_diag;   // 1: contraction starts at k >= first row of the tile
+  // split of the panel loop over several workgroups (fixed-order combine)
+  int splits;          // 1 = none
+  float* partials;     // workspace [splits][nz][Mb][Nb] fp32 when splits > 1
+};
+
+int launch_gemm(const GemmDesc& d, hipStream_t stream);           // picks MFMA or generic kernel
+int launch_gemm_generic(const GemmDesc& d, hipStream_t stream);    // scalar FMA kernel, any shape
+int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream);       // bf16 matrix-core kernel
+bool gemm_mfma_supported(const GemmDesc& d);
+int gemm_pick_splits(const GemmDesc& d);                           // heuristic; 1 when not worthwhile
+size_t gemm_partials_bytes(const GemmDesc& d, int splits);
+// force a specific kernel variant (benchmark sweeps); -1 = automatic
+void gemm_set_variant(int v);
+int gemm_get_variant();
+
+// element-wise / reduction kernels
+int launch_pack(const void* src, void* dst, long long R, long long C, int q, int elem_bytes, bool unpack,
+                hipStream_t stream);
+int launch_colsum(const void* X, float* out, int rows, int cols, int ld, int nz, long long sX, long long sOut,
+                  int dtype, hipStream_t stream);
+
+struct LnDesc {
+  int rows, cols;  // block dims M/q, H/q
+  int H;           // full hidden size
+  int q;
+  int i0, ni;      // grid rows handled: i0 .. i0+ni-1
+  int j0, nj;      // grid cols handled
+  int dtype;
+  float eps;
+};
+int launch_ln_stats(const void* X, float* stats, const LnDesc& d, hipStream_t stream);
+int launch_ln_apply(const void* X, const float* gamma, const float* beta, void* Y, void* xhat, float* rstd,
+                    float* stats, const LnDesc& d, bool own_stats_ready, hipStream_t stream);
+int launch_ln_bwd_stats(const void* dY, const void* xhat, const float* gamma, float* stats, const LnDesc& d,
+                        hipStream_t stream);
+int launch_ln_bwd_apply(const void* dY, const void* xhat, const float* rstd, const float* gamma, const void* dres,
+                        void* dX, float* stats, const LnDesc& d, bool own_stats_ready, hipStream_t stream);
+int launch_ln_param_grads(const void* dY, const void* xhat, float* dgamma_part, float* dbeta_part, const LnDesc& d,
+                          hipStream_t stream);
+
+// softmax over rows of nmat square [s x s] score matrices (fp32 in, bf16 out), optional causal mask
+int launch_softmax_fwd(const float* S, void* P, int nmat, int s, int causal, hipStream_t stream);
+// dS = P * (dP - rowsum(dP * P)); dP fp32, P bf16, dS bf16
+int launch_softmax_bwd(const float* dP, const void* P, void* dS, int nmat, int s, int causal, hipStream_t stream);
+
+inline int hip_launch_status() { return hipGetLastError() == hipSuccess ? OPTIMUS_OK : OPTIMUS_EHIP; }
+
+}  // namespace optimus

@@ -1,0 +1,300 @@
+// 2D LayerNorm (Section 3.2.2 of the paper): a row of the hidden dimension is spread over the q devices of a
+// grid row; each device sums x and x^2 over its own h/q columns, the q partials are added (the row
+// all-reduce), and the device normalises its own block.  Backward treats (sum xhat*g, sum g) the same way.
+//
+// One wavefront owns one row of a block: the row (<= 2048 columns on the fast path) is read once with
+// 16-byte loads, kept in registers, reduced with DPP-free shuffles, and written once.  Wider or unaligned
+// rows take a scalar path that re-reads the row.  Statistics are fp32; partials are always added in the
+// order l = 0..q-1 so that every device of a row, and grid and device mode, get identical bits.
+#include "common.hpp"
+
+namespace optimus {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+constexpr int LN_MAXCH = 4;  // 16-byte chunks per lane on the fast path (bf16: 8 elems, fp32: 4 elems)
+
+template <typename T> struct Vec;
+template <> struct Vec<bf16_t> {
+  static constexpr int N = 8;
+  __device__ static void load(const bf16_t* p, float* f) {
+    uint4 w = *(const uint4*)p;
+    unsigned u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { f[2 * k] = __uint_as_float(u[k] << 16); f[2 * k + 1] = __uint_as_float(u[k] & 0xffff0000u); }
+  }
+  __device__ static void store(bf16_t* p, const float* f) {
+    *(uint4*)p = make_uint4(pack2_bf16(f[0], f[1]), pack2_bf16(f[2], f[3]), pack2_bf16(f[4], f[5]), pack2_bf16(f[6], f[7]));
+  }
+  __device__ static float ld1(const bf16_t* p) { return bf16_to_f32(*p); }
+  __device__ static void st1(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  __device__ static void load(const float* p, float* f) { float4 w = *(const float4*)p; f[0] = w.x; f[1] = w.y; f[2] = w.z; f[3] = w.w; }
+  __device__ static void store(float* p, const float* f) { *(float4*)p = make_float4(f[0], f[1], f[2], f[3]); }
+  __device__ static float ld1(const float* p) { return *p; }
+  __device__ static void st1(float* p, float v) { *p = v; }
+};
+
+struct LnArgs {
+  int rows, cols, H, q;
+  int i0, ni, j0, nj;
+  float eps;
+  int vec;  // fast path allowed
+};
+
+// MODE 0: forward stats only.  MODE 1: forward apply (own partial computed here unless own_ready).
+// MODE 2: backward stats only. MODE 3: backward apply.
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void ln_kernel(const T* __restrict__ X, const T* __restrict__ X2, const float* __restrict__ gamma,
+                                                 const float* __restrict__ beta, const float* __restrict__ rstd_in,
+                                                 const T* __restrict__ dres, T* __restrict__ Y, T* __restrict__ xhat_out,
+                                                 float* __restrict__ rstd_out, float* __restrict__ stats, LnArgs a, int own_ready) {
+  constexpr int VN = Vec<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int dev = blockIdx.y;
+  const int di = a.i0 + dev / a.nj, dj = a.j0 + dev % a.nj;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= a.rows) return;
+  const long long blk = (long long)a.rows * a.cols;
+  const long long base = ((long long)di * a.q + dj) * blk + (long long)row * a.cols;
+  const T* x = X + base;                    // forward: x ; backward: dy
+  const T* x2 = X2 ? X2 + base : nullptr;   // backward: xhat
+  const float* gm = gamma ? gamma + (long long)dj * a.cols : nullptr;
+  const float* bt = beta ? beta + (long long)dj * a.cols : nullptr;
+  float* st_row = stats + ((long long)di * a.q * a.rows + row) * 2;  // + l*rows*2 selects device (di, l)
+  const long long st_dev = (long long)a.rows * 2;
+
+  float v[LN_MAXCH * VN];   // forward: x ; backward: g = dy*gamma
+  float w[LN_MAXCH * VN];   // backward: xhat
+  float s0 = 0.f, s1 = 0.f;
+  const bool need_own = !(own_ready && (MODE == 1 || MODE == 3));
+  if (a.vec) {
+#pragma unroll
+    for (int c = 0; c < LN_MAXCH; ++c) {
+      int col = (c * 64 + lane) * VN;
+      if (col < a.cols) {
+        Vec<T>::load(x + col, v + c * VN);
+        if (MODE >= 2) {
+          Vec<T>::load(x2 + col, w + c * VN);
+#pragma unroll
+          for (int k = 0; k < VN; ++k) { v[c * VN + k] *= gm[col + k]; s0 += w[c * VN + k] * v[c * VN + k]; s1 += v[c * VN + k]; }
+        } else {
+#pragma unroll
+          for (int k = 0; k < VN; ++k) { s0 += v[c * VN + k]; s1 += v[c * VN + k] * v[c * VN + k]; }
+        }
+      }
+    }
+  } else if (need_own) {
+    for (int col = lane; col < a.cols; col += 64) {
+      float t = Vec<T>::ld1(x + col);
+      if (MODE >= 2) { float g = t * gm[col]; s0 += Vec<T>::ld1(x2 + col) * g; s1 += g; }
+      else { s0 += t; s1 += t * t; }
+    }
+  }
+  float own0 = 0.f, own1 = 0.f;
+  if (need_own) {
+    own0 = wave_sum(s0);
+    own1 = wave_sum(s1);
+    if (lane == 0) { st_row[dj * st_dev] = own0; st_row[dj * st_dev + 1] = own1; }
+  }
+  if (MODE == 0 || MODE == 2) return;
+
+  // add the q partials of this grid row in fixed order (own partial from registers when computed here)
+  float t0 = 0.f, t1 = 0.f;
+  for (int l = 0; l < a.q; ++l) {
+    float p0, p1;
+    if (l == dj && need_own) { p0 = own0; p1 = own1; }
+    else { p0 = st_row[l * st_dev]; p1 = st_row[l * st_dev + 1]; }
+    t0 += p0; t1 += p1;
+  }
+  const float invH = 1.0f / (float)a.H;
+  if (MODE == 1) {
+    float mean = t0 * invH;
+    float var = fmaxf(t1 * invH - mean * mean, 0.f);
+    float rstd = 1.0f / sqrtf(var + a.eps);
+    if (lane == 0) rstd_out[((long long)di * a.q + dj) * a.rows + row] = rstd;
+    T* y = Y + base;
+    T* xh = xhat_out + base;
+    if (a.vec) {
+#pragma unroll
+      for (int c = 0; c < LN_MAXCH; ++c) {
+        int col = (c * 64 + lane) * VN;
+        if (col < a.cols) {
+          float o[VN], h[VN];
+#pragma unroll
+          for (int k = 0; k < VN; ++k) { h[k] = (v[c * VN + k] - mean) * rstd; o[k] = h[k] * gm[col + k] + bt[col + k]; }
+          Vec<T>::store(xh + col, h);
+          Vec<T>::store(y + col, o);
+        }
+      }
+    } else {
+      for (int col = lane; col < a.cols; col += 64) {
+        float h = (Vec<T>::ld1(x + col) - mean) * rstd;
+        Vec<T>::st1(xh + col, h);
+        Vec<T>::st1(y + col, h * gm[col] + bt[col]);
+      }
+    }
+  } else {  // MODE 3
+    float rstd = rstd_in[((long long)di * a.q + dj) * a.rows + row];
+    float mxg = t0 * invH, mg = t1 * invH;
+    T* dx = Y + base;
+    const T* dr = dres ? dres + base : nullptr;
+    if (a.vec) {
+#pragma unroll
+      for (int c = 0; c < LN_MAXCH; ++c) {
+        int col = (c * 64 + lane) * VN;
+        if (col < a.cols) {
+          float o[VN], r[VN];
+          if (dr) Vec<T>::load(dr + col, r);
+#pragma unroll
+          for (int k = 0; k < VN; ++k) {
+            o[k] = rstd * (v[c * VN + k] - w[c * VN + k] * mxg - mg);
+            if (dr) o[k] += r[k];
+          }
+          Vec<T>::store(dx + col, o);
+        }
+      }
+    } else {
+      for (int col = lane; col < a.cols; col += 64) {
+        float g = Vec<T>::ld1(x + col) * gm[col];
+        float o = rstd * (g - Vec<T>::ld1(x2 + col) * mxg - mg);
+        if (dr) o += Vec<T>::ld1(dr + col);
+        Vec<T>::st1(dx + col, o);
+      }
+    }
+  }
+}
+
+static LnArgs make_args(const LnDesc& d, bool ptr_ok, int elem_bytes) {
+  LnArgs a;
+  a.rows = d.rows; a.cols = d.cols; a.H = d.H; a.q = d.q;
+  a.i0 = d.i0; a.ni = d.ni; a.j0 = d.j0; a.nj = d.nj;
+  a.eps = d.eps;
+  int vn = 16 / elem_bytes;
+  a.vec = ptr_ok && (d.cols % vn == 0) && (d.cols <= LN_MAXCH * 64 * vn);
+  return a;
+}
+static bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+template <typename T, int MODE>
+static int run(const void* X, const void* X2, const float* gamma, const float* beta, const float* rstd_in, const void* dres,
+               void* Y, void* xhat, float* rstd_out, float* stats, const LnDesc& d, bool own_ready, hipStream_t stream) {
+  bool ok = al16(X) && (!X2 || al16(X2)) && (!dres || al16(dres)) && (!Y || al16(Y)) && (!xhat || al16(xhat)) &&
+            (!gamma || al16(gamma)) && (!beta || al16(beta));
+  LnArgs a = make_args(d, ok, (int)sizeof(T));
+  dim3 grid((unsigned)((d.rows + 3) / 4), (unsigned)(d.ni * d.nj));
+  hipLaunchKernelGGL((ln_kernel<T, MODE>), grid, dim3(256), 0, stream, (const T*)X, (const T*)X2, gamma, beta, rstd_in,
+                     (const T*)dres, (T*)Y, (T*)xhat, rstd_out, stats, a, own_ready ? 1 : 0);
+  return hip_launch_status();
+}
+
+#define LN_DISPATCH(MODE, ...)                                              \
+  (d.dtype == OPTIMUS_BF16 ? run<bf16_t, MODE>(__VA_ARGS__) : run<float, MODE>(__VA_ARGS__))
+
+int launch_ln_stats(const void* X, float* stats, const LnDesc& d, hipStream_t stream) {
+  return LN_DISPATCH(0, X, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, stats, d, false, stream);
+}
+int launch_ln_apply(const void* X, const float* gamma, const float* beta, void* Y, void* xhat, float* rstd, float* stats,
+                    const LnDesc& d, bool own_ready, hipStream_t stream) {
+  return LN_DISPATCH(1, X, nullptr, gamma, beta, nullptr, nullptr, Y, xhat, rstd, stats, d, own_ready, stream);
+}
+int launch_ln_bwd_stats(const void* dY, const void* xhat, const float* gamma, float* stats, const LnDesc& d, hipStream_t stream) {
+  return LN_DISPATCH(2, dY, xhat, gamma, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, stats, d, false, stream);
+}
+int launch_ln_bwd_apply(const void* dY, const void* xhat, const float* rstd, const float* gamma, const void* dres, void* dX,
+                        float* stats, const LnDesc& d, bool own_ready, hipStream_t stream) {
+  return LN_DISPATCH(3, dY, xhat, gamma, nullptr, rstd, dres, dX, nullptr, nullptr, stats, d, own_ready, stream);
+}
+
+// ---- column sums over the rows of a block: dgamma/dbeta partials, bias gradients ----
+// Workgroup = 32 row lanes x 8 column lanes; each thread accumulates 8 adjacent columns (one 16-byte load per row
+// for bf16) over rows ty, ty+32, ...; the 32 row lanes are then added through LDS in fixed order.
+template <typename T, bool PROD>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, const T* __restrict__ W, float* __restrict__ out,
+                                                     float* __restrict__ out2, int rows, int cols, int ld, long long sX, long long sOut) {
+  __shared__ float red[32][65];
+  __shared__ float red2[32][65];
+  const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
+  const int c0 = blockIdx.x * 64 + tx * 8;
+  const long long zoff = (long long)blockIdx.y * sX;
+  float acc[8], acc2[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { acc[k] = 0.f; acc2[k] = 0.f; }
+  const bool vec = (ld % 8 == 0) && (sX % 8 == 0) && (c0 + 8 <= cols) && sizeof(T) == 2 && (((uintptr_t)X & 15) == 0) &&
+                   (!PROD || ((uintptr_t)W & 15) == 0);
+  for (int r = ty; r < rows; r += 32) {
+    const long long off = zoff + (long long)r * ld + c0;
+    float x[8], w[8];
+    if (vec) {
+      Vec<bf16_t>::load((const bf16_t*)X + off, x);
+      if (PROD) Vec<bf16_t>::load((const bf16_t*)W + off, w);
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        bool in = c0 + k < cols;
+        x[k] = in ? Vec<T>::ld1(X + off + k) : 0.f;
+        if (PROD) w[k] = in ? Vec<T>::ld1(W + off + k) : 0.f;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      acc[k] += x[k];                      // sum x           (dbeta / bias gradient)
+      if (PROD) acc2[k] += x[k] * w[k];    // sum x*w         (dgamma)
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { red[ty][tx * 8 + k] = acc[k]; if (PROD) red2[ty][tx * 8 + k] = acc2[k]; }
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    int c = blockIdx.x * 64 + threadIdx.x;
+    if (c < cols) {
+      float s = 0.f, s2 = 0.f;
+      for (int r = 0; r < 32; ++r) { s += red[r][threadIdx.x]; if (PROD) s2 += red2[r][threadIdx.x]; }
+      out[(long long)blockIdx.y * sOut + c] = s;
+      if (PROD) out2[(long long)blockIdx.y * sOut + c] = s2;
+    }
+  }
+}
+
+int launch_colsum(const void* X, float* out, int rows, int cols, int ld, int nz, long long sX, long long sOut, int dtype,
+                  hipStream_t stream) {
+  dim3 grid((unsigned)((cols + 63) / 64), (unsigned)nz);
+  if (dtype == OPTIMUS_BF16)
+    hipLaunchKernelGGL((colsum_kernel<bf16_t, false>), grid, dim3(256), 0, stream, (const bf16_t*)X, (const bf16_t*)nullptr, out,
+                       (float*)nullptr, rows, cols, ld, sX, sOut);
+  else
+    hipLaunchKernelGGL((colsum_kernel<float, false>), grid, dim3(256), 0, stream, (const float*)X, (const float*)nullptr, out,
+                       (float*)nullptr, rows, cols, ld, sX, sOut);
+  return hip_launch_status();
+}
+
+// dbeta_part = column sums of dy, dgamma_part = column sums of dy*xhat, for the blocks (i0.., j0..) of d
+int launch_ln_param_grads(const void* dY, const void* xhat, float* dgamma_part, float* dbeta_part, const LnDesc& d,
+                          hipStream_t stream) {
+  const long long blk = (long long)d.rows * d.cols;
+  int rc = OPTIMUS_OK;
+  for (int ii = 0; ii < d.ni && rc == OPTIMUS_OK; ++ii) {
+    // the nj blocks of one grid row are contiguous in block-major storage
+    const long long first = ((long long)(d.i0 + ii) * d.q + d.j0);
+    dim3 grid((unsigned)((d.cols + 63) / 64), (unsigned)d.nj);
+    if (d.dtype == OPTIMUS_BF16)
+      hipLaunchKernelGGL((colsum_kernel<bf16_t, true>), grid, dim3(256), 0, stream, (const bf16_t*)dY + first * blk,
+                         (const bf16_t*)xhat + first * blk, dbeta_part + first * d.cols, dgamma_part + first * d.cols, d.rows,
+                         d.cols, d.cols, blk, (long long)d.cols);
+    else
+      hipLaunchKernelGGL((colsum_kernel<float, true>), grid, dim3(256), 0, stream, (const float*)dY + first * blk,
+                         (const float*)xhat + first * blk, dbeta_part + first * d.cols, dgamma_part + first * d.cols, d.rows,
+                         d.cols, d.cols, blk, (long long)d.cols);
+    rc = hip_launch_status();
+  }
+  return rc;
+}
+
+}  // namespace optimus
