@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-device hot path (one MI355X).
+
+A step is one pass of the whole hot path for ONE device (i, j) of the q x q grid: optimus_layer_fwd followed
+by optimus_layer_bwd with explicit coordinates (block addressing, 2D LayerNorm, the twelve SUMMA products with
+their epilogues, local attention forward/backward, bias and affine gradients), the other q*q-1 devices' blocks
+being resident in HBM from one untimed grid-mode pass.  Inputs are already in HBM when the timed region starts.
+
+Reported: value = SUMMA-product flops of the step / step time (the step also contains every non-GEMM row, so
+this is a lower bound on kernel rate); roofline = the dominant SUMMA product alone, timed with HIP events on
+the launch stream; per-GEMM and per-config TFLOP/s and % of the 2.5 PFLOP/s dense bf16 MFMA peak; achieved
+GB/s of the LayerNorm and softmax kernels; and the CPU oracle timed on the host cores as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="config2", choices=["config2", "config4", "config5"])
+    ap.add_argument("--device-coords", default="1,2", help="device (i,j) whose share is timed")
+    ap.add_argument("--gemm-reps", type=int, default=30)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the per-config GEMM table")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+def event_time_ms(fn, reps, warm=3):
+    """Average duration of fn() over reps back-to-back calls, HIP events on the current (launch) stream."""
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def layer_gemm_list(b, s, h):
+    """The twelve SUMMA products of a layer: (name, form, M, K, N) with (M, N) the logical output shape."""
+    M = b * s
+    return [
+        ("qkv.ab", "ab", M, h, 3 * h), ("dense.ab", "ab", M, h, h), ("mlp_up.ab", "ab", M, h, 4 * h), ("mlp_down.ab", "ab", M, 4 * h, h),
+        ("mlp_down.abt", "abt", M, h, 4 * h), ("mlp_down.atb", "atb", 4 * h, M, h),
+        ("mlp_up.abt", "abt", M, 4 * h, h), ("mlp_up.atb", "atb", h, M, 4 * h),
+        ("dense.abt", "abt", M, h, h), ("dense.atb", "atb", h, M, h),
+        ("qkv.abt", "abt", M, 3 * h, h), ("qkv.atb", "atb", h, M, 3 * h),
+    ]
+
+
+def time_gemms(opt, torch, gemms, q, i, j, reps, seed):
+    """Time each product alone (device mode, workspace given, warm caches) on device-generated N(0,1)/N(0,0.02) data."""
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(seed)
+    rows = []
+    for (name, form, M, K, N) in gemms:
+        na = M * K
+        nb = K * N
+        A = torch.randn(na, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+        B = (torch.randn(nb, generator=gen, device="cuda:0", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+        C = torch.empty(M * N, device="cuda:0", dtype=torch.bfloat16)
+        nbytes = opt.summa_workspace_bytes(form, M, K, N, q, i, j, opt.BF16)
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
+        ms = event_time_ms(lambda: opt.summa(form, A, B, C, M, K, N, q, i, j, opt.BF16, ws=ws), reps)
+        fl = opt.gemm_flops(M, K, N, q)
+        tf = fl / (ms * 1e-3) / 1e12
+        rows.append({"name": name, "form": form, "block": [M // q, K, N // q], "panel": K // q, "us": round(ms * 1e3, 2),
+                     "tflops": round(tf, 1), "pct_peak": round(100 * tf / PEAK_BF16_TFLOPS, 1), "split_ws_bytes": int(nbytes)})
+        del A, B, C, ws
+    return rows
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the other q*q-1 devices' blocks are resident in HBM); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2104_05343_amd as opt
+    from paper_2104_05343_amd import harness
+    from workloads import CONFIGS, layer_inputs, bf16_bits
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfgd = CONFIGS[args.workload]
+    shp = cfgd["layer"]
+    b, s, h, n, q = shp.b, shp.s, shp.h, shp.n, shp.q
+    di, dj = (int(v) for v in args.device_coords.split(","))
+    di, dj = di % q, dj % q
+
+    # ---- workload: seeded synthetic inputs of the config's recipe, uploaded and packed block-major ----
+    inp = layer_inputs(cfgd["seed"], shp, "bf16")
+    bits = {k: bf16_bits(inp[k]) for k in ("x", "w_qkv", "w_o", "w1", "w2", "d_out")}
+    vecs = {k: inp[k] for k in ("ln1_g", "ln1_b", "b_qkv", "b_o", "ln2_g", "ln2_b", "b1", "b2")}
+    cfg, T, lt, ws = harness.alloc_layer(bits, vecs, b, s, h, n, q, causal=True)
+    # one untimed grid-mode pass leaves every peer block resident
+    opt.layer_fwd(cfg, lt, -1, -1, ws)
+    opt.layer_bwd(cfg, lt, -1, -1, ws)
+    torch.cuda.synchronize()
+
+    def step():
+        opt.layer_fwd(cfg, lt, di, dj, ws)
+        opt.layer_bwd(cfg, lt, di, dj, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    gemms = layer_gemm_list(b, s, h)
+    summa_flops = sum(opt.gemm_flops(M, K, N, q) for (_, _, M, K, N) in gemms)
+    layer_flops = opt.layer_flops(cfg, 0) + opt.layer_flops(cfg, 1)
+    value = summa_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel timings with HIP events on the launch stream ----
+    fwd_ms = event_time_ms(lambda: opt.layer_fwd(cfg, lt, di, dj, ws), max(5, args.steps // 2))
+    bwd_ms = event_time_ms(lambda: opt.layer_bwd(cfg, lt, di, dj, ws), max(5, args.steps // 2))
+    gemm_rows = time_gemms(opt, torch, gemms, q, di, dj, args.gemm_reps, cfgd["seed"])
+    dom = max(gemm_rows, key=lambda r: r["us"])
+    dom_flops = 2 * dom["block"][0] * dom["block"][1] * dom["block"][2]
+    roofline = {"bound": "mfma", "kernel": f"gemm_mfma_kernel ({dom['name']}, block {dom['block']})",
+                "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "flops_per_launch": dom_flops,
+                "avg_us": dom["us"], "traffic": None}
+    sum_us = sum(r["us"] for r in gemm_rows)
+    gemm_only_tflops = summa_flops / (sum_us * 1e-6) / 1e12
+
+    # bandwidth-bound kernels of the step (device mode): algorithmic bytes / event time
+    rows_b, cols_b = (b * s) // q, h // q
+    ln_ms = event_time_ms(lambda: opt.layernorm2d(T["x"], T["ln1_g"], T["ln1_b"], T["ln1_out"], T["xhat1"], T["rstd1"], T["stats1"],
+                                                   b * s, h, q, di, dj, 1e-5, opt.BF16), args.gemm_reps)
+    ln_bytes = rows_b * cols_b * 2 * 3   # read x, write y and xhat
+    nmat = (b // q) * (n // q)
+    aws = torch.empty(opt.attention_workspace_bytes(b, s, h, n, q), dtype=torch.uint8, device="cuda:0")
+    att_ms = event_time_ms(lambda: opt.attention_fwd(T["qkv"], T["probs"], T["attn"], b, s, h, n, q, di, dj, True, opt.BF16, aws), args.gemm_reps)
+    bw = {"layernorm2d_fwd": {"us": round(ln_ms * 1e3, 2), "algorithmic_bytes": ln_bytes,
+                              "GBps": round(ln_bytes / (ln_ms * 1e-3) / 1e9, 1),
+                              "frac_hbm_peak": round(ln_bytes / (ln_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+          "attention_fwd_3_kernels": {"us": round(att_ms * 1e3, 2), "score_matrices": nmat, "s": s}}
+
+    out = {
+        "metric": "per-device SUMMA GEMM TFLOP/s (AB/ABᵀ/AᵀB) and % of MI355X bf16 MFMA peak",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: one device ({di},{dj}) of a q={q} grid, layer fwd+bwd, b={b} s={s} h={h} n={n}, causal",
+                   "q": q, "device": [di, dj], "b": b, "s": s, "h": h, "heads": n,
+                   "step": "optimus_layer_fwd + optimus_layer_bwd (device mode, peers resident)"},
+        "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
+        "roofline": roofline,
+        "step_detail": {"summa_flops_per_step": summa_flops, "layer_flops_per_step_table1": layer_flops,
+                        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
+                        "sum_of_12_gemm_kernels_us": round(sum_us, 1), "gemm_only_tflops": round(gemm_only_tflops, 1),
+                        "gemm_only_pct_peak": round(100 * gemm_only_tflops / PEAK_BF16_TFLOPS, 1)},
+        "gemms": gemm_rows,
+        "bandwidth_kernels": bw,
+        "paper_context": {"training_speedup_vs_megatron_64gpu": 1.48, "inference_speedup_vs_megatron_64gpu": 1.78,
+                          "hardware": "64x Quadro RTX 5000, TACC Frontera (other machine: context, not a target)"},
+    }
+
+    if not args.no_sweep:
+        from workloads import gemm_cases
+        per = {}
+        for name in ("config2", "config3", "config4", "config5"):
+            cases = [(g.name, g.form, g.M, g.K, g.N) for g in gemm_cases(name)]
+            qq = gemm_cases(name)[0].q
+            rows = time_gemms(opt, torch, cases, qq, qq - 1, 1, max(10, args.gemm_reps // 2), 1000 + qq)
+            tot_fl = sum(2 * r["block"][0] * r["block"][1] * r["block"][2] for r in rows)
+            tot_us = sum(r["us"] for r in rows)
+            per[name] = {"q": qq, "aggregate_tflops": round(tot_fl / (tot_us * 1e-6) / 1e12, 1),
+                         "aggregate_pct_peak": round(100 * tot_fl / (tot_us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 1),
+                         "best_pct_peak": max(r["pct_peak"] for r in rows), "worst_pct_peak": min(r["pct_peak"] for r in rows),
+                         "gemms": rows}
+        out["per_config"] = per
+
+    if not args.no_cpu:
+        # CPU oracle (fp64 numpy, as it stands) on the host cores: the whole logical problem of this workload
+        # for config2; for the larger workloads a bounded sample (the forward SUMMA products of the MLP only).
+        from oracle import layer as olayer, summa as osumma
+        import threadpoolctl
+        info = threadpoolctl.threadpool_info()
+        threads = max([d.get("num_threads", 1) for d in info] + [1])
+        c0 = time.perf_counter()
+        if args.workload == "config2":
+            fwd_o = olayer.forward(inp, b, s, n, causal=True, keep_probs=False)
+            olayer.backward(inp, fwd_o, b, s, n, causal=True)
+            cpu_flops = 3 * 2 * 12 * b * s * h * h          # SUMMA-product flops of the full logical layer, fwd + bwd
+            sample = "oracle.layer forward+backward (fp64) of the whole logical config2 layer = all 16 devices' work"
+        else:
+            rowsN = min(b * s, 2048)
+            osumma.matmul_ab(inp["x"][:rowsN], inp["w1"])
+            cpu_flops = 2 * rowsN * h * 4 * h
+            sample = f"oracle.summa.matmul_ab (fp64) on {rowsN} rows of the h->4h product"
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": round(cpu_flops / (c1 - c0) / 1e12, 4), "unit": "TFLOP/s", "cores": threads,
+                               "kind": "oracle", "sample": sample, "seconds": round(c1 - c0, 2),
+                               "os_cpu_count": os.cpu_count()}
+    print(json.dumps(out, ensure_ascii=False))
+
+
+if __name__ == "__main__":
+    main()

@@ -27,8 +27,20 @@ __device__ __forceinline__ void store_elem(void* p, long long idx, int bf16, flo
   else ((float*)p)[idx] = v;
 }
 
+// The transcendental parts are kept out of line: the matrix-core kernels unroll this epilogue 64 times per lane and
+// must stay small enough to unroll fully (otherwise the accumulators are forced into scratch memory).
+__device__ __attribute__((noinline)) void gelu4(float t[4]) {
+#pragma unroll
+  for (int c = 0; c < 4; ++c) t[c] = gelu_exact(t[c]);
+}
+__device__ __attribute__((noinline)) void gelu_grad_mul4(float t[4], const float z[4]) {
+#pragma unroll
+  for (int c = 0; c < 4; ++c) t[c] *= gelu_grad_exact(z[c]);
+}
+
 // v[0..3]: accumulators of row m, columns n..n+3 (n % 4 == 0); coff: element offset of this batch's C block;
-// nvalid: how many of the four columns exist.
+// nvalid: how many of the four columns exist.  VEC_ONLY: the caller guarantees e.vec_ok and nvalid == 4.
+template <bool VEC_ONLY = false>
 __device__ __forceinline__ void epilogue_store4(const EpiArgs& e, long long coff, int m, int n, float v[4], int nvalid) {
   long long off = coff + (long long)m * e.ldc + n;
   float t[4];
@@ -39,32 +51,28 @@ __device__ __forceinline__ void epilogue_store4(const EpiArgs& e, long long coff
     for (int c = 0; c < 4; ++c)
       if (c < nvalid) t[c] += e.bias[n + c];
   }
-  const bool vec = e.vec_ok && nvalid == 4;
+  const bool vec = VEC_ONLY || (e.vec_ok && nvalid == 4);
   if (e.pre_act) {
     if (vec && e.in_bf16) {
       uint2 w = make_uint2(pack2_bf16(t[0], t[1]), pack2_bf16(t[2], t[3]));
       *(uint2*)((bf16_t*)e.pre_act + off) = w;
     } else if (vec) {
       *(float4*)((float*)e.pre_act + off) = make_float4(t[0], t[1], t[2], t[3]);
-    } else {
+    } else if (!VEC_ONLY) {
       for (int c = 0; c < nvalid; ++c) store_elem(e.pre_act, off + c, e.in_bf16, t[c]);
     }
   }
-  if (e.act == 1) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) t[c] = gelu_exact(t[c]);
-  }
+  if (e.act == 1) gelu4(t);
   if (e.gelu_grad_of) {
     float z[4] = {0.f, 0.f, 0.f, 0.f};
     if (vec && e.in_bf16) {
       uint2 w = *(const uint2*)((const bf16_t*)e.gelu_grad_of + off);
       z[0] = __uint_as_float(w.x << 16); z[1] = __uint_as_float(w.x & 0xffff0000u);
       z[2] = __uint_as_float(w.y << 16); z[3] = __uint_as_float(w.y & 0xffff0000u);
-    } else {
+    } else if (!VEC_ONLY) {
       for (int c = 0; c < nvalid; ++c) z[c] = load_elem(e.gelu_grad_of, off + c, e.in_bf16);
     }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) t[c] *= gelu_grad_exact(z[c]);
+    gelu_grad_mul4(t, z);
   }
   if (e.residual) {
     float r[4] = {0.f, 0.f, 0.f, 0.f};
@@ -72,7 +80,7 @@ __device__ __forceinline__ void epilogue_store4(const EpiArgs& e, long long coff
       uint2 w = *(const uint2*)((const bf16_t*)e.residual + off);
       r[0] = __uint_as_float(w.x << 16); r[1] = __uint_as_float(w.x & 0xffff0000u);
       r[2] = __uint_as_float(w.y << 16); r[3] = __uint_as_float(w.y & 0xffff0000u);
-    } else {
+    } else if (!VEC_ONLY) {
       for (int c = 0; c < nvalid; ++c) r[c] = load_elem(e.residual, off + c, e.in_bf16);
     }
 #pragma unroll
@@ -83,7 +91,7 @@ __device__ __forceinline__ void epilogue_store4(const EpiArgs& e, long long coff
     *(uint2*)((bf16_t*)e.C + off) = make_uint2(pack2_bf16(t[0], t[1]), pack2_bf16(t[2], t[3]));
   } else if (vec) {
     *(float4*)((float*)e.C + off) = make_float4(t[0], t[1], t[2], t[3]);
-  } else {
+  } else if (!VEC_ONLY) {
     for (int c = 0; c < nvalid; ++c) store_elem(e.C, off + c, out_bf16, t[c]);
   }
 }

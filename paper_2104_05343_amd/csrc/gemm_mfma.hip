@@ -1,4 +1,4 @@
-// bf16 matrix-core product kernel for gfx950 (CDNA4).
+// bf16 matrix-core product kernels for gfx950 (CDNA4).
 //
 // Computes, per batch entry, C = alpha * sum_{l<nl} op(A_l) * op(B_l) with fp32 accumulation in
 // v_mfma_f32_32x32x16_bf16 and applies the epilogue once.  The nl panels of a SUMMA product
@@ -7,11 +7,21 @@
 // arithmetic and no partial C ever goes to HBM (unless the caller asked for a panel split).
 //
 // Tiling: a workgroup of WM*WN wavefronts owns a BM x BN output tile; k advances in slabs of
-// BK = 64.  Slabs go global -> registers -> LDS (double buffered, one barrier per slab).
-//   * k-contiguous operands ([rows][k] in memory) are stored as rows of 8 sixteen-byte chunks,
-//     chunk index XOR-ed with (row & 7) so that the 32 lanes of a fragment read hit all banks.
-//   * k-strided operands ([k][cols] in memory: B of A*B, both operands of A^T*B) are stored
-//     as they are, rows padded by 16 elements, and fetched with the transposing LDS read
+// BK = 32 through FOUR LDS stages (three slabs in flight while one is multiplied: the latency
+// of L2/HBM under load is about three slab times).
+//   * Full tiles (FAST): every wavefront issues buffer_load_dwordx4 ... lds, which moves 64 x 16
+//     bytes from per-lane offsets straight into one contiguous KiB of LDS without passing
+//     through registers.  The LDS swizzles below are therefore applied on the GLOBAL side:
+//     lane p of a KiB fetches the 16 bytes that belong at LDS position p.  Buffer addressing
+//     (SGPR resource + one 32-bit VGPR offset) is used because 64-bit per-lane addresses were
+//     measured to stall the MFMA pipe twice as much.  Slab hand-over uses s_waitcnt vmcnt(N) and
+//     a bare s_barrier: a fenced barrier would drain the loads in flight.
+//   * Ragged tiles: global -> registers (zero filled outside the operand) -> LDS, same layout.
+// LDS layouts (conflict free for their readers on the 64-bank, 256 B/clk LDS of this part):
+//   * k-contiguous operand ([rows][k] in memory): rows of 4 sixteen-byte chunks, chunk index
+//     XOR ((row >> 2) & 3); fragments are read with ds_read_b128.
+//   * k-strided operand ([k][cols] in memory: B of A*B, both operands of A^T*B): kept as it is,
+//     32-byte column granules XOR 2*(k & 3); fragments are fetched with the transposing read
 //     ds_read_b64_tr_b16, which hands each lane four consecutive k of one column.
 // The two MFMA operands are swapped (D^T = B^T A^T) so that every lane ends up with four
 // consecutive columns of one output row: 8-byte bf16 stores, and vector loads of the residual.
@@ -21,7 +31,6 @@
 namespace optimus {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -31,8 +40,8 @@ static int g_variant = -1;
 void gemm_set_variant(int v) { g_variant = v; }
 int gemm_get_variant() { return g_variant; }
 
-constexpr int BK = 64;
-constexpr int PAD = 16;  // elements of row padding for k-strided LDS tiles
+constexpr int BK = 32;
+constexpr int NSTAGE = 4;
 
 struct KArgs {
   const bf16_t* A;
@@ -51,13 +60,89 @@ struct KArgs {
   EpiArgs epi;
 };
 
-template <int ROWS, bool KC>
-struct TileLds {
-  // KC: [ROWS][64] swizzled; else [64][ROWS + PAD]
-  static constexpr int elems = KC ? ROWS * BK : BK * (ROWS + PAD);
+// element offset inside an LDS tile
+// The LDS of this part serves 256 bytes per clock (64 four-byte banks).  A ds_read_b128 is served 16 lanes at a
+// time (16 consecutive rows, one chunk each): four 64-byte rows span the 64 banks, so the XOR term must take 4
+// distinct values over the 4 rows of equal (row & 3) -> (row >> 2) & 3.  A ds_read_b64_tr_b16 is served 32 lanes at
+// a time (4 k-rows x two adjacent 32-byte granules): rows start at bank 0, so the 8 (k, granule) pairs must fall in
+// 8 distinct granule slots -> XOR with 2 * (k & 3).  Measured with a read-only microbenchmark: > 200 B/clk for
+// these patterns against 128 B/clk for swizzles designed for 32 banks.
+__device__ __forceinline__ int lds_off_kc(int row, int chunk) { return row * BK + ((chunk ^ ((row >> 2) & 3)) << 3); }
+template <int ROWS>
+__device__ __forceinline__ int lds_off_ks(int krow, int col) {
+  return krow * ROWS + ((((col >> 4) ^ ((krow & 3) << 1))) << 4) + (col & 15);
+}
+
+// ---- FAST path: direct global -> LDS, one KiB per wavefront instruction ----
+template <int ROWS, int NW>
+struct DirectPlan {
+  static constexpr int CHUNKS = ROWS * BK * 2 / 1024;  // KiB chunks in a [ROWS x BK] bf16 slab
+  static constexpr int PER = CHUNKS / NW;
+  static_assert(CHUNKS % NW == 0 && PER >= 1, "slab must divide over the wavefronts");
 };
 
-// ---- global -> register staging of one operand slab ----
+// Per-lane source offsets (BYTES, relative to the slab origin) of the KiB chunks this wavefront moves.
+template <int ROWS, bool KC, int NW, int PER>
+__device__ __forceinline__ void direct_offsets(unsigned (&off)[PER], int ld, int wave, int lane) {
+#pragma unroll
+  for (int it = 0; it < PER; ++it) {
+    const int q = wave * PER + it;
+    if (KC) {
+      const int row = q * 16 + (lane >> 2);
+      const int kc = (lane & 3) ^ ((row >> 2) & 3);  // inverse of lds_off_kc for LDS position (row, lane & 3)
+      off[it] = (unsigned)(row * ld + kc * 8) * 2u;
+    } else {
+      constexpr int PPR = ROWS / 8;  // 16-byte pieces per k-row
+      const int idx = q * 64 + lane;
+      const int krow = idx / PPR, pp = idx % PPR;
+      const int col = ((((pp >> 1) ^ ((krow & 3) << 1))) << 4) + ((pp & 1) << 3);  // inverse of lds_off_ks
+      off[it] = (unsigned)(krow * ld + col) * 2u;
+    }
+  }
+}
+
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+// Buffer resource (raw, stride 0) whose base is the current panel's tile origin, with a 2 GiB window: every offset
+// used is below it (checked on the host).  Built by hand as four SGPR words.
+__device__ __forceinline__ i32x4 make_rsrc(const bf16_t* base) {
+  const unsigned long long p = (unsigned long long)base;
+  return i32x4{(int)(unsigned)p, (int)(unsigned)((p >> 32) & 0xffffu), (int)0x80000000u, 0x00020000};
+}
+
+// rsrc: see make_rsrc; soff: byte offset of the slab inside the panel; off: per-lane byte offsets.
+// The LDS load is written in assembly on purpose: issued through the compiler's builtin, every later LDS read is
+// preceded by a compiler-inserted wait for ALL loads in flight (it cannot tell the stages apart), which collapses
+// the four-stage pipeline to one slab.  Here the hand-over is explicit instead: s_waitcnt vmcnt(N) + barrier.
+template <int ROWS, int NW, int PER>
+__device__ __forceinline__ void direct_issue(i32x4 rsrc, unsigned soff, const unsigned (&off)[PER], bf16_t* lds_tile, int wave) {
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)lds_tile;
+#pragma unroll
+  for (int it = 0; it < PER; ++it) {
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)(wave * PER + it) * 1024u);
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds" ::"v"(off[it]), "s"(rsrc), "s"(soff), "s"(m0v)
+                 : "memory");
+  }
+}
+
+// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt left at their maxima), gfx9 encoding.  The builtin rather than inline
+// assembly: the compiler's own wait-count pass then knows which LDS loads have landed and adds no full drain.
+constexpr int waitcnt_vm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+#define OPTIMUS_WAIT_VMCNT(n)                      \
+  do {                                             \
+    asm volatile("" ::: "memory");                 \
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(n));     \
+    asm volatile("" ::: "memory");                 \
+  } while (0)
+// barrier without the memory fence of __syncthreads(): loads of later slabs stay in flight across it
+#define OPTIMUS_BARRIER()                  \
+  do {                                     \
+    asm volatile("" ::: "memory");         \
+    __builtin_amdgcn_s_barrier();          \
+    asm volatile("" ::: "memory");         \
+  } while (0)
+
+// ---- ragged path: global -> registers -> LDS ----
 template <int ROWS, int THREADS>
 struct StageDims {
   static constexpr int CHUNKS = ROWS * BK / 8;  // 16-byte chunks in a slab
@@ -65,9 +150,9 @@ struct StageDims {
   static_assert(CHUNKS % THREADS == 0, "slab must divide over the workgroup");
 };
 
-// base: panel base already offset to this tile's first row/col; ld: leading dimension;
-// rows_left: valid rows (m or n) from the tile origin; k_left: valid k from the slab origin
-template <int ROWS, bool KC, int THREADS, bool GUARD, int PER>
+// base: panel base already offset to this tile's first row/col; rows_left: valid rows (m or n) from the tile
+// origin; k_left: valid k from the slab origin
+template <int ROWS, bool KC, int THREADS, int PER>
 __device__ __forceinline__ void stage_load(u32x4 (&r)[PER], const bf16_t* base, int ld, int k0, int rows_left, int k_left,
                                            int tid) {
   static_assert(PER == StageDims<ROWS, THREADS>::PER, "staging array size");
@@ -75,32 +160,29 @@ __device__ __forceinline__ void stage_load(u32x4 (&r)[PER], const bf16_t* base, 
   for (int it = 0; it < PER; ++it) {
     const int c = tid + it * THREADS;
     if (KC) {
-      const int row = c >> 3, kc = c & 7;
+      const int row = c / (BK / 8), kc = c % (BK / 8);
       const bf16_t* p = base + (long long)row * ld + k0 + kc * 8;
-      if (!GUARD || (row < rows_left && kc * 8 < k_left)) r[it] = *(const u32x4*)p;
+      if (row < rows_left && kc * 8 < k_left) r[it] = *(const u32x4*)p;
       else r[it] = u32x4{0u, 0u, 0u, 0u};
     } else {
       constexpr int CPR = ROWS / 8;
       const int krow = c / CPR, mc = c % CPR;
       const bf16_t* p = base + (long long)(k0 + krow) * ld + mc * 8;
-      if (!GUARD || (krow < k_left && mc * 8 < rows_left)) r[it] = *(const u32x4*)p;
+      if (krow < k_left && mc * 8 < rows_left) r[it] = *(const u32x4*)p;
       else r[it] = u32x4{0u, 0u, 0u, 0u};
     }
   }
 }
 template <int ROWS, bool KC, int THREADS, int PER>
 __device__ __forceinline__ void stage_store(const u32x4 (&r)[PER], bf16_t* lds, int tid) {
-  static_assert(PER == StageDims<ROWS, THREADS>::PER, "staging array size");
 #pragma unroll
   for (int it = 0; it < PER; ++it) {
     const int c = tid + it * THREADS;
     if (KC) {
-      const int row = c >> 3, kc = c & 7;
-      *(u32x4*)(lds + row * BK + ((kc ^ (row & 7)) << 3)) = r[it];
+      *(u32x4*)(lds + lds_off_kc(c / (BK / 8), c % (BK / 8))) = r[it];
     } else {
       constexpr int CPR = ROWS / 8;
-      const int krow = c / CPR, mc = c % CPR;
-      *(u32x4*)(lds + krow * (ROWS + PAD) + mc * 8) = r[it];
+      *(u32x4*)(lds + lds_off_ks<ROWS>(c / CPR, (c % CPR) * 8)) = r[it];
     }
   }
 }
@@ -109,15 +191,13 @@ __device__ __forceinline__ void stage_store(const u32x4 (&r)[PER], bf16_t* lds, 
 template <int ROWS, bool KC>
 __device__ __forceinline__ bf16x8 read_frag(const bf16_t* lds, int rc0, int ks, int lane) {
   if (KC) {
-    int row = rc0 + (lane & 31);
-    int chunk = ks * 2 + (lane >> 5);
-    return *(const bf16x8*)(lds + row * BK + ((chunk ^ (row & 7)) << 3));
+    return *(const bf16x8*)(lds + lds_off_kc(rc0 + (lane & 31), ks * 2 + (lane >> 5)));
   } else {
-    int lg = lane & 15;
-    int col = rc0 + (((lane >> 4) & 1) << 4) + ((lg & 3) << 2);
-    int krow = ks * 16 + ((lane >> 5) << 3) + (lg >> 2);
-    const bf16_t* p0 = lds + krow * (ROWS + PAD) + col;
-    const bf16_t* p1 = p0 + 4 * (ROWS + PAD);
+    const int lg = lane & 15;
+    const int col = rc0 + (((lane >> 4) & 1) << 4) + ((lg & 3) << 2);
+    const int krow = ks * 16 + ((lane >> 5) << 3) + (lg >> 2);
+    const bf16_t* p0 = lds + lds_off_ks<ROWS>(krow, col);
+    const bf16_t* p1 = p0 + 4 * ROWS;  // krow + 4: same (k & 3), same swizzle term
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
     s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
     s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -125,20 +205,96 @@ __device__ __forceinline__ bf16x8 read_frag(const bf16_t* lds, int rc0, int ks, 
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool GUARD>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const KArgs a) {
-  constexpr int THREADS = WM * WN * 64;
-  constexpr int TM = BM / WM, TN = BN / WN;
-  constexpr int MI = TM / 32, NI = TN / 32;
-  constexpr int A_ELEMS = TileLds<BM, AKC>::elems;
-  constexpr int B_ELEMS = TileLds<BN, BKC>::elems;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t* smem = (bf16_t*)smem_raw;
-  constexpr int STAGE = A_ELEMS + B_ELEMS;  // stage s: A at smem + s*STAGE, B right after it
+template <int BM, int BN, int WM, int WN>
+struct Tile {
+  static constexpr int NW = WM * WN, THREADS = NW * 64;
+  static constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
+  static constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK;
+};
+
+// Instruction-order hint for one sub-step: spread the DS fragment reads of the NEXT sub-step between the first
+// MFMAs of the current one (PER reads, one MFMA, ...), then the remaining MFMAs.  Masks: 0x100 DS read, 0x8 MFMA.
+template <int DS, int MFMA, int PER>
+__device__ __forceinline__ void sched_interleave() {
+  if constexpr (DS > 0 && MFMA > 0) {
+    constexpr int n = DS < PER ? DS : PER;
+    __builtin_amdgcn_sched_group_barrier(0x100, n, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    sched_interleave<DS - n, MFMA - 1, PER>();
+  } else if constexpr (MFMA > 0) {
+    __builtin_amdgcn_sched_group_barrier(0x008, MFMA, 0);
+  } else if constexpr (DS > 0) {
+    __builtin_amdgcn_sched_group_barrier(0x100, DS, 0);
+  }
+}
+
+// One slab of MFMAs from LDS.  Software pipeline over the four 16-wide sub-steps: the fragments of sub-step
+// ks+1 are requested while the MFMAs of sub-step ks run (their operands were requested one sub-step earlier).
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC>
+__device__ __forceinline__ void compute_slab(f32x16 (&acc)[BM / WM / 32][BN / WN / 32], const bf16_t* la, const bf16_t* lb,
+                                             int wm, int wn, int lane) {
+  using T = Tile<BM, BN, WM, WN>;
+  constexpr int DS = T::MI * (AKC ? 1 : 2) + T::NI * (BKC ? 1 : 2);  // DS instructions per sub-step
+  constexpr int MF = T::MI * T::NI;
+  constexpr int PER = (DS + MF / 2 - 1) / (MF / 2 > 0 ? MF / 2 : 1);  // reads finished within the first half of the MFMAs
+  bf16x8 af[2][T::MI], bfr[2][T::NI];
+#pragma unroll
+  for (int mi = 0; mi < T::MI; ++mi) af[0][mi] = read_frag<BM, AKC>(la, wm * T::TM + mi * 32, 0, lane);
+#pragma unroll
+  for (int ni = 0; ni < T::NI; ++ni) bfr[0][ni] = read_frag<BN, BKC>(lb, wn * T::TN + ni * 32, 0, lane);
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) {
+    const int c = ks & 1, nx = c ^ 1;
+    __builtin_amdgcn_sched_barrier(0);
+    if (ks + 1 < BK / 16) {
+#pragma unroll
+      for (int mi = 0; mi < T::MI; ++mi) af[nx][mi] = read_frag<BM, AKC>(la, wm * T::TM + mi * 32, ks + 1, lane);
+#pragma unroll
+      for (int ni = 0; ni < T::NI; ++ni) bfr[nx][ni] = read_frag<BN, BKC>(lb, wn * T::TN + ni * 32, ks + 1, lane);
+    }
+#pragma unroll
+    for (int mi = 0; mi < T::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < T::NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[c][ni], af[c][mi], acc[mi][ni], 0, 0, 0);
+    if (ks + 1 < BK / 16) sched_interleave<DS, MF, PER>();
+  }
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// wavefronts per SIMD the kernel is compiled for: what two LDS stages of the tile allow on a 160 KiB CU
+template <int BM, int BN, int WM, int WN>
+struct Occ {
+  static constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
+  static constexpr int wgs = (160 * 1024) / lds_bytes;
+  static constexpr int waves_per_simd_raw = wgs * WM * WN / 4;
+  static constexpr int value = waves_per_simd_raw < 1 ? 1 : (waves_per_simd_raw > 2 ? 2 : waves_per_simd_raw);
+};
+
+// FAST = full tiles, direct-to-LDS loads, vector epilogue; !FAST = bounds-checked everything.
+// PLAIN (FAST only) = the epilogue is a bare store of the accumulator (alpha 1, no bias / activation / residual):
+// a short, fully unrolled store sequence instead of the general epilogue, whose straight-line code costs
+// microseconds per tile.
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST, bool PLAIN>
+__global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gemm_mfma_kernel(const KArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  using T = Tile<BM, BN, WM, WN>;
+  constexpr int THREADS = T::THREADS, NW = T::NW;
+  constexpr int TM = T::TM, TN = T::TN, MI = T::MI, NI = T::NI;
+  // the stages are separate LDS objects: the compiler can then see that a load into one stage does not alias
+  // the fragment reads of another and does not serialise them
+  __shared__ __attribute__((aligned(1024))) bf16_t sA0[T::A_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB0[T::B_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA1[T::A_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB1[T::B_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA2[T::A_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB2[T::B_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sA3[T::A_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t sB3[T::B_ELEMS];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
   // ---- which tile: XCD-aware remap of the linear workgroup id ----
@@ -149,8 +305,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const KArgs a) {
   {
     long long per = nwg >> 3, rem = nwg & 7;
     long long xcd = wg & 7, slot = wg >> 3;
-    // XCDs 0..rem-1 own per+1 workgroups, the rest own per
-    long long start = xcd * per + (xcd < rem ? xcd : rem);
+    long long start = xcd * per + (xcd < rem ? xcd : rem);  // XCDs 0..rem-1 own per+1 workgroups
     wg = start + slot;
   }
   const int split = (int)(wg % a.splits);
@@ -158,9 +313,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const KArgs a) {
   const int tiles = a.tiles_m * a.tiles_n;
   const long long z = wg / tiles;
   int t = (int)(wg % tiles);
-  // column-major walk within groups of 8 tile rows keeps the working set of an XCD compact
   int tm, tn;
-  {
+  {  // column-major walk within groups of 8 tile rows keeps the working set of an XCD compact
     constexpr int GROUP = 8;
     int per_group = GROUP * a.tiles_n;
     int g = t / per_group;
@@ -198,49 +352,97 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const KArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
 
-  u32x4 ra[StageDims<BM, THREADS>::PER];
-  u32x4 rb[StageDims<BN, THREADS>::PER];
   const bf16_t* Atile = Az + (AKC ? (long long)m0 * a.lda : (long long)m0);
   const bf16_t* Btile = Bz + (BKC ? (long long)n0 * a.ldb : (long long)n0);
-  const int rowsA = a.Mb - m0, rowsB = a.Nb - n0;
 
   if (t_lo < t_hi) {
-    // slab index -> (panel l, offset k0 inside the panel); advanced incrementally, no division in the loop
+    // slab index -> (panel l, offset k0 inside the panel); advanced incrementally
     int l = t_lo / tpp, k0 = (t_lo - l * tpp) * BK;
-    stage_load<BM, AKC, THREADS, GUARD>(ra, Atile + l * a.sAl, a.lda, k0, rowsA, a.Kp - k0, tid);
-    stage_load<BN, BKC, THREADS, GUARD>(rb, Btile + l * a.sBl, a.ldb, k0, rowsB, a.Kp - k0, tid);
-    stage_store<BM, AKC, THREADS>(ra, smem, tid);
-    stage_store<BN, BKC, THREADS>(rb, smem + A_ELEMS, tid);
-    __syncthreads();
-    for (int tt = t_lo; tt < t_hi; ++tt) {
-      const int cur = (tt - t_lo) & 1;
-      const bool more = tt + 1 < t_hi;
-      if (more) {
-        k0 += BK;
-        if (k0 >= a.Kp) { k0 = 0; ++l; }
-        stage_load<BM, AKC, THREADS, GUARD>(ra, Atile + l * a.sAl, a.lda, k0, rowsA, a.Kp - k0, tid);
-        stage_load<BN, BKC, THREADS, GUARD>(rb, Btile + l * a.sBl, a.ldb, k0, rowsB, a.Kp - k0, tid);
+    if constexpr (FAST) {
+      constexpr int PA = DirectPlan<BM, NW>::PER, PB = DirectPlan<BN, NW>::PER;
+      constexpr int LPS = PA + PB;  // load instructions per wavefront per slab
+      unsigned offA[PA], offB[PB];
+      direct_offsets<BM, AKC, NW, PA>(offA, a.lda, wave, lane);
+      direct_offsets<BN, BKC, NW, PB>(offB, a.ldb, wave, lane);
+      const unsigned stepA = (unsigned)(AKC ? BK : BK * a.lda) * 2u;  // slab-to-slab byte advance inside a panel
+      const unsigned stepB = (unsigned)(BKC ? BK : BK * a.ldb) * 2u;
+      // load cursor: panel lq, k offset kq, one buffer resource per panel, byte offsets inside the panel
+      int lq = l, kq = k0;
+      i32x4 ra = make_rsrc(Atile + lq * a.sAl), rb = make_rsrc(Btile + lq * a.sBl);
+      unsigned sa = (unsigned)(AKC ? kq : kq * a.lda) * 2u, sb = (unsigned)(BKC ? kq : kq * a.ldb) * 2u;
+      const int nslab = t_hi - t_lo;
+      int issued = 0;
+#define OPTIMUS_ISSUE(SA, SB)                                                        \
+  do {                                                                               \
+    direct_issue<BM, NW, PA>(ra, sa, offA, SA, wave);                                \
+    direct_issue<BN, NW, PB>(rb, sb, offB, SB, wave);                                \
+    ++issued;                                                                        \
+    kq += BK;                                                                        \
+    if (kq >= a.Kp) {                                                                \
+      kq = 0; ++lq; sa = 0; sb = 0;                                                  \
+      ra = make_rsrc(Atile + lq * a.sAl); rb = make_rsrc(Btile + lq * a.sBl);        \
+    } else { sa += stepA; sb += stepB; }                                             \
+  } while (0)
+      // One pipeline step: slab i is resident in (SA, SB); refill the stage that held slab i-1 with slab i+3;
+      // multiply; then make sure slab i+1 has landed (leaving the younger loads in flight) and meet the others.
+#define OPTIMUS_STEP(SA, SB, PA_, PB_)                                               \
+  do {                                                                               \
+    if (issued < nslab) OPTIMUS_ISSUE(PA_, PB_);                                     \
+    compute_slab<BM, BN, WM, WN, AKC, BKC>(acc, SA, SB, wm, wn, lane);               \
+    const int younger = issued - (i + 2); /* slabs beyond i+1 already requested */   \
+    if (younger >= 2) OPTIMUS_WAIT_VMCNT(2 * LPS);                                   \
+    else if (younger == 1) OPTIMUS_WAIT_VMCNT(LPS);                                  \
+    else OPTIMUS_WAIT_VMCNT(0);                                                      \
+    OPTIMUS_BARRIER();                                                               \
+    ++i;                                                                             \
+  } while (0)
+      // prologue: slabs 0..2
+      OPTIMUS_ISSUE(sA0, sB0);
+      if (issued < nslab) OPTIMUS_ISSUE(sA1, sB1);
+      if (issued < nslab) OPTIMUS_ISSUE(sA2, sB2);
+      if (issued >= 3) OPTIMUS_WAIT_VMCNT(2 * LPS);
+      else if (issued == 2) OPTIMUS_WAIT_VMCNT(LPS);
+      else OPTIMUS_WAIT_VMCNT(0);
+      OPTIMUS_BARRIER();
+      int i = 0;
+      while (i + 4 <= nslab) {
+        OPTIMUS_STEP(sA0, sB0, sA3, sB3);
+        OPTIMUS_STEP(sA1, sB1, sA0, sB0);
+        OPTIMUS_STEP(sA2, sB2, sA1, sB1);
+        OPTIMUS_STEP(sA3, sB3, sA2, sB2);
       }
-      const bf16_t* la = smem + cur * STAGE;
-      const bf16_t* lb = la + A_ELEMS;
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        bf16x8 af[MI], bfg[NI];
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) af[mi] = read_frag<BM, AKC>(la, wm * TM + mi * 32, ks, lane);
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) bfg[ni] = read_frag<BN, BKC>(lb, wn * TN + ni * 32, ks, lane);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfg[ni], af[mi], acc[mi][ni], 0, 0, 0);
-      }
-      if (more) {
-        stage_store<BM, AKC, THREADS>(ra, smem + (cur ^ 1) * STAGE, tid);
-        stage_store<BN, BKC, THREADS>(rb, smem + (cur ^ 1) * STAGE + A_ELEMS, tid);
-      }
+      // tail: up to three slabs, already requested (issued == nslab by now)
+      if (i < nslab) OPTIMUS_STEP(sA0, sB0, sA3, sB3);
+      if (i < nslab) OPTIMUS_STEP(sA1, sB1, sA0, sB0);
+      if (i < nslab) OPTIMUS_STEP(sA2, sB2, sA1, sB1);
+#undef OPTIMUS_STEP
+#undef OPTIMUS_ISSUE
+    } else {
+      u32x4 ra[StageDims<BM, THREADS>::PER];
+      u32x4 rb[StageDims<BN, THREADS>::PER];
+      const int rowsA = a.Mb - m0, rowsB = a.Nb - n0;
+      stage_load<BM, AKC, THREADS>(ra, Atile + l * a.sAl, a.lda, k0, rowsA, a.Kp - k0, tid);
+      stage_load<BN, BKC, THREADS>(rb, Btile + l * a.sBl, a.ldb, k0, rowsB, a.Kp - k0, tid);
+      stage_store<BM, AKC, THREADS>(ra, sA0, tid);
+      stage_store<BN, BKC, THREADS>(rb, sB0, tid);
       __syncthreads();
+      for (int tt = t_lo; tt < t_hi; ++tt) {
+        const int cur = (tt - t_lo) & 1;
+        const bool more = tt + 1 < t_hi;
+        if (more) {
+          k0 += BK;
+          if (k0 >= a.Kp) { k0 = 0; ++l; }
+          stage_load<BM, AKC, THREADS>(ra, Atile + l * a.sAl, a.lda, k0, rowsA, a.Kp - k0, tid);
+          stage_load<BN, BKC, THREADS>(rb, Btile + l * a.sBl, a.ldb, k0, rowsB, a.Kp - k0, tid);
+        }
+        if (cur == 0) compute_slab<BM, BN, WM, WN, AKC, BKC>(acc, sA0, sB0, wm, wn, lane);
+        else compute_slab<BM, BN, WM, WN, AKC, BKC>(acc, sA1, sB1, wm, wn, lane);
+        if (more) {
+          stage_store<BM, AKC, THREADS>(ra, cur == 0 ? sA1 : sA0, tid);
+          stage_store<BN, BKC, THREADS>(rb, cur == 0 ? sB1 : sB0, tid);
+        }
+        __syncthreads();
+      }
     }
   }
 
@@ -254,11 +456,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const KArgs a) {
       for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          int m = m0 + wm * TM + mi * 32 + (lane & 31);
-          int n = n0 + wn * TN + ni * 32 + g * 8 + ((lane >> 5) << 2);
-          if (GUARD && (m >= a.Mb || n >= a.Nb)) continue;
+          const int m = m0 + wm * TM + mi * 32 + (lane & 31);
+          const int n = n0 + wn * TN + ni * 32 + g * 8 + ((lane >> 5) << 2);
+          if (!FAST && (m >= a.Mb || n >= a.Nb)) continue;
           float* p = P + (long long)m * a.Nb + n;
-          if (!GUARD || n + 3 < a.Nb) {
+          if (FAST || n + 3 < a.Nb) {
             *(float4*)p = make_float4(acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]);
           } else {
             for (int c = 0; c < 4 && n + c < a.Nb; ++c) p[c] = acc[mi][ni][g * 4 + c];
@@ -267,21 +469,52 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const KArgs a) {
     return;
   }
   EpiArgs e = a.epi;
-  if (e.bias) e.bias += z0 * a.sBias0;
   const long long coff = z1 * a.sC1 + z0 * a.sC0;
+  if constexpr (PLAIN) {
+    // this lane's first element: row m0 + wm*TM + lane%32, column n0 + wn*TN + 4*(lane/32)
+    const long long first = coff + (long long)(m0 + wm * TM + (lane & 31)) * e.ldc + n0 + wn * TN + ((lane >> 5) << 2);
+    if (!e.out_fp32) {
+      bf16_t* crow = (bf16_t*)e.C + first;
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
+      for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+        for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        int m = m0 + wm * TM + mi * 32 + (lane & 31);
-        int n = n0 + wn * TN + ni * 32 + g * 8 + ((lane >> 5) << 2);
-        if (GUARD && (m >= a.Mb || n >= a.Nb)) continue;
-        float v[4] = {acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]};
-        int nvalid = GUARD ? min(4, a.Nb - n) : 4;
-        epilogue_store4(e, coff, m, n, v, nvalid);
+          for (int g = 0; g < 4; ++g)
+            *(uint2*)(crow + ni * 32 + g * 8) = make_uint2(pack2_bf16(acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1]),
+                                                           pack2_bf16(acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]));
+        crow += 32LL * e.ldc;
       }
+    } else {
+      float* crow = (float*)e.C + first;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            *(float4*)(crow + ni * 32 + g * 8) =
+                make_float4(acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]);
+        crow += 32LL * e.ldc;
+      }
+    }
+  } else {
+    if (e.bias) e.bias += z0 * a.sBias0;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int m = m0 + wm * TM + mi * 32 + (lane & 31);
+          const int n = n0 + wn * TN + ni * 32 + g * 8 + ((lane >> 5) << 2);
+          if (!FAST && (m >= a.Mb || n >= a.Nb)) continue;
+          float v[4] = {acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]};
+          const int nvalid = FAST ? 4 : min(4, a.Nb - n);
+          epilogue_store4<FAST>(e, coff, m, n, v, nvalid);
+        }
+  }
+#endif  // __HIP_DEVICE_COMPILE__
 }
 
 // ---- fixed-order combine of panel-split partials + epilogue ----
@@ -305,46 +538,44 @@ __global__ __launch_bounds__(256) void gemm_combine_kernel(const float* partials
   }
   int z1 = (int)(z / nz0), z0 = (int)(z % nz0);
   if (e.bias) e.bias += z0 * sBias0;
-  epilogue_store4(e, z1 * sC1 + z0 * sC0, m, n, v, nvalid);
+  epilogue_store4<false>(e, z1 * sC1 + z0 * sC0, m, n, v, nvalid);
 }
 
 // ---- host side ----
 struct Variant {
   int BM, BN, WM, WN;
+  bool fast;
 };
 // index = variant id used by gemm_set_variant
 static const Variant kVariants[] = {
-    {256, 256, 2, 2},  // 0
-    {256, 128, 2, 2},  // 1
-    {128, 256, 2, 2},  // 2
-    {128, 128, 2, 2},  // 3
-    {256, 256, 2, 4},  // 4: 8 waves
-    {128, 128, 2, 2},  // 5: guarded (ragged shapes)
+    {256, 256, 2, 4, true},   // 0: 8 waves, wave tile 128x64
+    {256, 128, 4, 2, true},   // 1: 8 waves, wave tile 64x64
+    {128, 256, 2, 4, true},   // 2: 8 waves, wave tile 64x64
+    {128, 128, 2, 2, true},   // 3: 4 waves, wave tile 64x64, two workgroups per CU
+    {256, 256, 2, 4, true},   // 4: same as 0 (kept so that variant ids stay stable)
+    {128, 128, 2, 2, false},  // 5: bounds-checked (ragged shapes)
 };
 constexpr int kNumVariants = 6;
 constexpr int kGuardVariant = 5;
 
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool GUARD>
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST>
 static int launch_one(const KArgs& ka, long long nwg, hipStream_t stream) {
-  constexpr size_t lds = 2 * (size_t)(TileLds<BM, AKC>::elems + TileLds<BN, BKC>::elems) * sizeof(bf16_t);
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, AKC, BKC, GUARD>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-      (void)hipGetLastError();
-      return OPTIMUS_EHIP;
-    }
-    attr_set = true;
+  const EpiArgs& e = ka.epi;
+  const bool plain = FAST && ka.splits == 1 && e.alpha == 1.0f && !e.bias && !e.pre_act && !e.act && !e.gelu_grad_of && !e.residual;
+  if (plain) {
+    if constexpr (FAST)
+      hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, AKC, BKC, true, true>), dim3((unsigned)nwg), dim3(WM * WN * 64), 0, stream, ka);
+  } else {
+    hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, AKC, BKC, FAST, false>), dim3((unsigned)nwg), dim3(WM * WN * 64), 0, stream, ka);
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(WM * WN * 64), lds, stream, ka);
   return hip_launch_status();
 }
 
-template <int BM, int BN, int WM, int WN, bool GUARD>
+template <int BM, int BN, int WM, int WN, bool FAST>
 static int launch_layout(const GemmDesc& d, const KArgs& ka, long long nwg, hipStream_t stream) {
-  if (d.a_kcontig && !d.b_kcontig) return launch_one<BM, BN, WM, WN, true, false, GUARD>(ka, nwg, stream);
-  if (d.a_kcontig && d.b_kcontig) return launch_one<BM, BN, WM, WN, true, true, GUARD>(ka, nwg, stream);
-  if (!d.a_kcontig && !d.b_kcontig) return launch_one<BM, BN, WM, WN, false, false, GUARD>(ka, nwg, stream);
+  if (d.a_kcontig && !d.b_kcontig) return launch_one<BM, BN, WM, WN, true, false, FAST>(ka, nwg, stream);
+  if (d.a_kcontig && d.b_kcontig) return launch_one<BM, BN, WM, WN, true, true, FAST>(ka, nwg, stream);
+  if (!d.a_kcontig && !d.b_kcontig) return launch_one<BM, BN, WM, WN, false, false, FAST>(ka, nwg, stream);
   return OPTIMUS_EINVAL;  // [K][M] x [N][K] does not occur in the method
 }
 
@@ -363,10 +594,14 @@ bool gemm_mfma_supported(const GemmDesc& d) {
 }
 
 static bool variant_fits(const Variant& v, const GemmDesc& d) {
-  return d.Mb % v.BM == 0 && d.Nb % v.BN == 0 && d.Kp % BK == 0;
+  if (d.Mb % v.BM || d.Nb % v.BN || d.Kp % BK) return false;
+  // buffer addressing: per-lane byte offset (< 256 * ld * 2) plus slab byte offset (< Kp * ld * 2) inside a 2 GiB window
+  const long long ld = d.lda > d.ldb ? d.lda : d.ldb;
+  return 512 * ld < (1LL << 30) && 2 * (long long)d.Kp * ld < (1LL << 30);
 }
 
-static int pick_variant(const GemmDesc& d) {
+static int pick_variant(const GemmDesc& d, bool vec_ok) {
+  if (!vec_ok) return kGuardVariant;  // the fast kernels only have the vector epilogue
   if (g_variant >= 0 && g_variant < kNumVariants) {
     if (g_variant == kGuardVariant || variant_fits(kVariants[g_variant], d)) return g_variant;
   }
@@ -394,10 +629,11 @@ size_t gemm_partials_bytes(const GemmDesc& d, int splits) {
 }
 
 int gemm_pick_splits(const GemmDesc& d) {
-  // only plain multi-panel products with few output tiles and a long contraction benefit
+  // Only plain multi-panel products with few output tiles and a long contraction benefit.  The decision looks at
+  // ONE device's block only (not at the batch count), so that grid mode and device mode sum in the same order
+  // and produce identical bits.
   if (d.dtype != OPTIMUS_BF16 || d.nl < 2 || d.skip_upper || d.k_hi_diag || d.k_lo_diag) return 1;
-  long long nz = (long long)d.nz0 * d.nz1;
-  long long tiles128 = (long long)((d.Mb + 127) / 128) * ((d.Nb + 127) / 128) * nz;
+  long long tiles128 = (long long)((d.Mb + 127) / 128) * ((d.Nb + 127) / 128);
   if (tiles128 >= 192) return 1;
   long long slabs = (long long)d.nl * ((d.Kp + BK - 1) / BK);
   int s = 1;
@@ -407,7 +643,10 @@ int gemm_pick_splits(const GemmDesc& d) {
 
 int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
   if (!gemm_mfma_supported(d)) return OPTIMUS_EINVAL;
-  int vi = pick_variant(d);
+  const bool vec_ok = (d.ldc % 4 == 0) && (d.sC0 % 4 == 0) && (d.sC1 % 4 == 0) && aligned16(d.C) &&
+                      (!d.pre_act || aligned16(d.pre_act)) && (!d.gelu_grad_of || aligned16(d.gelu_grad_of)) &&
+                      (!d.residual || aligned16(d.residual));
+  int vi = pick_variant(d, vec_ok);
   const Variant& v = kVariants[vi];
   KArgs ka;
   ka.A = (const bf16_t*)d.A;
@@ -427,20 +666,18 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
   EpiArgs& e = ka.epi;
   e.alpha = d.alpha; e.bias = d.bias; e.C = d.C; e.pre_act = d.pre_act; e.gelu_grad_of = d.gelu_grad_of;
   e.residual = d.residual; e.ldc = d.ldc; e.act = d.act; e.out_fp32 = d.out_fp32; e.in_bf16 = 1;
-  e.vec_ok = (d.ldc % 4 == 0) && (d.sC0 % 4 == 0) && (d.sC1 % 4 == 0) && aligned16(d.C) &&
-             (!d.pre_act || aligned16(d.pre_act)) && (!d.gelu_grad_of || aligned16(d.gelu_grad_of)) &&
-             (!d.residual || aligned16(d.residual));
+  e.vec_ok = vec_ok ? 1 : 0;
   if (ka.splits > 1 && !d.partials) return OPTIMUS_EWORKSPACE;
   long long nwg = (long long)ka.tiles_m * ka.tiles_n * ka.nz * ka.splits;
   if (nwg <= 0 || nwg > 0x7fffffffLL) return OPTIMUS_ESHAPE;
   int rc;
   switch (vi) {
-    case 0: rc = launch_layout<256, 256, 2, 2, false>(d, ka, nwg, stream); break;
-    case 1: rc = launch_layout<256, 128, 2, 2, false>(d, ka, nwg, stream); break;
-    case 2: rc = launch_layout<128, 256, 2, 2, false>(d, ka, nwg, stream); break;
-    case 3: rc = launch_layout<128, 128, 2, 2, false>(d, ka, nwg, stream); break;
-    case 4: rc = launch_layout<256, 256, 2, 4, false>(d, ka, nwg, stream); break;
-    default: rc = launch_layout<128, 128, 2, 2, true>(d, ka, nwg, stream); break;
+    case 0: rc = launch_layout<256, 256, 2, 4, true>(d, ka, nwg, stream); break;
+    case 1: rc = launch_layout<256, 128, 4, 2, true>(d, ka, nwg, stream); break;
+    case 2: rc = launch_layout<128, 256, 2, 4, true>(d, ka, nwg, stream); break;
+    case 3: rc = launch_layout<128, 128, 2, 2, true>(d, ka, nwg, stream); break;
+    case 4: rc = launch_layout<256, 256, 2, 4, true>(d, ka, nwg, stream); break;
+    default: rc = launch_layout<128, 128, 2, 2, false>(d, ka, nwg, stream); break;
   }
   if (rc != OPTIMUS_OK) return rc;
   if (ka.splits > 1) {
