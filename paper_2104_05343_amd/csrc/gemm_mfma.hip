@@ -600,27 +600,51 @@ static bool variant_fits(const Variant& v, const GemmDesc& d) {
   return 512 * ld < (1LL << 30) && 2 * (long long)d.Kp * ld < (1LL << 30);
 }
 
-static int pick_variant(const GemmDesc& d, bool vec_ok) {
-  if (!vec_ok) return kGuardVariant;  // the fast kernels only have the vector epilogue
-  if (g_variant >= 0 && g_variant < kNumVariants) {
-    if (g_variant == kGuardVariant || variant_fits(kVariants[g_variant], d)) return g_variant;
-  }
-  // estimated cost = rounds of tiles over 256 CUs * (tile area / relative efficiency)
-  static const float eff[4] = {1.0f, 0.85f, 0.85f, 0.7f};
-  long long nz = (long long)d.nz0 * d.nz1;
-  int best = -1;
+// Tile shape and panel split for one product.  The choice looks at ONE device's block only (never at the batch
+// count), so that grid mode and device mode add the same slabs in the same order and give identical bits.
+// Cost model (microseconds, calibrated on MI355X): fixed launch/prologue/epilogue cost, plus the slabs one
+// workgroup walks times the measured time per slab of the variant, times the rounds needed to place all
+// workgroups; a split adds the combine launch and the fp32 partial tiles written once and read once.
+struct Plan {
+  int variant;
+  int splits;
+};
+
+static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
+  Plan best = {kGuardVariant, 1};
+  if (!vec_ok || g_variant == kGuardVariant) return best;  // the fast kernels only have the vector epilogue
+  static const float t_slab[4] = {0.63f, 0.50f, 0.50f, 0.30f};  // us per BK-slab per workgroup, CU not shared
+  static const int wg_per_cu[4] = {1, 1, 1, 2};
+  const long long slabs = (long long)d.nl * (d.Kp / BK);
+  const bool splittable = allow_split && d.nl > 1 && !d.skip_upper && !d.k_hi_diag && !d.k_lo_diag;
   float best_cost = 0.f;
+  bool found = false;
   for (int v = 0; v < 4; ++v) {
+    if (g_variant >= 0 && g_variant < 4 && v != g_variant) continue;
     if (!variant_fits(kVariants[v], d)) continue;
-    long long tiles = (long long)(d.Mb / kVariants[v].BM) * (d.Nb / kVariants[v].BN) * nz * (d.splits > 1 ? d.splits : 1);
-    long long rounds = (tiles + 255) / 256;
-    float cost = (float)rounds * (float)(kVariants[v].BM * kVariants[v].BN) / eff[v];
-    if (best < 0 || cost < best_cost) {
-      best = v;
-      best_cost = cost;
+    const long long tiles = (long long)(d.Mb / kVariants[v].BM) * (d.Nb / kVariants[v].BN);
+    for (int sp = 1; sp <= 8; ++sp) {
+      if (sp > 1 && (!splittable || slabs / sp < 8)) break;
+      const long long wgs = tiles * sp;
+      const long long cap = 256LL * wg_per_cu[v];
+      const long long rounds = (wgs + cap - 1) / cap;
+      const float share = (wg_per_cu[v] == 2 && wgs > 256) ? 1.8f : 1.0f;  // two resident workgroups share the CU
+      const float per_wg = (float)((slabs + sp - 1) / sp) * t_slab[v] * share;
+      const float traffic_us = sp > 1 ? 6.0f + 2.0f * sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f : 0.f;
+      const float cost = 8.0f + (float)rounds * per_wg + traffic_us;
+      if (!found || cost < best_cost) {
+        found = true;
+        best_cost = cost;
+        best = {v, sp};
+      }
     }
   }
-  return best >= 0 ? best : kGuardVariant;
+  return best;
+}
+
+static bool epilogue_vec_ok(const GemmDesc& d) {
+  return (d.ldc % 4 == 0) && (d.sC0 % 4 == 0) && (d.sC1 % 4 == 0) && aligned16(d.C) && (!d.pre_act || aligned16(d.pre_act)) &&
+         (!d.gelu_grad_of || aligned16(d.gelu_grad_of)) && (!d.residual || aligned16(d.residual));
 }
 
 size_t gemm_partials_bytes(const GemmDesc& d, int splits) {
@@ -629,24 +653,16 @@ size_t gemm_partials_bytes(const GemmDesc& d, int splits) {
 }
 
 int gemm_pick_splits(const GemmDesc& d) {
-  // Only plain multi-panel products with few output tiles and a long contraction benefit.  The decision looks at
-  // ONE device's block only (not at the batch count), so that grid mode and device mode sum in the same order
-  // and produce identical bits.
-  if (d.dtype != OPTIMUS_BF16 || d.nl < 2 || d.skip_upper || d.k_hi_diag || d.k_lo_diag) return 1;
-  long long tiles128 = (long long)((d.Mb + 127) / 128) * ((d.Nb + 127) / 128);
-  if (tiles128 >= 192) return 1;
-  long long slabs = (long long)d.nl * ((d.Kp + BK - 1) / BK);
-  int s = 1;
-  while (s * 2 <= d.nl && tiles128 * (s * 2) <= 512 && slabs / (s * 2) >= 8) s *= 2;
-  return s;
+  if (!gemm_mfma_supported(d)) return 1;
+  return make_plan(d, epilogue_vec_ok(d), true).splits;
 }
 
 int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
   if (!gemm_mfma_supported(d)) return OPTIMUS_EINVAL;
-  const bool vec_ok = (d.ldc % 4 == 0) && (d.sC0 % 4 == 0) && (d.sC1 % 4 == 0) && aligned16(d.C) &&
-                      (!d.pre_act || aligned16(d.pre_act)) && (!d.gelu_grad_of || aligned16(d.gelu_grad_of)) &&
-                      (!d.residual || aligned16(d.residual));
-  int vi = pick_variant(d, vec_ok);
+  const bool vec_ok = epilogue_vec_ok(d);
+  // d.splits > 1 means the caller provided the workspace that the planned split asked for
+  const Plan plan = make_plan(d, vec_ok, d.splits > 1 && d.partials != nullptr);
+  const int vi = plan.variant;
   const Variant& v = kVariants[vi];
   KArgs ka;
   ka.A = (const bf16_t*)d.A;
@@ -660,7 +676,7 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
   ka.tiles_m = (d.Mb + v.BM - 1) / v.BM;
   ka.tiles_n = (d.Nb + v.BN - 1) / v.BN;
   ka.skip_upper = d.skip_upper; ka.k_hi_diag = d.k_hi_diag; ka.k_lo_diag = d.k_lo_diag;
-  ka.splits = d.splits > 1 ? d.splits : 1;
+  ka.splits = plan.splits;
   ka.partials = d.partials;
   ka.nz = (long long)d.nz0 * d.nz1;
   EpiArgs& e = ka.epi;
