@@ -27,21 +27,23 @@ __device__ __forceinline__ void store_elem(void* p, long long idx, int bf16, flo
   else ((float*)p)[idx] = v;
 }
 
-// The transcendental parts are kept out of line: the matrix-core kernels unroll this epilogue 64 times per lane and
-// must stay small enough to unroll fully (otherwise the accumulators are forced into scratch memory).
-__device__ __attribute__((noinline)) void gelu4(float t[4]) {
+// GeLU of four values.  EXACT: erff (fp32 kernels, tolerance 1e-5); otherwise the short rational form (bf16 kernels,
+// which unroll this epilogue 64-256 times per lane and must stay small enough to unroll fully).
+template <bool EXACT>
+__device__ __forceinline__ void gelu4(float (&t)[4]) {
 #pragma unroll
-  for (int c = 0; c < 4; ++c) t[c] = gelu_exact(t[c]);
+  for (int c = 0; c < 4; ++c) t[c] = EXACT ? gelu_exact(t[c]) : gelu_fast(t[c]);
 }
-__device__ __attribute__((noinline)) void gelu_grad_mul4(float t[4], const float z[4]) {
+template <bool EXACT>
+__device__ __forceinline__ void gelu_grad_mul4(float (&t)[4], const float (&z)[4]) {
 #pragma unroll
-  for (int c = 0; c < 4; ++c) t[c] *= gelu_grad_exact(z[c]);
+  for (int c = 0; c < 4; ++c) t[c] *= EXACT ? gelu_grad_exact(z[c]) : gelu_grad_fast(z[c]);
 }
 
 // v[0..3]: accumulators of row m, columns n..n+3 (n % 4 == 0); coff: element offset of this batch's C block;
 // nvalid: how many of the four columns exist.  VEC_ONLY: the caller guarantees e.vec_ok and nvalid == 4.
-template <bool VEC_ONLY = false>
-__device__ __forceinline__ void epilogue_store4(const EpiArgs& e, long long coff, int m, int n, float v[4], int nvalid) {
+template <bool VEC_ONLY = false, bool EXACT = false>
+__device__ __forceinline__ void epilogue_store4(const EpiArgs& e, long long coff, int m, int n, const float (&v)[4], int nvalid) {
   long long off = coff + (long long)m * e.ldc + n;
   float t[4];
 #pragma unroll
@@ -62,7 +64,7 @@ __device__ __forceinline__ void epilogue_store4(const EpiArgs& e, long long coff
       for (int c = 0; c < nvalid; ++c) store_elem(e.pre_act, off + c, e.in_bf16, t[c]);
     }
   }
-  if (e.act == 1) gelu4(t);
+  if (e.act == 1) gelu4<EXACT>(t);
   if (e.gelu_grad_of) {
     float z[4] = {0.f, 0.f, 0.f, 0.f};
     if (vec && e.in_bf16) {
@@ -72,7 +74,7 @@ __device__ __forceinline__ void epilogue_store4(const EpiArgs& e, long long coff
     } else if (!VEC_ONLY) {
       for (int c = 0; c < nvalid; ++c) z[c] = load_elem(e.gelu_grad_of, off + c, e.in_bf16);
     }
-    gelu_grad_mul4(t, z);
+    gelu_grad_mul4<EXACT>(t, z);
   }
   if (e.residual) {
     float r[4] = {0.f, 0.f, 0.f, 0.f};

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GArgs a) {
   for (int r = 0; r < 4; ++r) {
     int m = m0 + ty * 4 + r, n = n0 + tx * 4;
     if (m >= a.Mb || n >= a.Nb) continue;
-    epilogue_store4(e, coff, m, n, acc[r], min(4, a.Nb - n));
+    epilogue_store4<false, true>(e, coff, m, n, acc[r], min(4, a.Nb - n));
   }
 }
 

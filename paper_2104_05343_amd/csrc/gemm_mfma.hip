@@ -65,12 +65,16 @@ struct KArgs {
 // time (16 consecutive rows, one chunk each): four 64-byte rows span the 64 banks, so the XOR term must take 4
 // distinct values over the 4 rows of equal (row & 3) -> (row >> 2) & 3.  A ds_read_b64_tr_b16 is served 32 lanes at
 // a time (4 k-rows x two adjacent 32-byte granules): rows start at bank 0, so the 8 (k, granule) pairs must fall in
-// 8 distinct granule slots -> XOR with 2 * (k & 3).  Measured with a read-only microbenchmark: > 200 B/clk for
+// 8 distinct granule slots -> XOR with 2 * (k & 3) (masked to the row's granule count for 64-wide tiles).  Measured with a read-only microbenchmark: > 200 B/clk for
 // these patterns against 128 B/clk for swizzles designed for 32 banks.
 __device__ __forceinline__ int lds_off_kc(int row, int chunk) { return row * BK + ((chunk ^ ((row >> 2) & 3)) << 3); }
+// k-contiguous operand on the fast path: two slabs side by side, [row][64 k] = 128 bytes per row, so that one row
+// of a load is a whole 128-byte cache line.  Two rows span the 64 banks: the XOR term takes 8 values over the 8 row
+// pairs of a 16-lane group.
+__device__ __forceinline__ int lds_off_kc2(int row, int chunk) { return row * (2 * BK) + ((chunk ^ ((row >> 1) & 7)) << 3); }
 template <int ROWS>
 __device__ __forceinline__ int lds_off_ks(int krow, int col) {
-  return krow * ROWS + ((((col >> 4) ^ ((krow & 3) << 1))) << 4) + (col & 15);
+  return krow * ROWS + ((((col >> 4) ^ (((krow & 3) << 1) & (ROWS / 16 - 1)))) << 4) + (col & 15);
 }
 
 // ---- FAST path: direct global -> LDS, one KiB per wavefront instruction ----
@@ -82,20 +86,22 @@ struct DirectPlan {
 };
 
 // Per-lane source offsets (BYTES, relative to the slab origin) of the KiB chunks this wavefront moves.
+// k-contiguous operand: the unit is a PAIR of slabs (64 k): 8 rows of 128 bytes per instruction.
+// k-strided operand: the unit is one slab of 32 k-rows.
 template <int ROWS, bool KC, int NW, int PER>
 __device__ __forceinline__ void direct_offsets(unsigned (&off)[PER], int ld, int wave, int lane) {
 #pragma unroll
   for (int it = 0; it < PER; ++it) {
     const int q = wave * PER + it;
     if (KC) {
-      const int row = q * 16 + (lane >> 2);
-      const int kc = (lane & 3) ^ ((row >> 2) & 3);  // inverse of lds_off_kc for LDS position (row, lane & 3)
+      const int row = q * 8 + (lane >> 3);
+      const int kc = (lane & 7) ^ ((row >> 1) & 7);  // inverse of lds_off_kc2 for LDS position (row, lane & 7)
       off[it] = (unsigned)(row * ld + kc * 8) * 2u;
     } else {
       constexpr int PPR = ROWS / 8;  // 16-byte pieces per k-row
       const int idx = q * 64 + lane;
       const int krow = idx / PPR, pp = idx % PPR;
-      const int col = ((((pp >> 1) ^ ((krow & 3) << 1))) << 4) + ((pp & 1) << 3);  // inverse of lds_off_ks
+      const int col = ((((pp >> 1) ^ (((krow & 3) << 1) & (ROWS / 16 - 1)))) << 4) + ((pp & 1) << 3);  // inverse of lds_off_ks
       off[it] = (unsigned)(krow * ld + col) * 2u;
     }
   }
@@ -125,9 +131,24 @@ __device__ __forceinline__ void direct_issue(i32x4 rsrc, unsigned soff, const un
   }
 }
 
+// one KiB chunk (number c of the operand's issue unit) with this lane's offset
+__device__ __forceinline__ void direct_issue_one(i32x4 rsrc, unsigned soff, unsigned off, bf16_t* lds_unit, int c) {
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)lds_unit;
+  const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)c * 1024u);
+  asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds" ::"v"(off), "s"(rsrc), "s"(soff), "s"(m0v)
+               : "memory");
+}
+
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt left at their maxima), gfx9 encoding.  The builtin rather than inline
 // assembly: the compiler's own wait-count pass then knows which LDS loads have landed and adds no full drain.
 constexpr int waitcnt_vm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }  // + lgkmcnt(0)
+#define OPTIMUS_WAIT_VMCNT_LGKM0(n)                      \
+  do {                                                   \
+    asm volatile("" ::: "memory");                       \
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(n));     \
+    asm volatile("" ::: "memory");                       \
+  } while (0)
 #define OPTIMUS_WAIT_VMCNT(n)                      \
   do {                                             \
     asm volatile("" ::: "memory");                 \
@@ -228,6 +249,52 @@ __device__ __forceinline__ void sched_interleave() {
   }
 }
 
+// Fast-path fragment: the operand's LDS ring holds four slabs.  A k-strided operand keeps four [32][ROWS] stages;
+// a k-contiguous one keeps two [ROWS][64] pairs, slab s4 being half (s4 & 1) of pair (s4 >> 1).
+template <int ROWS, bool KC>
+__device__ __forceinline__ bf16x8 read_frag_ring(const bf16_t* ring, int s4, int rc0, int ks, int lane) {
+  if (KC) {
+    const bf16_t* pair = ring + (s4 >> 1) * (2 * ROWS * BK);
+    return *(const bf16x8*)(pair + lds_off_kc2(rc0 + (lane & 31), (s4 & 1) * 4 + ks * 2 + (lane >> 5)));
+  } else {
+    return read_frag<ROWS, false>(ring + s4 * (ROWS * BK), rc0, ks, lane);
+  }
+}
+// Fragment set of one 16-wide sub-step (MI A-fragments, NI B-fragments) and the MFMAs that consume it.
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC>
+__device__ __forceinline__ void load_frags(bf16x8 (&fa)[BM / WM / 32], bf16x8 (&fb)[BN / WN / 32], const bf16_t* ringA,
+                                           const bf16_t* ringB, int s4, int ks, int wm, int wn, int lane) {
+  using T = Tile<BM, BN, WM, WN>;
+#pragma unroll
+  for (int mi = 0; mi < T::MI; ++mi) fa[mi] = read_frag_ring<BM, AKC>(ringA, s4, wm * T::TM + mi * 32, ks, lane);
+#pragma unroll
+  for (int ni = 0; ni < T::NI; ++ni) fb[ni] = read_frag_ring<BN, BKC>(ringB, s4, wn * T::TN + ni * 32, ks, lane);
+}
+// fragment R of a sub-step: R < MI -> A fragment R, else B fragment R - MI; nothing beyond MI + NI
+template <int R, int BM, int BN, int WM, int WN, bool AKC, bool BKC>
+__device__ __forceinline__ void load_frag_r(bf16x8 (&fa)[BM / WM / 32], bf16x8 (&fb)[BN / WN / 32], const bf16_t* ringA,
+                                            const bf16_t* ringB, int s4, int ks, int wm, int wn, int lane) {
+  using T = Tile<BM, BN, WM, WN>;
+  if constexpr (R < T::MI) fa[R] = read_frag_ring<BM, AKC>(ringA, s4, wm * T::TM + R * 32, ks, lane);
+  else if constexpr (R < T::MI + T::NI) fb[R - T::MI] = read_frag_ring<BN, BKC>(ringB, s4, wn * T::TN + (R - T::MI) * 32, ks, lane);
+}
+// MFMA number M of a sub-step (row-major over the MI x NI accumulators)
+template <int M, int MI, int NI>
+__device__ __forceinline__ void mfma_m(f32x16 (&acc)[MI][NI], const bf16x8 (&fa)[MI], const bf16x8 (&fb)[NI]) {
+  constexpr int mi = M / NI, ni = M % NI;
+  acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0);
+}
+// slot (0 .. MF-1) in front of whose MFMA load G of GN is issued: spread evenly over the sub-step
+constexpr int dma_slot(int g, int gn, int mf) { return ((2 * g + 1) * mf) / (2 * gn); }
+
+template <int MI, int NI>
+__device__ __forceinline__ void mma_step(f32x16 (&acc)[MI][NI], const bf16x8 (&fa)[MI], const bf16x8 (&fb)[NI]) {
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0);
+}
+
 // One slab of MFMAs from LDS.  Software pipeline over the four 16-wide sub-steps: the fragments of sub-step
 // ks+1 are requested while the MFMAs of sub-step ks run (their operands were requested one sub-step earlier).
 template <int BM, int BN, int WM, int WN, bool AKC, bool BKC>
@@ -281,16 +348,9 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
   using T = Tile<BM, BN, WM, WN>;
   constexpr int THREADS = T::THREADS, NW = T::NW;
   constexpr int TM = T::TM, TN = T::TN, MI = T::MI, NI = T::NI;
-  // the stages are separate LDS objects: the compiler can then see that a load into one stage does not alias
-  // the fragment reads of another and does not serialise them
-  __shared__ __attribute__((aligned(1024))) bf16_t sA0[T::A_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB0[T::B_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sA1[T::A_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB1[T::B_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sA2[T::A_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB2[T::B_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sA3[T::A_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t sB3[T::B_ELEMS];
+  // one ring of four slabs per operand (see read_frag_ring); the ragged path uses the first two slabs as two stages
+  __shared__ __attribute__((aligned(1024))) bf16_t ldsA[(FAST ? NSTAGE : 2) * T::A_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t ldsB[(FAST ? NSTAGE : 2) * T::B_ELEMS];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -339,6 +399,7 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
   if (a.splits > 1) {
     int total = t_hi - t_lo;
     int per = (total + a.splits - 1) / a.splits;
+    per = (per + 1) & ~1;  // the fast path walks slabs in pairs
     int lo = t_lo + split * per;
     t_hi = min(t_hi, lo + per);
     t_lo = lo;
@@ -359,72 +420,213 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
     // slab index -> (panel l, offset k0 inside the panel); advanced incrementally
     int l = t_lo / tpp, k0 = (t_lo - l * tpp) * BK;
     if constexpr (FAST) {
-      constexpr int PA = DirectPlan<BM, NW>::PER, PB = DirectPlan<BN, NW>::PER;
-      constexpr int LPS = PA + PB;  // load instructions per wavefront per slab
+      // Loads per wavefront: a k-strided operand moves one slab per step; a k-contiguous operand moves a pair of
+      // slabs (whole 128-byte lines per row) every second step.  The slab count of a workgroup is even (host).
+      constexpr int PA1 = DirectPlan<BM, NW>::PER, PB1 = DirectPlan<BN, NW>::PER;
+      constexpr int PA = AKC ? 2 * PA1 : PA1, PB = BKC ? 2 * PB1 : PB1;
+      constexpr int PKS = (AKC ? 0 : PA1) + (BKC ? 0 : PB1);          // loads of one k-strided slab issue
+      constexpr int PKC2 = (AKC ? 2 * PA1 : 0) + (BKC ? 2 * PB1 : 0);  // loads of one k-contiguous pair issue
       unsigned offA[PA], offB[PB];
       direct_offsets<BM, AKC, NW, PA>(offA, a.lda, wave, lane);
       direct_offsets<BN, BKC, NW, PB>(offB, a.ldb, wave, lane);
-      const unsigned stepA = (unsigned)(AKC ? BK : BK * a.lda) * 2u;  // slab-to-slab byte advance inside a panel
-      const unsigned stepB = (unsigned)(BKC ? BK : BK * a.ldb) * 2u;
-      // load cursor: panel lq, k offset kq, one buffer resource per panel, byte offsets inside the panel
-      int lq = l, kq = k0;
-      i32x4 ra = make_rsrc(Atile + lq * a.sAl), rb = make_rsrc(Btile + lq * a.sBl);
-      unsigned sa = (unsigned)(AKC ? kq : kq * a.lda) * 2u, sb = (unsigned)(BKC ? kq : kq * a.ldb) * 2u;
+      // one load cursor per operand: panel, k offset, buffer resource of the panel, byte offset inside the panel
+      constexpr int KA = AKC ? 2 * BK : BK, KB = BKC ? 2 * BK : BK;  // k advance per issue
+      const unsigned stepA = (unsigned)(AKC ? KA : KA * a.lda) * 2u;
+      const unsigned stepB = (unsigned)(BKC ? KB : KB * a.ldb) * 2u;
+      int lqa = l, kqa = k0, lqb = l, kqb = k0;
+      i32x4 ra = make_rsrc(Atile + lqa * a.sAl), rb = make_rsrc(Btile + lqb * a.sBl);
+      unsigned sa = (unsigned)(AKC ? kqa : kqa * a.lda) * 2u, sb = (unsigned)(BKC ? kqb : kqb * a.ldb) * 2u;
       const int nslab = t_hi - t_lo;
-      int issued = 0;
-#define OPTIMUS_ISSUE(SA, SB)                                                        \
+#define OPTIMUS_ISSUE_A(DST)                                                         \
   do {                                                                               \
-    direct_issue<BM, NW, PA>(ra, sa, offA, SA, wave);                                \
-    direct_issue<BN, NW, PB>(rb, sb, offB, SB, wave);                                \
-    ++issued;                                                                        \
-    kq += BK;                                                                        \
-    if (kq >= a.Kp) {                                                                \
-      kq = 0; ++lq; sa = 0; sb = 0;                                                  \
-      ra = make_rsrc(Atile + lq * a.sAl); rb = make_rsrc(Btile + lq * a.sBl);        \
-    } else { sa += stepA; sb += stepB; }                                             \
+    direct_issue<BM, NW, PA>(ra, sa, offA, DST, wave);                               \
+    kqa += KA;                                                                       \
+    if (kqa >= a.Kp) { kqa = 0; ++lqa; sa = 0; ra = make_rsrc(Atile + lqa * a.sAl); } \
+    else sa += stepA;                                                                \
   } while (0)
-      // One pipeline step: slab i is resident in (SA, SB); refill the stage that held slab i-1 with slab i+3;
-      // multiply; then make sure slab i+1 has landed (leaving the younger loads in flight) and meet the others.
-#define OPTIMUS_STEP(SA, SB, PA_, PB_)                                               \
+#define OPTIMUS_ISSUE_B(DST)                                                         \
   do {                                                                               \
-    if (issued < nslab) OPTIMUS_ISSUE(PA_, PB_);                                     \
-    compute_slab<BM, BN, WM, WN, AKC, BKC>(acc, SA, SB, wm, wn, lane);               \
-    const int younger = issued - (i + 2); /* slabs beyond i+1 already requested */   \
-    if (younger >= 2) OPTIMUS_WAIT_VMCNT(2 * LPS);                                   \
-    else if (younger == 1) OPTIMUS_WAIT_VMCNT(LPS);                                  \
-    else OPTIMUS_WAIT_VMCNT(0);                                                      \
-    OPTIMUS_BARRIER();                                                               \
-    ++i;                                                                             \
+    direct_issue<BN, NW, PB>(rb, sb, offB, DST, wave);                               \
+    kqb += KB;                                                                       \
+    if (kqb >= a.Kp) { kqb = 0; ++lqb; sb = 0; rb = make_rsrc(Btile + lqb * a.sBl); } \
+    else sb += stepB;                                                                \
   } while (0)
-      // prologue: slabs 0..2
-      OPTIMUS_ISSUE(sA0, sB0);
-      if (issued < nslab) OPTIMUS_ISSUE(sA1, sB1);
-      if (issued < nslab) OPTIMUS_ISSUE(sA2, sB2);
-      if (issued >= 3) OPTIMUS_WAIT_VMCNT(2 * LPS);
-      else if (issued == 2) OPTIMUS_WAIT_VMCNT(LPS);
-      else OPTIMUS_WAIT_VMCNT(0);
+      // pair P (0/1) of the k-contiguous operands; slab S (0..3) of the k-strided ones
+#define OPTIMUS_ISSUE_KC(P)                                                          \
+  do {                                                                               \
+    if constexpr (AKC) OPTIMUS_ISSUE_A(ldsA + (P) * 2 * T::A_ELEMS);                 \
+    if constexpr (BKC) OPTIMUS_ISSUE_B(ldsB + (P) * 2 * T::B_ELEMS);                 \
+  } while (0)
+#define OPTIMUS_ISSUE_KS(S)                                                          \
+  do {                                                                               \
+    if constexpr (!AKC) OPTIMUS_ISSUE_A(ldsA + (S) * T::A_ELEMS);                    \
+    if constexpr (!BKC) OPTIMUS_ISSUE_B(ldsB + (S) * T::B_ELEMS);                    \
+  } while (0)
+      // Continuous pipeline over 16-wide sub-steps; F0 = (fa0, fb0) holds sub-step 0 of the current slab i.
+      //   A  sub-step 0: MFMAs on F0; between them the fragment reads of sub-step 1 (F1) and the second half of the
+      //      loads of the group opened in the previous step;
+      //   B  wait for F1 (after it this wavefront reads slab i no more) and for the loads slab i+1 needs, leaving the
+      //      younger ones in flight; barrier: nobody reads slab i any more, slab i+1 is complete in LDS;
+      //   C  open the group that refills what slab i freed: its stage for the k-strided operands (slab i+4); after an
+      //      odd slab also its pair for the k-contiguous operands (slabs i+3, i+4);
+      //   D  sub-step 1: MFMAs on F1; between them the reads of sub-step 0 of slab i+1 (F0) and the first half of
+      //      the group's loads.
+      // The loads are spread between the MFMAs one by one: issued in one burst after the barrier they fill the
+      // CU's memory-instruction queue, and a wavefront stalled on a full queue issues no MFMA either.
+      // Loads retire in issue order.  Issue order is [pair 0, slab 0, slab 1, pair 1, slab 2, slab 3], then per even
+      // step [slab i+4], per odd step [pair, slab i+4]; the wait counts below are the loads younger than what slab
+      // i+1 needs in that order (at B of step i everything up to the group of step i-1 has been issued).
+      constexpr int MF = MI * NI;
+      constexpr int NF = MI + NI;                                   // fragments per sub-step
+      constexpr int FPS = (NF + MF / 2 - 1) / (MF / 2 > 0 ? MF / 2 : 1);  // fragments requested per MFMA slot
+      static_assert(BK == 32 && NSTAGE == 4, "the pipeline below is written for two sub-steps per slab, four slabs");
+      static_assert(MF <= 16 && FPS <= 3 && PA + PB <= 16, "slot and load lists below");
+      constexpr int G_ODD = PA + PB, G_EVEN = PKS;  // loads per group
+      bf16x8 fa0[MI], fb0[NI], fa1[MI], fb1[NI];
+      bool pend = false;  // the group opened in the previous step still has its second half to issue
+      // load N of the group of parity ODD refilling slab S's space: A's chunks first, then B's
+#define OPTIMUS_DMA_N(ODD, S, N)                                                                                  \
+  do {                                                                                                            \
+    constexpr int nA_ = (ODD) ? PA : (AKC ? 0 : PA);                                                              \
+    constexpr int nB_ = (ODD) ? PB : (BKC ? 0 : PB);                                                              \
+    if constexpr ((N) < nA_)                                                                                      \
+      direct_issue_one(ra, sa, offA[(N) < nA_ ? (N) : 0], ldsA + (AKC ? ((S) >> 1) * 2 : (S)) * T::A_ELEMS,       \
+                       wave * PA + (N));                                                                          \
+    else if constexpr ((N) < nA_ + nB_)                                                                           \
+      direct_issue_one(rb, sb, offB[(N) >= nA_ && (N) < nA_ + nB_ ? (N) - nA_ : 0],                               \
+                       ldsB + (BKC ? ((S) >> 1) * 2 : (S)) * T::B_ELEMS, wave * PB + (N) - nA_);                  \
+  } while (0)
+      // in slot M: the loads G0 .. G0+GN-1 of the group whose turn it is
+#define OPTIMUS_DMA_SLOT(M, ODD, S, G0, GN, DO)                                                                   \
+  do {                                                                                                            \
+    if constexpr ((GN) > 0) {                                                                                     \
+      if constexpr (dma_slot(0, (GN) > 0 ? (GN) : 1, MF) == (M)) { if (DO) OPTIMUS_DMA_N(ODD, S, (G0) + 0); }     \
+      if constexpr ((GN) > 1 && dma_slot(1, (GN) > 0 ? (GN) : 1, MF) == (M)) { if (DO) OPTIMUS_DMA_N(ODD, S, (G0) + 1); }\
+      if constexpr ((GN) > 2 && dma_slot(2, (GN) > 0 ? (GN) : 1, MF) == (M)) { if (DO) OPTIMUS_DMA_N(ODD, S, (G0) + 2); }\
+      if constexpr ((GN) > 3 && dma_slot(3, (GN) > 0 ? (GN) : 1, MF) == (M)) { if (DO) OPTIMUS_DMA_N(ODD, S, (G0) + 3); }\
+      if constexpr ((GN) > 4 && dma_slot(4, (GN) > 0 ? (GN) : 1, MF) == (M)) { if (DO) OPTIMUS_DMA_N(ODD, S, (G0) + 4); }\
+      if constexpr ((GN) > 5 && dma_slot(5, (GN) > 0 ? (GN) : 1, MF) == (M)) { if (DO) OPTIMUS_DMA_N(ODD, S, (G0) + 5); }\
+      if constexpr ((GN) > 6 && dma_slot(6, (GN) > 0 ? (GN) : 1, MF) == (M)) { if (DO) OPTIMUS_DMA_N(ODD, S, (G0) + 6); }\
+      if constexpr ((GN) > 7 && dma_slot(7, (GN) > 0 ? (GN) : 1, MF) == (M)) { if (DO) OPTIMUS_DMA_N(ODD, S, (G0) + 7); }\
+    }                                                                                                             \
+  } while (0)
+#define OPTIMUS_SLOT(M, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO)                              \
+  do {                                                                                                            \
+    if constexpr ((M) < MF) {                                                                                     \
+      load_frag_r<(M) * FPS, BM, BN, WM, WN, AKC, BKC>(FA_LD, FB_LD, ldsA, ldsB, S_LD, KS_LD, wm, wn, lane); \
+      load_frag_r<((FPS > 1) ? (M) * FPS + 1 : NF), BM, BN, WM, WN, AKC, BKC>(FA_LD, FB_LD, ldsA, ldsB, S_LD, KS_LD, wm, wn, lane); \
+      load_frag_r<((FPS > 2) ? (M) * FPS + 2 : NF), BM, BN, WM, WN, AKC, BKC>(FA_LD, FB_LD, ldsA, ldsB, S_LD, KS_LD, wm, wn, lane); \
+      OPTIMUS_DMA_SLOT(M, ODD, S, G0, GN, DO);                                                                    \
+      mfma_m<(((M) < MF) ? (M) : 0), MI, NI>(acc, FA_MM, FB_MM);                                                      \
+      __builtin_amdgcn_sched_barrier(0);                                                                          \
+    }                                                                                                             \
+  } while (0)
+#define OPTIMUS_HALF(FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO)                                 \
+  do {                                                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                            \
+    OPTIMUS_SLOT(0, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(1, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(2, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(3, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(4, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(5, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(6, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(7, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(8, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(9, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                 \
+    OPTIMUS_SLOT(10, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                \
+    OPTIMUS_SLOT(11, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                \
+    OPTIMUS_SLOT(12, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                \
+    OPTIMUS_SLOT(13, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                \
+    OPTIMUS_SLOT(14, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                \
+    OPTIMUS_SLOT(15, FA_LD, FB_LD, S_LD, KS_LD, FA_MM, FB_MM, ODD, S, G0, GN, DO);                                \
+  } while (0)
+      // cursor advance once a group is out: every operand that had loads in it
+#define OPTIMUS_ADVANCE(ODD)                                                                  \
+  do {                                                                                        \
+    if constexpr ((ODD) || !AKC) {                                                            \
+      kqa += KA;                                                                              \
+      if (kqa >= a.Kp) { kqa = 0; ++lqa; sa = 0; ra = make_rsrc(Atile + lqa * a.sAl); }       \
+      else sa += stepA;                                                                       \
+    }                                                                                         \
+    if constexpr ((ODD) || !BKC) {                                                            \
+      kqb += KB;                                                                              \
+      if (kqb >= a.Kp) { kqb = 0; ++lqb; sb = 0; rb = make_rsrc(Btile + lqb * a.sBl); }       \
+      else sb += stepB;                                                                       \
+    }                                                                                         \
+  } while (0)
+      // S = slab position (0..3) of slab i; the previous step's group refills position (S + 3) & 3
+#define OPTIMUS_STEP_EVEN(S)                                                                                      \
+  do {                                                                                                            \
+    OPTIMUS_HALF(fa1, fb1, S, 1, fa0, fb0, true, ((S) + 3) & 3, (G_ODD + 1) / 2, G_ODD / 2, pend);                \
+    if (pend) OPTIMUS_ADVANCE(true);                                                                              \
+    pend = false;                                                                                                 \
+    if constexpr (PKS > 0) { /* all k-contiguous: slab i+1 came with slab i, nothing to hand over */              \
+      if (i + 2 < nslab) OPTIMUS_WAIT_VMCNT_LGKM0(2 * PKS + PKC2);                                                \
+      else OPTIMUS_WAIT_VMCNT_LGKM0(0);                                                                           \
+      OPTIMUS_BARRIER();                                                                                          \
+      pend = i + 4 < nslab;                                                                                       \
+    }                                                                                                             \
+    OPTIMUS_HALF(fa0, fb0, (S) + 1, 0, fa1, fb1, false, S, 0, (G_EVEN + 1) / 2, pend);                            \
+    ++i;                                                                                                          \
+  } while (0)
+#define OPTIMUS_STEP_ODD(S)                                                                                       \
+  do {                                                                                                            \
+    OPTIMUS_HALF(fa1, fb1, S, 1, fa0, fb0, false, (S) - 1, (G_EVEN + 1) / 2, G_EVEN / 2, pend);                   \
+    if (pend) OPTIMUS_ADVANCE(false);                                                                             \
+    if (i + 3 < nslab) OPTIMUS_WAIT_VMCNT_LGKM0(2 * PKS);                                                         \
+    else if (i + 2 < nslab) OPTIMUS_WAIT_VMCNT_LGKM0(PKS);                                                        \
+    else OPTIMUS_WAIT_VMCNT_LGKM0(0);                                                                             \
+    OPTIMUS_BARRIER();                                                                                            \
+    pend = i + 3 < nslab;                                                                                         \
+    /* after the last slab this reads a slab nobody writes any more; the values are never used */                \
+    OPTIMUS_HALF(fa0, fb0, ((S) + 1) & 3, 0, fa1, fb1, true, S, 0, (G_ODD + 1) / 2, pend);                        \
+    ++i;                                                                                                          \
+  } while (0)
+      // prologue: whole groups at once
+      OPTIMUS_ISSUE_KC(0);
+      OPTIMUS_ISSUE_KS(0);
+      OPTIMUS_ISSUE_KS(1);
+      if (nslab > 2) {
+        OPTIMUS_ISSUE_KC(1);
+        OPTIMUS_ISSUE_KS(2);
+        OPTIMUS_ISSUE_KS(3);
+        OPTIMUS_WAIT_VMCNT(PKC2 + 2 * PKS);
+      } else {
+        OPTIMUS_WAIT_VMCNT(0);
+      }
       OPTIMUS_BARRIER();
+      load_frags<BM, BN, WM, WN, AKC, BKC>(fa0, fb0, ldsA, ldsB, 0, 0, wm, wn, lane);
       int i = 0;
       while (i + 4 <= nslab) {
-        OPTIMUS_STEP(sA0, sB0, sA3, sB3);
-        OPTIMUS_STEP(sA1, sB1, sA0, sB0);
-        OPTIMUS_STEP(sA2, sB2, sA1, sB1);
-        OPTIMUS_STEP(sA3, sB3, sA2, sB2);
+        OPTIMUS_STEP_EVEN(0);
+        OPTIMUS_STEP_ODD(1);
+        OPTIMUS_STEP_EVEN(2);
+        OPTIMUS_STEP_ODD(3);
       }
-      // tail: up to three slabs, already requested (issued == nslab by now)
-      if (i < nslab) OPTIMUS_STEP(sA0, sB0, sA3, sB3);
-      if (i < nslab) OPTIMUS_STEP(sA1, sB1, sA0, sB0);
-      if (i < nslab) OPTIMUS_STEP(sA2, sB2, sA1, sB1);
-#undef OPTIMUS_STEP
-#undef OPTIMUS_ISSUE
+      if (i < nslab) {  // one pair left
+        OPTIMUS_STEP_EVEN(0);
+        OPTIMUS_STEP_ODD(1);
+      }
+#undef OPTIMUS_STEP_EVEN
+#undef OPTIMUS_STEP_ODD
+#undef OPTIMUS_HALF
+#undef OPTIMUS_SLOT
+#undef OPTIMUS_DMA_SLOT
+#undef OPTIMUS_DMA_N
+#undef OPTIMUS_ADVANCE
+#undef OPTIMUS_ISSUE_KS
+#undef OPTIMUS_ISSUE_KC
+#undef OPTIMUS_ISSUE_A
+#undef OPTIMUS_ISSUE_B
     } else {
       u32x4 ra[StageDims<BM, THREADS>::PER];
       u32x4 rb[StageDims<BN, THREADS>::PER];
       const int rowsA = a.Mb - m0, rowsB = a.Nb - n0;
       stage_load<BM, AKC, THREADS>(ra, Atile + l * a.sAl, a.lda, k0, rowsA, a.Kp - k0, tid);
       stage_load<BN, BKC, THREADS>(rb, Btile + l * a.sBl, a.ldb, k0, rowsB, a.Kp - k0, tid);
-      stage_store<BM, AKC, THREADS>(ra, sA0, tid);
-      stage_store<BN, BKC, THREADS>(rb, sB0, tid);
+      stage_store<BM, AKC, THREADS>(ra, ldsA, tid);
+      stage_store<BN, BKC, THREADS>(rb, ldsB, tid);
       __syncthreads();
       for (int tt = t_lo; tt < t_hi; ++tt) {
         const int cur = (tt - t_lo) & 1;
@@ -435,11 +637,11 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
           stage_load<BM, AKC, THREADS>(ra, Atile + l * a.sAl, a.lda, k0, rowsA, a.Kp - k0, tid);
           stage_load<BN, BKC, THREADS>(rb, Btile + l * a.sBl, a.ldb, k0, rowsB, a.Kp - k0, tid);
         }
-        if (cur == 0) compute_slab<BM, BN, WM, WN, AKC, BKC>(acc, sA0, sB0, wm, wn, lane);
-        else compute_slab<BM, BN, WM, WN, AKC, BKC>(acc, sA1, sB1, wm, wn, lane);
+        if (cur == 0) compute_slab<BM, BN, WM, WN, AKC, BKC>(acc, ldsA, ldsB, wm, wn, lane);
+        else compute_slab<BM, BN, WM, WN, AKC, BKC>(acc, (ldsA + T::A_ELEMS), (ldsB + T::B_ELEMS), wm, wn, lane);
         if (more) {
-          stage_store<BM, AKC, THREADS>(ra, cur == 0 ? sA1 : sA0, tid);
-          stage_store<BN, BKC, THREADS>(rb, cur == 0 ? sB1 : sB0, tid);
+          stage_store<BM, AKC, THREADS>(ra, cur == 0 ? (ldsA + T::A_ELEMS) : ldsA, tid);
+          stage_store<BN, BKC, THREADS>(rb, cur == 0 ? (ldsB + T::B_ELEMS) : ldsB, tid);
         }
         __syncthreads();
       }
@@ -498,6 +700,63 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
         crow += 32LL * e.ldc;
       }
     }
+  } else if constexpr (FAST) {
+    // General epilogue, vector form (bf16 in, 8- or 16-byte accesses; the host has checked the alignments).
+    // Everything it reads is requested in batches ahead of the stores: the compiler cannot prove that C aliases
+    // none of the inputs, so a load written after a store waits for it, and 16 * MI * NI dependent round trips
+    // to memory would cost more than the product itself.
+    const float* bias = e.bias ? e.bias + z0 * a.sBias0 + n0 + wn * TN + ((lane >> 5) << 2) : nullptr;
+    float4 b4[NI][4];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) b4[ni][g] = bias ? *(const float4*)(bias + ni * 32 + g * 8) : make_float4(0.f, 0.f, 0.f, 0.f);
+    const long long first = coff + (long long)(m0 + wm * TM + (lane & 31)) * e.ldc + n0 + wn * TN + ((lane >> 5) << 2);
+    const bf16_t* zrow = e.gelu_grad_of ? (const bf16_t*)e.gelu_grad_of + first : nullptr;
+    const bf16_t* rrow = e.residual ? (const bf16_t*)e.residual + first : nullptr;
+    bf16_t* prow = e.pre_act ? (bf16_t*)e.pre_act + first : nullptr;
+    const bool act = e.act == 1, out32 = e.out_fp32 != 0;
+    const float alpha = e.alpha;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const long long ro = (long long)mi * 32 * e.ldc;
+      uint2 zz[NI][4], rr[NI][4];
+      if (zrow) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) zz[ni][g] = *(const uint2*)(zrow + ro + ni * 32 + g * 8);
+      }
+      if (rrow) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) rr[ni][g] = *(const uint2*)(rrow + ro + ni * 32 + g * 8);
+      }
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float t[4] = {acc[mi][ni][g * 4] * alpha + b4[ni][g].x, acc[mi][ni][g * 4 + 1] * alpha + b4[ni][g].y,
+                        acc[mi][ni][g * 4 + 2] * alpha + b4[ni][g].z, acc[mi][ni][g * 4 + 3] * alpha + b4[ni][g].w};
+          const long long o = ro + ni * 32 + g * 8;
+          if (prow) *(uint2*)(prow + o) = make_uint2(pack2_bf16(t[0], t[1]), pack2_bf16(t[2], t[3]));
+          if (act) gelu4<false>(t);
+          if (zrow) {
+            const uint2 w = zz[ni][g];
+            const float z[4] = {__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                                __uint_as_float(w.y & 0xffff0000u)};
+            gelu_grad_mul4<false>(t, z);
+          }
+          if (rrow) {
+            const uint2 w = rr[ni][g];
+            t[0] += __uint_as_float(w.x << 16); t[1] += __uint_as_float(w.x & 0xffff0000u);
+            t[2] += __uint_as_float(w.y << 16); t[3] += __uint_as_float(w.y & 0xffff0000u);
+          }
+          if (out32) *(float4*)((float*)e.C + first + o) = make_float4(t[0], t[1], t[2], t[3]);
+          else *(uint2*)((bf16_t*)e.C + first + o) = make_uint2(pack2_bf16(t[0], t[1]), pack2_bf16(t[2], t[3]));
+        }
+    }
   } else {
     if (e.bias) e.bias += z0 * a.sBias0;
 #pragma unroll
@@ -508,10 +767,9 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
         for (int g = 0; g < 4; ++g) {
           const int m = m0 + wm * TM + mi * 32 + (lane & 31);
           const int n = n0 + wn * TN + ni * 32 + g * 8 + ((lane >> 5) << 2);
-          if (!FAST && (m >= a.Mb || n >= a.Nb)) continue;
-          float v[4] = {acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]};
-          const int nvalid = FAST ? 4 : min(4, a.Nb - n);
-          epilogue_store4<FAST>(e, coff, m, n, v, nvalid);
+          if (m >= a.Mb || n >= a.Nb) continue;
+          const float v[4] = {acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]};
+          epilogue_store4<false>(e, coff, m, n, v, min(4, a.Nb - n));
         }
   }
 #endif  // __HIP_DEVICE_COMPILE__
@@ -532,9 +790,19 @@ __global__ __launch_bounds__(256) void gemm_combine_kernel(const float* partials
   int n = nq * 4;
   int nvalid = min(4, Nb - n);
   float v[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < splits; ++s) {
-    const float* p = partials + ((long long)s * nz + z) * (long long)Mb * Nb + (long long)m * Nb + n;
-    for (int c = 0; c < nvalid; ++c) v[c] += p[c];
+  if ((Nb & 3) == 0 && ((size_t)partials & 15) == 0) {  // rows of the partial tiles are 16-byte aligned: one load per split, all in flight together
+    const float* p = partials + z * (long long)Mb * Nb + (long long)m * Nb + n;
+    const long long sstride = nz * (long long)Mb * Nb;
+#pragma unroll 8
+    for (int s = 0; s < splits; ++s) {
+      const float4 w = *(const float4*)(p + s * sstride);
+      v[0] += w.x; v[1] += w.y; v[2] += w.z; v[3] += w.w;
+    }
+  } else {
+    for (int s = 0; s < splits; ++s) {
+      const float* p = partials + ((long long)s * nz + z) * (long long)Mb * Nb + (long long)m * Nb + n;
+      for (int c = 0; c < nvalid; ++c) v[c] += p[c];
+    }
   }
   int z1 = (int)(z / nz0), z0 = (int)(z % nz0);
   if (e.bias) e.bias += z0 * sBias0;
@@ -554,8 +822,9 @@ static const Variant kVariants[] = {
     {128, 128, 2, 2, true},   // 3: 4 waves, wave tile 64x64, two workgroups per CU
     {256, 256, 2, 4, true},   // 4: same as 0 (kept so that variant ids stay stable)
     {128, 128, 2, 2, false},  // 5: bounds-checked (ragged shapes)
+    {128, 64, 2, 2, true},    // 6: 4 waves, wave tile 64x32: narrow outputs (attention with 64-wide heads)
 };
-constexpr int kNumVariants = 6;
+constexpr int kNumVariants = 7;
 constexpr int kGuardVariant = 5;
 
 template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST>
@@ -594,7 +863,7 @@ bool gemm_mfma_supported(const GemmDesc& d) {
 }
 
 static bool variant_fits(const Variant& v, const GemmDesc& d) {
-  if (d.Mb % v.BM || d.Nb % v.BN || d.Kp % BK) return false;
+  if (d.Mb % v.BM || d.Nb % v.BN || d.Kp % (2 * BK)) return false;  // slabs are walked in pairs
   // buffer addressing: per-lane byte offset (< 256 * ld * 2) plus slab byte offset (< Kp * ld * 2) inside a 2 GiB window
   const long long ld = d.lda > d.ldb ? d.lda : d.ldb;
   return 512 * ld < (1LL << 30) && 2 * (long long)d.Kp * ld < (1LL << 30);
@@ -613,23 +882,25 @@ struct Plan {
 static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
   Plan best = {kGuardVariant, 1};
   if (!vec_ok || g_variant == kGuardVariant) return best;  // the fast kernels only have the vector epilogue
-  static const float t_slab[4] = {0.63f, 0.50f, 0.50f, 0.30f};  // us per BK-slab per workgroup, CU not shared
-  static const int wg_per_cu[4] = {1, 1, 1, 2};
+  static const int cand[5] = {0, 1, 2, 3, 6};
+  static const float t_slab[5] = {0.56f, 0.50f, 0.50f, 0.29f, 0.17f};  // us per BK-slab per workgroup, CU not shared
+  static const int wg_per_cu[5] = {1, 1, 1, 2, 2};
   const long long slabs = (long long)d.nl * (d.Kp / BK);
   const bool splittable = allow_split && d.nl > 1 && !d.skip_upper && !d.k_hi_diag && !d.k_lo_diag;
   float best_cost = 0.f;
   bool found = false;
-  for (int v = 0; v < 4; ++v) {
-    if (g_variant >= 0 && g_variant < 4 && v != g_variant) continue;
+  for (int ci = 0; ci < 5; ++ci) {
+    const int v = cand[ci];
+    if (g_variant >= 0 && g_variant != kGuardVariant && v != (g_variant == 4 ? 0 : g_variant)) continue;
     if (!variant_fits(kVariants[v], d)) continue;
     const long long tiles = (long long)(d.Mb / kVariants[v].BM) * (d.Nb / kVariants[v].BN);
     for (int sp = 1; sp <= 8; ++sp) {
       if (sp > 1 && (!splittable || slabs / sp < 8)) break;
       const long long wgs = tiles * sp;
-      const long long cap = 256LL * wg_per_cu[v];
+      const long long cap = 256LL * wg_per_cu[ci];
       const long long rounds = (wgs + cap - 1) / cap;
-      const float share = (wg_per_cu[v] == 2 && wgs > 256) ? 1.8f : 1.0f;  // two resident workgroups share the CU
-      const float per_wg = (float)((slabs + sp - 1) / sp) * t_slab[v] * share;
+      const float share = (wg_per_cu[ci] == 2 && wgs > 256) ? 1.8f : 1.0f;  // two resident workgroups share the CU
+      const float per_wg = (float)((slabs + sp - 1) / sp) * t_slab[ci] * share;
       const float traffic_us = sp > 1 ? 6.0f + 2.0f * sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f : 0.f;
       const float cost = 8.0f + (float)rounds * per_wg + traffic_us;
       if (!found || cost < best_cost) {
@@ -644,7 +915,8 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
 
 static bool epilogue_vec_ok(const GemmDesc& d) {
   return (d.ldc % 4 == 0) && (d.sC0 % 4 == 0) && (d.sC1 % 4 == 0) && aligned16(d.C) && (!d.pre_act || aligned16(d.pre_act)) &&
-         (!d.gelu_grad_of || aligned16(d.gelu_grad_of)) && (!d.residual || aligned16(d.residual));
+         (!d.gelu_grad_of || aligned16(d.gelu_grad_of)) && (!d.residual || aligned16(d.residual)) &&
+         (!d.bias || (aligned16(d.bias) && d.sBias0 % 4 == 0));
 }
 
 size_t gemm_partials_bytes(const GemmDesc& d, int splits) {
@@ -693,6 +965,7 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
     case 2: rc = launch_layout<128, 256, 2, 4, true>(d, ka, nwg, stream); break;
     case 3: rc = launch_layout<128, 128, 2, 2, true>(d, ka, nwg, stream); break;
     case 4: rc = launch_layout<256, 256, 2, 4, true>(d, ka, nwg, stream); break;
+    case 6: rc = launch_layout<128, 64, 2, 2, true>(d, ka, nwg, stream); break;
     default: rc = launch_layout<128, 128, 2, 2, false>(d, ka, nwg, stream); break;
   }
   if (rc != OPTIMUS_OK) return rc;

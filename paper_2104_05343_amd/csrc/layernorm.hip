@@ -214,22 +214,29 @@ int launch_ln_bwd_apply(const void* dY, const void* xhat, const float* rstd, con
 }
 
 // ---- column sums over the rows of a block: dgamma/dbeta partials, bias gradients ----
-// Workgroup = 32 row lanes x 8 column lanes; each thread accumulates 8 adjacent columns (one 16-byte load per row
-// for bf16) over rows ty, ty+32, ...; the 32 row lanes are then added through LDS in fixed order.
+// Workgroup = 1024 threads = 256 row lanes x 4 column lanes covering 32 columns; each thread accumulates 8 adjacent
+// columns (one 16-byte load per row for bf16) over rows ty, ty+256, ...  A wavefront holds 16 row lanes x 4 column
+// lanes: its row lanes are added by four butterfly exchanges, the 16 wavefronts through LDS, both in a fixed order
+// (the result does not depend on the launch).  Narrow column strips and many row lanes keep the chain of dependent
+// loads short: the matrices here have thousands of rows and only a few hundred columns per block.
+constexpr int CS_COLS = 32, CS_THREADS = 1024;
 template <typename T, bool PROD>
-__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, const T* __restrict__ W, float* __restrict__ out,
-                                                     float* __restrict__ out2, int rows, int cols, int ld, long long sX, long long sOut) {
-  __shared__ float red[32][65];
-  __shared__ float red2[32][65];
-  const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
-  const int c0 = blockIdx.x * 64 + tx * 8;
+__global__ __launch_bounds__(CS_THREADS) void colsum_kernel(const T* __restrict__ X, const T* __restrict__ W, float* __restrict__ out,
+                                                            float* __restrict__ out2, int rows, int cols, int ld, long long sX,
+                                                            long long sOut) {
+  __shared__ float red[16][CS_COLS];
+  __shared__ float red2[16][CS_COLS];
+  const int tx = threadIdx.x & 3, ty = threadIdx.x >> 2;
+  const int wave = threadIdx.x >> 6;
+  const int c0 = blockIdx.x * CS_COLS + tx * 8;
   const long long zoff = (long long)blockIdx.y * sX;
   float acc[8], acc2[8];
 #pragma unroll
   for (int k = 0; k < 8; ++k) { acc[k] = 0.f; acc2[k] = 0.f; }
   const bool vec = (ld % 8 == 0) && (sX % 8 == 0) && (c0 + 8 <= cols) && sizeof(T) == 2 && (((uintptr_t)X & 15) == 0) &&
                    (!PROD || ((uintptr_t)W & 15) == 0);
-  for (int r = ty; r < rows; r += 32) {
+#pragma unroll 4
+  for (int r = ty; r < rows; r += CS_THREADS / 4) {
     const long long off = zoff + (long long)r * ld + c0;
     float x[8], w[8];
     if (vec) {
@@ -249,14 +256,25 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, co
       if (PROD) acc2[k] += x[k] * w[k];    // sum x*w         (dgamma)
     }
   }
+  // the 16 row lanes of a wavefront: lanes that differ in bits 2..5
 #pragma unroll
-  for (int k = 0; k < 8; ++k) { red[ty][tx * 8 + k] = acc[k]; if (PROD) red2[ty][tx * 8 + k] = acc2[k]; }
+  for (int d = 4; d < 64; d <<= 1) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      acc[k] += __shfl_xor(acc[k], d, 64);
+      if (PROD) acc2[k] += __shfl_xor(acc2[k], d, 64);
+    }
+  }
+  if ((threadIdx.x & 63) < 4) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { red[wave][tx * 8 + k] = acc[k]; if (PROD) red2[wave][tx * 8 + k] = acc2[k]; }
+  }
   __syncthreads();
-  if (threadIdx.x < 64) {
-    int c = blockIdx.x * 64 + threadIdx.x;
+  if (threadIdx.x < CS_COLS) {
+    int c = blockIdx.x * CS_COLS + threadIdx.x;
     if (c < cols) {
       float s = 0.f, s2 = 0.f;
-      for (int r = 0; r < 32; ++r) { s += red[r][threadIdx.x]; if (PROD) s2 += red2[r][threadIdx.x]; }
+      for (int r = 0; r < 16; ++r) { s += red[r][threadIdx.x]; if (PROD) s2 += red2[r][threadIdx.x]; }
       out[(long long)blockIdx.y * sOut + c] = s;
       if (PROD) out2[(long long)blockIdx.y * sOut + c] = s2;
     }
@@ -265,12 +283,12 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, co
 
 int launch_colsum(const void* X, float* out, int rows, int cols, int ld, int nz, long long sX, long long sOut, int dtype,
                   hipStream_t stream) {
-  dim3 grid((unsigned)((cols + 63) / 64), (unsigned)nz);
+  dim3 grid((unsigned)((cols + CS_COLS - 1) / CS_COLS), (unsigned)nz);
   if (dtype == OPTIMUS_BF16)
-    hipLaunchKernelGGL((colsum_kernel<bf16_t, false>), grid, dim3(256), 0, stream, (const bf16_t*)X, (const bf16_t*)nullptr, out,
+    hipLaunchKernelGGL((colsum_kernel<bf16_t, false>), grid, dim3(CS_THREADS), 0, stream, (const bf16_t*)X, (const bf16_t*)nullptr, out,
                        (float*)nullptr, rows, cols, ld, sX, sOut);
   else
-    hipLaunchKernelGGL((colsum_kernel<float, false>), grid, dim3(256), 0, stream, (const float*)X, (const float*)nullptr, out,
+    hipLaunchKernelGGL((colsum_kernel<float, false>), grid, dim3(CS_THREADS), 0, stream, (const float*)X, (const float*)nullptr, out,
                        (float*)nullptr, rows, cols, ld, sX, sOut);
   return hip_launch_status();
 }
@@ -283,13 +301,13 @@ int launch_ln_param_grads(const void* dY, const void* xhat, float* dgamma_part, 
   for (int ii = 0; ii < d.ni && rc == OPTIMUS_OK; ++ii) {
     // the nj blocks of one grid row are contiguous in block-major storage
     const long long first = ((long long)(d.i0 + ii) * d.q + d.j0);
-    dim3 grid((unsigned)((d.cols + 63) / 64), (unsigned)d.nj);
+    dim3 grid((unsigned)((d.cols + CS_COLS - 1) / CS_COLS), (unsigned)d.nj);
     if (d.dtype == OPTIMUS_BF16)
-      hipLaunchKernelGGL((colsum_kernel<bf16_t, true>), grid, dim3(256), 0, stream, (const bf16_t*)dY + first * blk,
+      hipLaunchKernelGGL((colsum_kernel<bf16_t, true>), grid, dim3(CS_THREADS), 0, stream, (const bf16_t*)dY + first * blk,
                          (const bf16_t*)xhat + first * blk, dbeta_part + first * d.cols, dgamma_part + first * d.cols, d.rows,
                          d.cols, d.cols, blk, (long long)d.cols);
     else
-      hipLaunchKernelGGL((colsum_kernel<float, true>), grid, dim3(256), 0, stream, (const float*)dY + first * blk,
+      hipLaunchKernelGGL((colsum_kernel<float, true>), grid, dim3(CS_THREADS), 0, stream, (const float*)dY + first * blk,
                          (const float*)xhat + first * blk, dbeta_part + first * d.cols, dgamma_part + first * d.cols, d.rows,
                          d.cols, d.cols, blk, (long long)d.cols);
     rc = hip_launch_status();

@@ -109,7 +109,7 @@ def test_fp32_random_ragged(form):
     _check_blocks(dC, summa.product(form, A, B), M, N, q, TOL["fp32"])
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("form", FORMS)
 def test_every_tile_variant(form, variant):
     q, mb, kp, nb = 2, 512, 128, 512
