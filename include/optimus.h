@@ -246,11 +246,14 @@ int optimus_layer_bwd(const optimus_layer_cfg* cfg, const optimus_layer_tensors*
 int64_t optimus_gemm_flops(int64_t M, int64_t K, int64_t N, int q);
 int64_t optimus_layer_flops(const optimus_layer_cfg* cfg, int what);
 
-/* ---- tuning hook for benchmark sweeps (no effect on results beyond summation order) ----
- * Force the matrix-core tile variant used by bf16 products: 0 = 256x256 (4 waves), 1 = 256x128,
- * 2 = 128x256, 3 = 128x128, 4 = 256x256 (8 waves), 5 = bounds-checked 128x128; -1 = automatic.
- * A variant whose tile does not divide the block falls back to the automatic choice. */
+/* ---- tuning hooks for benchmark sweeps (no effect on results beyond summation order) ----
+ * Force the matrix-core tile variant used by bf16 products: 0 = 256x256, 1 = 256x128, 2 = 128x256,
+ * 3 = 128x128, 4 = alias of 0, 5 = bounds-checked 128x128, 6 = 128x64; -1 = automatic.
+ * A variant whose tile does not divide the block falls back to the bounds-checked kernel. */
 void optimus_debug_set_gemm_variant(int v);
+/* The plan of the most recent matrix-core product launched by this process: variant | (panel splits << 8);
+ * -1 before the first one.  Host state only, not synchronised between threads. */
+int optimus_debug_last_gemm_plan(void);
 
 #ifdef __cplusplus
 }

@@ -78,6 +78,7 @@ SIGNATURES = {
     "optimus_gemm_flops": (_I64, [_I64, _I64, _I64, _INT]),
     "optimus_layer_flops": (_I64, [C.POINTER(LayerCfg), _INT]),
     "optimus_debug_set_gemm_variant": (None, [_INT]),
+    "optimus_debug_last_gemm_plan": (_INT, []),
 }
 
 
@@ -245,3 +246,9 @@ def layer_flops(cfg: LayerCfg, what: int) -> int:
 
 def debug_set_gemm_variant(v: int):
     lib().optimus_debug_set_gemm_variant(v)
+
+
+def debug_last_gemm_plan():
+    """(variant, panel splits) of the most recent matrix-core product."""
+    p = lib().optimus_debug_last_gemm_plan()
+    return (p & 0xFF, p >> 8) if p >= 0 else None

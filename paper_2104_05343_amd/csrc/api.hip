@@ -545,5 +545,6 @@ int64_t optimus_layer_flops(const optimus_layer_cfg* c, int what) {
 
 // ---- tuning hook used by the benchmark (not part of the method): force a matrix-core tile variant, -1 = automatic ----
 void optimus_debug_set_gemm_variant(int v) { gemm_set_variant(v); }
+int optimus_debug_last_gemm_plan(void) { return gemm_last_plan(); }
 
 }  // extern "C"

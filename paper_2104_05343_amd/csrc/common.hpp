@@ -94,6 +94,7 @@ size_t gemm_partials_bytes(const GemmDesc& d, int splits);
 // force a specific kernel variant (benchmark sweeps); -1 = automatic
 void gemm_set_variant(int v);
 int gemm_get_variant();
+int gemm_last_plan();
 
 // element-wise / reduction kernels
 int launch_pack(const void* src, void* dst, long long R, long long C, int q, int elem_bytes, bool unpack,

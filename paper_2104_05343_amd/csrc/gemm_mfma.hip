@@ -39,6 +39,8 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 static int g_variant = -1;
 void gemm_set_variant(int v) { g_variant = v; }
 int gemm_get_variant() { return g_variant; }
+static int g_last_plan = -1;
+int gemm_last_plan() { return g_last_plan; }
 
 constexpr int BK = 32;
 constexpr int NSTAGE = 4;
@@ -882,27 +884,37 @@ struct Plan {
 static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
   Plan best = {kGuardVariant, 1};
   if (!vec_ok || g_variant == kGuardVariant) return best;  // the fast kernels only have the vector epilogue
-  static const int cand[5] = {0, 1, 2, 3, 6};
-  static const float t_slab[5] = {0.56f, 0.50f, 0.50f, 0.29f, 0.17f};  // us per BK-slab per workgroup, CU not shared
-  static const int wg_per_cu[5] = {1, 1, 1, 2, 2};
+  // per candidate: variant id, workgroups resident per CU, fixed cost (launch, prologue, epilogue: us and us per MiB
+  // of output), time per slab of one workgroup alone on its CU and its growth per resident workgroup per CU (the
+  // loads of all CUs share the L2 fabric)
+  struct Cand { int v, per_cu; float fixed_us, out_us_per_mib, slab_us, slab_us_per_resident; };
+  static const Cand cand[5] = {{0, 1, 12.0f, 0.15f, 0.57f, 0.00f},
+                               {1, 1, 8.0f, 0.30f, 0.35f, 0.20f},
+                               {2, 1, 8.0f, 0.30f, 0.35f, 0.20f},
+                               {3, 2, 5.5f, 0.45f, 0.25f, 0.16f},
+                               {6, 4, 4.5f, 0.50f, 0.18f, 0.13f}};
   const long long slabs = (long long)d.nl * (d.Kp / BK);
   const bool splittable = allow_split && d.nl > 1 && !d.skip_upper && !d.k_hi_diag && !d.k_lo_diag;
+  const float out_mib = (float)d.Mb * (float)d.Nb * 2.0f / 1048576.0f;
   float best_cost = 0.f;
   bool found = false;
   for (int ci = 0; ci < 5; ++ci) {
-    const int v = cand[ci];
+    const Cand& c = cand[ci];
+    const int v = c.v;
     if (g_variant >= 0 && g_variant != kGuardVariant && v != (g_variant == 4 ? 0 : g_variant)) continue;
     if (!variant_fits(kVariants[v], d)) continue;
     const long long tiles = (long long)(d.Mb / kVariants[v].BM) * (d.Nb / kVariants[v].BN);
     for (int sp = 1; sp <= 8; ++sp) {
       if (sp > 1 && (!splittable || slabs / sp < 8)) break;
       const long long wgs = tiles * sp;
-      const long long cap = 256LL * wg_per_cu[ci];
+      const long long cap = 256LL * c.per_cu;
       const long long rounds = (wgs + cap - 1) / cap;
-      const float share = (wg_per_cu[ci] == 2 && wgs > 256) ? 1.8f : 1.0f;  // two resident workgroups share the CU
-      const float per_wg = (float)((slabs + sp - 1) / sp) * t_slab[ci] * share;
-      const float traffic_us = sp > 1 ? 6.0f + 2.0f * sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f : 0.f;
-      const float cost = 8.0f + (float)rounds * per_wg + traffic_us;
+      const float resident = (float)(wgs < cap ? wgs : cap) / 256.0f;
+      const float t_slab = c.slab_us + c.slab_us_per_resident * resident;
+      const float per_wg = (float)((((slabs + sp - 1) / sp) + 1) & ~1LL) * t_slab;
+      // split: the combine launch, and the fp32 partial tiles written once and read once
+      const float traffic_us = sp > 1 ? 4.0f + 2.0f * sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f : 0.f;
+      const float cost = c.fixed_us + c.out_us_per_mib * out_mib + (float)rounds * per_wg + traffic_us;
       if (!found || cost < best_cost) {
         found = true;
         best_cost = cost;
@@ -935,6 +947,7 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
   // d.splits > 1 means the caller provided the workspace that the planned split asked for
   const Plan plan = make_plan(d, vec_ok, d.splits > 1 && d.partials != nullptr);
   const int vi = plan.variant;
+  g_last_plan = plan.variant | (plan.splits << 8);
   const Variant& v = kVariants[vi];
   KArgs ka;
   ka.A = (const bf16_t*)d.A;
