@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--gemm-reps", type=int, default=30)
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-config GEMM table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="launch a 256 MiB copy, the dominant product and the bandwidth kernels a few times and exit "
+                         "(the command profiled with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -93,26 +96,123 @@ def layer_gemm_list(b, s, h):
     ]
 
 
-def time_gemms(opt, torch, gemms, q, i, j, reps, seed):
-    """Time each product alone (device mode, workspace given, warm caches) on device-generated N(0,1)/N(0,0.02) data."""
+ROTATE_BYTES = 320 << 20   # more than the 256 MB Infinity Cache
+
+
+def time_gemms(opt, torch, gemms, q, i, j, reps, seed, rotating=True):
+    """Time each product alone (device mode, workspace given) on device-generated N(0,1)/N(0,0.02) data:
+    'us' with the same buffers every launch (warm caches), 'us_rotating' cycling through enough independent
+    buffer sets that the device's panels of all sets exceed the Infinity Cache."""
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(seed)
     rows = []
     for (name, form, M, K, N) in gemms:
         na = M * K
         nb = K * N
-        A = torch.randn(na, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
-        B = (torch.randn(nb, generator=gen, device="cuda:0", dtype=torch.float32) * 0.02).to(torch.bfloat16)
-        C = torch.empty(M * N, device="cuda:0", dtype=torch.bfloat16)
+
+        def make():
+            A = torch.randn(na, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+            B = (torch.randn(nb, generator=gen, device="cuda:0", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            C = torch.empty(M * N, device="cuda:0", dtype=torch.bfloat16)
+            return A, B, C
+        sets = [make()]
         nbytes = opt.summa_workspace_bytes(form, M, K, N, q, i, j, opt.BF16)
         ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
+        A, B, C = sets[0]
         ms = event_time_ms(lambda: opt.summa(form, A, B, C, M, K, N, q, i, j, opt.BF16, ws=ws), reps)
         fl = opt.gemm_flops(M, K, N, q)
         tf = fl / (ms * 1e-3) / 1e12
-        rows.append({"name": name, "form": form, "block": [M // q, K, N // q], "panel": K // q, "us": round(ms * 1e3, 2),
-                     "tflops": round(tf, 1), "pct_peak": round(100 * tf / PEAK_BF16_TFLOPS, 1), "split_ws_bytes": int(nbytes)})
-        del A, B, C, ws
+        row = {"name": name, "form": form, "block": [M // q, K, N // q], "panel": K // q, "us": round(ms * 1e3, 2),
+               "tflops": round(tf, 1), "pct_peak": round(100 * tf / PEAK_BF16_TFLOPS, 1), "split_ws_bytes": int(nbytes)}
+        if rotating:
+            dev_ws = 2 * ((M // q) * K + K * (N // q) + (M // q) * (N // q))   # bytes one device touches per launch
+            nsets = max(2, min(64, -(-ROTATE_BYTES // dev_ws)))
+            while len(sets) < nsets:
+                sets.append(make())
+            turn = [0]
+
+            def launch():
+                a_, b_, c_ = sets[turn[0] % nsets]
+                turn[0] += 1
+                opt.summa(form, a_, b_, c_, M, K, N, q, i, j, opt.BF16, ws=ws)
+            rr = nsets * max(1, reps // nsets)
+            ms_r = event_time_ms(launch, rr)
+            row["us_rotating"] = round(ms_r * 1e3, 2)
+            row["rotating_sets"] = nsets
+        rows.append(row)
+        del A, B, C, ws, sets
     return rows
+
+
+def time_bandwidth(opt, torch, b, s, h, n, q, i, j, reps, seed):
+    """LayerNorm forward/backward and attention forward/backward of one device at a workload's block sizes, on
+    standalone buffers: event time and achieved GB/s = algorithmic bytes / time (bf16: forward reads x, writes y and
+    xhat; backward reads dy and xhat, writes dx; parameter-gradient column sums read dy and xhat once more)."""
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(seed)
+    M, H = b * s, h
+    rows_b, cols_b = M // q, H // q
+
+    def rnd(nel, scale=1.0):
+        return (torch.randn(nel, generator=gen, device="cuda:0", dtype=torch.float32) * scale).to(torch.bfloat16)
+    X, dY = rnd(M * H), rnd(M * H)
+    Y, xhat, dX = (torch.empty(M * H, dtype=torch.bfloat16, device="cuda:0") for _ in range(3))
+    gamma = torch.ones(H, dtype=torch.float32, device="cuda:0")
+    beta = torch.zeros(H, dtype=torch.float32, device="cuda:0")
+    rstd = torch.zeros(q * q * rows_b, dtype=torch.float32, device="cuda:0")
+    stats = torch.zeros(q * q * rows_b * 2, dtype=torch.float32, device="cuda:0")
+    bstats = torch.zeros(q * q * rows_b * 2, dtype=torch.float32, device="cuda:0")
+    dg = torch.zeros(q * q * cols_b, dtype=torch.float32, device="cuda:0")
+    db = torch.zeros(q * q * cols_b, dtype=torch.float32, device="cuda:0")
+    # one grid-mode pass leaves the peers' partial statistics resident
+    opt.layernorm2d(X, gamma, beta, Y, xhat, rstd, stats, M, H, q, -1, -1, 1e-5, opt.BF16)
+    opt.layernorm2d_bwd(dY, xhat, rstd, gamma, None, dX, dg, db, bstats, M, H, q, -1, -1, opt.BF16)
+    blk = rows_b * cols_b * 2
+    out = {}
+
+    def put(name, ms, nbytes, note):
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[name] = {"us": round(ms * 1e3, 2), "algorithmic_bytes": int(nbytes), "GBps": round(gbs, 1),
+                     "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "block": [rows_b, cols_b], "what": note}
+    ms = event_time_ms(lambda: opt.layernorm2d(X, gamma, beta, Y, xhat, rstd, stats, M, H, q, i, j, 1e-5, opt.BF16), reps)
+    put("layernorm2d_fwd", ms, 3 * blk, "read x, write y and xhat (one kernel)")
+    ms = event_time_ms(lambda: opt.layernorm2d_bwd(dY, xhat, rstd, gamma, None, dX, dg, db, bstats, M, H, q, i, j, opt.BF16), reps)
+    put("layernorm2d_bwd", ms, 5 * blk, "dx kernel (read dy, xhat; write dx) + column-sum kernel (read dy, xhat)")
+    # attention: scores fp32 scratch -> probabilities bf16; bytes counted for the two softmax-like passes only
+    nmat = (b // q) * (n // q)
+    qkv = rnd(M * 3 * H, 0.5)
+    d_attn = rnd(M * H)
+    probs = torch.zeros(q * q * nmat * s * s, dtype=torch.bfloat16, device="cuda:0")
+    attn = torch.empty(M * H, dtype=torch.bfloat16, device="cuda:0")
+    d_qkv = torch.empty(M * 3 * H, dtype=torch.bfloat16, device="cuda:0")
+    aws = torch.empty(opt.attention_workspace_bytes(b, s, h, n, q), dtype=torch.uint8, device="cuda:0")
+    ms = event_time_ms(lambda: opt.attention_fwd(qkv, probs, attn, b, s, h, n, q, i, j, True, opt.BF16, aws), reps)
+    d = h // n
+    att_flops = 2 * 2 * nmat * s * s * d   # QK^T and PV, non-causal equivalent
+    out["attention_fwd"] = {"us": round(ms * 1e3, 2), "score_matrices": nmat, "s": s, "d": d, "kernels": 3,
+                            "noncausal_equiv_tflops": round(att_flops / (ms * 1e-3) / 1e12, 1),
+                            "causal_useful_tflops": round(att_flops / 2 / (ms * 1e-3) / 1e12, 1)}
+    ms = event_time_ms(lambda: opt.attention_bwd(qkv, probs, d_attn, d_qkv, b, s, h, n, q, i, j, True, opt.BF16, aws), reps)
+    out["attention_bwd"] = {"us": round(ms * 1e3, 2), "kernels": 5,
+                            "noncausal_equiv_tflops": round(2 * att_flops / (ms * 1e-3) / 1e12, 1)}
+    return out
+
+
+def pmc_probe(opt, torch, gemm, q, i, j):
+    """A 256 MiB device copy (known traffic: 256 MiB read, 256 MiB written), then the given product, then the
+    LayerNorm kernels at config-4 block size, each a few times; profiled with rocprofv3 --pmc FETCH_SIZE and, in a
+    second run, --pmc WRITE_SIZE.  The copy's counter reading gives the scale of the counter."""
+    n = (256 << 20) // 4
+    src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    rows = time_gemms(opt, torch, [gemm], q, i, j, 5, 7, rotating=False)
+    bw = time_bandwidth(opt, torch, 8, 1024, 4096, 32, 4, 1, 2, 3, 11)
+    torch.cuda.synchronize()
+    print(json.dumps({"probe": "copy 268435456 B x3; product x graph replays; layernorm/attention at config-4 blocks",
+                      "gemm": rows, "bandwidth": bw}))
 
 
 def main():
@@ -134,6 +234,10 @@ def main():
     b, s, h, n, q = shp.b, shp.s, shp.h, shp.n, shp.q
     di, dj = (int(v) for v in args.device_coords.split(","))
     di, dj = di % q, dj % q
+    if args.pmc_probe:
+        dom_gemm = max(layer_gemm_list(b, s, h), key=lambda g: g[2] * g[3] * g[4])
+        pmc_probe(opt, torch, dom_gemm, q, di, dj)
+        return
 
     # ---- workload: seeded synthetic inputs of the config's recipe, uploaded and packed block-major ----
     inp = layer_inputs(cfgd["seed"], shp, "bf16")
@@ -171,7 +275,8 @@ def main():
     fwd_ms = event_time_ms(lambda: opt.layer_fwd(cfg, lt, di, dj, ws), max(5, args.steps // 2))
     bwd_ms = event_time_ms(lambda: opt.layer_bwd(cfg, lt, di, dj, ws), max(5, args.steps // 2))
     gemm_rows = time_gemms(opt, torch, gemms, q, di, dj, args.gemm_reps, cfgd["seed"])
-    dom = max(gemm_rows, key=lambda r: r["us"])
+    # dominant kernel = the product with the most flops (first of equals): the same rule picks it in --pmc-probe
+    dom = max(gemm_rows, key=lambda r: r["block"][0] * r["block"][1] * r["block"][2])
     dom_flops = 2 * dom["block"][0] * dom["block"][1] * dom["block"][2]
     roofline = {"bound": "mfma", "kernel": f"gemm_mfma_kernel ({dom['name']}, block {dom['block']})",
                 "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -180,18 +285,11 @@ def main():
     sum_us = sum(r["us"] for r in gemm_rows)
     gemm_only_tflops = summa_flops / (sum_us * 1e-6) / 1e12
 
-    # bandwidth-bound kernels of the step (device mode): algorithmic bytes / event time
-    rows_b, cols_b = (b * s) // q, h // q
-    ln_ms = event_time_ms(lambda: opt.layernorm2d(T["x"], T["ln1_g"], T["ln1_b"], T["ln1_out"], T["xhat1"], T["rstd1"], T["stats1"],
-                                                   b * s, h, q, di, dj, 1e-5, opt.BF16), args.gemm_reps)
-    ln_bytes = rows_b * cols_b * 2 * 3   # read x, write y and xhat
-    nmat = (b // q) * (n // q)
-    aws = torch.empty(opt.attention_workspace_bytes(b, s, h, n, q), dtype=torch.uint8, device="cuda:0")
-    att_ms = event_time_ms(lambda: opt.attention_fwd(T["qkv"], T["probs"], T["attn"], b, s, h, n, q, di, dj, True, opt.BF16, aws), args.gemm_reps)
-    bw = {"layernorm2d_fwd": {"us": round(ln_ms * 1e3, 2), "algorithmic_bytes": ln_bytes,
-                              "GBps": round(ln_bytes / (ln_ms * 1e-3) / 1e9, 1),
-                              "frac_hbm_peak": round(ln_bytes / (ln_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
-          "attention_fwd_3_kernels": {"us": round(att_ms * 1e3, 2), "score_matrices": nmat, "s": s}}
+    # bandwidth-bound kernels: at this workload's block sizes and at config 4's (4 MiB blocks)
+    bw = {args.workload: time_bandwidth(opt, torch, b, s, h, n, q, di, dj, args.gemm_reps, 5)}
+    if args.workload != "config4" and not args.no_sweep:
+        c4 = CONFIGS["config4"]["layer"]
+        bw["config4"] = time_bandwidth(opt, torch, c4.b, c4.s, c4.h, c4.n, c4.q, 1, 2, max(5, args.gemm_reps // 3), 6)
 
     out = {
         "metric": "per-device SUMMA GEMM TFLOP/s (AB/ABᵀ/AᵀB) and % of MI355X bf16 MFMA peak",
@@ -237,16 +335,23 @@ def main():
         info = threadpoolctl.threadpool_info()
         threads = max([d.get("num_threads", 1) for d in info] + [1])
         c0 = time.perf_counter()
-        if args.workload == "config2":
-            fwd_o = olayer.forward(inp, b, s, n, causal=True, keep_probs=False)
-            olayer.backward(inp, fwd_o, b, s, n, causal=True)
-            cpu_flops = 3 * 2 * 12 * b * s * h * h          # SUMMA-product flops of the full logical layer, fwd + bwd
-            sample = "oracle.layer forward+backward (fp64) of the whole logical config2 layer = all 16 devices' work"
-        else:
-            rowsN = min(b * s, 2048)
-            osumma.matmul_ab(inp["x"][:rowsN], inp["w1"])
-            cpu_flops = 2 * rowsN * h * 4 * h
-            sample = f"oracle.summa.matmul_ab (fp64) on {rowsN} rows of the h->4h product"
+        reps_cpu = 0
+        while True:   # bounded sample: repeat until about 10 s of host work
+            if args.workload == "config2":
+                fwd_o = olayer.forward(inp, b, s, n, causal=True, keep_probs=False)
+                olayer.backward(inp, fwd_o, b, s, n, causal=True)
+                flops_once = 3 * 2 * 12 * b * s * h * h      # SUMMA-product flops of the full logical layer, fwd + bwd
+                sample = "oracle.layer forward+backward (fp64) of the whole logical config2 layer = all 16 devices' work"
+            else:
+                rowsN = min(b * s, 2048)
+                osumma.matmul_ab(inp["x"][:rowsN], inp["w1"])
+                flops_once = 2 * rowsN * h * 4 * h
+                sample = f"oracle.summa.matmul_ab (fp64) on {rowsN} rows of the h->4h product"
+            reps_cpu += 1
+            if time.perf_counter() - c0 >= 10.0 or reps_cpu >= 200:
+                break
+        cpu_flops = flops_once * reps_cpu
+        sample += f", repeated {reps_cpu}x"
         c1 = time.perf_counter()
         out["cpu_baseline"] = {"value": round(cpu_flops / (c1 - c0) / 1e12, 4), "unit": "TFLOP/s", "cores": threads,
                                "kind": "oracle", "sample": sample, "seconds": round(c1 - c0, 2),
