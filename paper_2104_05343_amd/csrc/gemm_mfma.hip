@@ -55,6 +55,7 @@ struct KArgs {
   long long sA0, sA1, sB0, sB1, sC0, sC1;
   long long sBias0;
   int tiles_m, tiles_n;
+  int group;  // tile rows walked together (see the tile walk in the kernel)
   int skip_upper, k_hi_diag, k_lo_diag;
   int splits;
   float* partials;
@@ -376,8 +377,10 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
   const long long z = wg / tiles;
   int t = (int)(wg % tiles);
   int tm, tn;
-  {  // column-major walk within groups of 8 tile rows keeps the working set of an XCD compact
-    constexpr int GROUP = 8;
+  {  // column-major walk within groups of a.group tile rows: the contiguous tile range of an XCD is then a
+     // block of a.group rows by (range / a.group) columns, sized on the host so that its A rows and B columns
+     // weigh about the same (least bytes fetched per XCD)
+    const int GROUP = a.group;
     int per_group = GROUP * a.tiles_n;
     int g = t / per_group;
     int first = g * GROUP;
@@ -960,6 +963,12 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
   ka.sBias0 = d.sBias0;
   ka.tiles_m = (d.Mb + v.BM - 1) / v.BM;
   ka.tiles_n = (d.Nb + v.BN - 1) / v.BN;
+  {
+    const long long per_xcd = ((long long)ka.tiles_m * ka.tiles_n + 7) / 8;
+    int g = 1;
+    while ((long long)(2 * g) * (2 * g) * v.BM <= per_xcd * v.BN * 2 && 2 * g <= 16) g *= 2;  // g ~ sqrt(per_xcd * BN / BM)
+    ka.group = g;
+  }
   ka.skip_upper = d.skip_upper; ka.k_hi_diag = d.k_hi_diag; ka.k_lo_diag = d.k_lo_diag;
   ka.splits = plan.splits;
   ka.partials = d.partials;

@@ -214,19 +214,19 @@ int launch_ln_bwd_apply(const void* dY, const void* xhat, const float* rstd, con
 }
 
 // ---- column sums over the rows of a block: dgamma/dbeta partials, bias gradients ----
-// Workgroup = 1024 threads = 256 row lanes x 4 column lanes covering 32 columns; each thread accumulates 8 adjacent
-// columns (one 16-byte load per row for bf16) over rows ty, ty+256, ...  A wavefront holds 16 row lanes x 4 column
-// lanes: its row lanes are added by four butterfly exchanges, the 16 wavefronts through LDS, both in a fixed order
+// Workgroup = 1024 threads = 128 row lanes x 8 column lanes covering 64 columns (one 128-byte line per row); each thread accumulates 8 adjacent
+// columns (one 16-byte load per row for bf16) over rows ty, ty+128, ...  A wavefront holds 8 row lanes x 8 column
+// lanes: its row lanes are added by three butterfly exchanges, the 16 wavefronts through LDS, both in a fixed order
 // (the result does not depend on the launch).  Narrow column strips and many row lanes keep the chain of dependent
 // loads short: the matrices here have thousands of rows and only a few hundred columns per block.
-constexpr int CS_COLS = 32, CS_THREADS = 1024;
+constexpr int CS_COLS = 64, CS_THREADS = 1024, CS_CL = CS_COLS / 8;  // CS_CL column lanes
 template <typename T, bool PROD>
 __global__ __launch_bounds__(CS_THREADS) void colsum_kernel(const T* __restrict__ X, const T* __restrict__ W, float* __restrict__ out,
                                                             float* __restrict__ out2, int rows, int cols, int ld, long long sX,
                                                             long long sOut) {
   __shared__ float red[16][CS_COLS];
   __shared__ float red2[16][CS_COLS];
-  const int tx = threadIdx.x & 3, ty = threadIdx.x >> 2;
+  const int tx = threadIdx.x & (CS_CL - 1), ty = threadIdx.x / CS_CL;
   const int wave = threadIdx.x >> 6;
   const int c0 = blockIdx.x * CS_COLS + tx * 8;
   const long long zoff = (long long)blockIdx.y * sX;
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(CS_THREADS) void colsum_kernel(const T* __restrict_
   const bool vec = (ld % 8 == 0) && (sX % 8 == 0) && (c0 + 8 <= cols) && sizeof(T) == 2 && (((uintptr_t)X & 15) == 0) &&
                    (!PROD || ((uintptr_t)W & 15) == 0);
 #pragma unroll 4
-  for (int r = ty; r < rows; r += CS_THREADS / 4) {
+  for (int r = ty; r < rows; r += CS_THREADS / CS_CL) {
     const long long off = zoff + (long long)r * ld + c0;
     float x[8], w[8];
     if (vec) {
@@ -256,16 +256,16 @@ __global__ __launch_bounds__(CS_THREADS) void colsum_kernel(const T* __restrict_
       if (PROD) acc2[k] += x[k] * w[k];    // sum x*w         (dgamma)
     }
   }
-  // the 16 row lanes of a wavefront: lanes that differ in bits 2..5
+  // the row lanes of a wavefront: lanes that differ in the bits above the column-lane bits
 #pragma unroll
-  for (int d = 4; d < 64; d <<= 1) {
+  for (int d = CS_CL; d < 64; d <<= 1) {
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       acc[k] += __shfl_xor(acc[k], d, 64);
       if (PROD) acc2[k] += __shfl_xor(acc2[k], d, 64);
     }
   }
-  if ((threadIdx.x & 63) < 4) {
+  if ((threadIdx.x & 63) < CS_CL) {
 #pragma unroll
     for (int k = 0; k < 8; ++k) { red[wave][tx * 8 + k] = acc[k]; if (PROD) red2[wave][tx * 8 + k] = acc2[k]; }
   }
