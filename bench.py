@@ -20,6 +20,14 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# Bytes that crossed the L2 -> fabric boundary per launch of the dominant product, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE) of `bench.py [--workload W] --pmc-probe`, each scaled by what the counter reads for a
+# 256 MiB copy in the same run (fetch x 2.0, write x 1.0).  Hardware counters cannot be read from inside this
+# script; the values are those of the profiled runs of this same command and are None for anything not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("config2", "mlp_up.ab"): {"variant": "128x64", "fetch_KiB": 6218.0 * 2.0, "write_KiB": 2048.0},
+    ("config4", "mlp_up.ab"): {"variant": "256x128", "fetch_KiB": 65618.5 * 2.0, "write_KiB": 16385.9},
+}
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
@@ -282,6 +290,12 @@ def main():
                 "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "flops_per_launch": dom_flops,
                 "avg_us": dom["us"], "traffic": None}
+    mt = MEASURED_TRAFFIC_BYTES.get((args.workload, dom["name"]))
+    if mt is not None:
+        roofline["traffic"] = int((mt["fetch_KiB"] + mt["write_KiB"]) * 1024)
+        roofline["traffic_unit"] = "bytes per launch (L2 fabric reads + writes; rocprofv3 FETCH_SIZE/WRITE_SIZE, scaled by a copy)"
+        roofline["algorithmic_bytes"] = 2 * (dom["block"][0] * dom["block"][1] + dom["block"][1] * dom["block"][2]
+                                             + dom["block"][0] * dom["block"][2])
     sum_us = sum(r["us"] for r in gemm_rows)
     gemm_only_tflops = summa_flops / (sum_us * 1e-6) / 1e12
 
