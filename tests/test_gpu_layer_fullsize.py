@@ -1,0 +1,177 @@
+"""GPU parity at the full sizes of BASELINE configs 4 and 5, in the launch configuration the benchmark times.
+
+A whole-layer fp64 oracle at these sizes is 10-40 TFLOP of host work, so every stage is checked on SAMPLED
+outputs instead: for each stage of the forward and backward path (Section 3.2 of the paper: 2D LayerNorm, the
+SUMMA products with their epilogues, local attention, the parameter gradients) a few hundred output entries are
+recomputed in fp64 from the values the device stored for that stage's inputs (downloaded from HBM), with the
+oracle's own stage functions, and compared to the tolerance of one stage on bf16 inputs (5e-3 relative
+Frobenius).  The tensors are produced by one grid-mode pass; then device mode with explicit coordinates (what
+bench.py replays) must reproduce its own blocks bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2104_05343_amd as opt
+from oracle import attention as oatt
+from oracle import layer as olayer
+from oracle import layernorm as oln
+from oracle.metrics import rel_frobenius
+from workloads import CONFIGS, bits_to_f32, layer_inputs
+from gpu_util import to_host
+from layer_util import MAT_SHAPES, alloc_layer
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+
+
+class Dev:
+    """Sampled reads of block-major device tensors as fp64 numpy."""
+
+    def __init__(self, T, shp):
+        self.T, self.shp = T, shp
+
+    def _view(self, name):
+        M, h, q = self.shp.M, self.shp.h, self.shp.q
+        R, C = MAT_SHAPES[name](M, h)
+        return self.T[name].view(q, q, R // q, C // q), R, C
+
+    @staticmethod
+    def _np(t):
+        if t.dtype == torch.bfloat16:
+            return bits_to_f32(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        return t.double().cpu().numpy()
+
+    def rows(self, name, rows):
+        v, R, C = self._view(name)
+        rb = v.shape[2]
+        r = torch.as_tensor(rows, device=v.device)
+        return self._np(v[r // rb, :, r % rb, :].reshape(len(rows), C))          # [n, C]
+
+    def cols(self, name, cols):
+        v, R, C = self._view(name)
+        cb = v.shape[3]
+        c = torch.as_tensor(cols, device=v.device)
+        return self._np(v[:, c // cb, :, c % cb].reshape(len(cols), R)).T          # [R, n]
+
+    def sub(self, name, rows, cols):
+        full = self.rows(name, rows)
+        return full[:, cols]
+
+    def vec(self, name):
+        return to_host(self.T[name]).astype(np.float64)
+
+
+def _check(label, got, want, worst):
+    e = rel_frobenius(got, want)
+    worst[label] = e
+    assert e <= TOL, f"{label}: {e:.3e} > {TOL}"
+
+
+@pytest.mark.parametrize("name,dev_ij", [("config4", (1, 2)), ("config5", (6, 3))])
+def test_layer_full_size_stagewise(name, dev_ij):
+    shp = CONFIGS[name]["layer"]
+    b, s, h, n, q, M = shp.b, shp.s, shp.h, shp.n, shp.q, shp.M
+    d = h // n
+    inp = layer_inputs(CONFIGS[name]["seed"], shp, "bf16", perturb_affine=True)
+    cfg, T, lt, ws = alloc_layer(inp, shp, True)
+    del inp["x"], inp["w1"], inp["w2"], inp["w_qkv"], inp["w_o"], inp["d_out"]   # read back from the device below
+    opt.layer_fwd(cfg, lt, -1, -1, ws)
+    opt.layer_bwd(cfg, lt, -1, -1, ws)
+    torch.cuda.synchronize()
+    D = Dev(T, shp)
+    rng = np.random.default_rng(5)
+    worst = {}
+    st = olayer._make_store("bf16")   # the oracle's model of what the device keeps in bf16 between two products
+    R = np.sort(rng.choice(M, 24, replace=False))        # sampled rows (span all block rows)
+    g1, be1, g2, be2 = D.vec("ln1_g"), D.vec("ln1_b"), D.vec("ln2_g"), D.vec("ln2_b")
+    rows_b = M // q
+
+    def cs(width, k=48):
+        return np.sort(rng.choice(width, k, replace=False))
+
+    # ---- forward ----
+    y, xh, rstd = oln.forward(D.rows("x", R), g1, be1)
+    _check("ln1_out", D.rows("ln1_out", R), y, worst)
+    _check("xhat1", D.rows("xhat1", R), xh, worst)
+    r1 = to_host(T["rstd1"]).reshape(q, q, rows_b)
+    _check("rstd1", r1[R // rows_b, :, R % rows_b], np.repeat(rstd[:, None], q, axis=1), worst)
+    C = cs(3 * h)
+    _check("qkv", D.sub("qkv", R, C), D.rows("ln1_out", R) @ D.cols("w_qkv", C) + D.vec("b_qkv")[C][None, :], worst)
+    # attention: a few (sequence, head) pairs, whole heads
+    pairs = [(int(rng.integers(b)), int(rng.integers(n))) for _ in range(3)]
+    nb, nh = b // q, n // q
+    probs_dev = T["probs"].view(q, q, nb * nh, s, s)
+    for (seq, head) in pairs:
+        rr = np.arange(seq * s, (seq + 1) * s)
+        cc = np.arange(head * 3 * d, (head + 1) * 3 * d)
+        qkv_h = D.sub("qkv", rr, cc)
+        _, P = oatt.head_forward(qkv_h[:, :d], qkv_h[:, d:2 * d], qkv_h[:, 2 * d:], causal=True)
+        O = st("probs", P) @ qkv_h[:, 2 * d:]     # the device multiplies the probabilities it stored
+        _check(f"attn[{seq},{head}]", D.sub("attn", rr, np.arange(head * d, (head + 1) * d)), O, worst)
+        pd = Dev._np(probs_dev[seq // nb, head // nh, (seq % nb) * nh + head % nh])
+        _check(f"probs[{seq},{head}]", pd, P, worst)
+    C = cs(h)
+    hm = D.sub("x", R, C) + D.rows("attn", R) @ D.cols("w_o", C) + D.vec("b_o")[C][None, :]
+    _check("h_mid", D.sub("h_mid", R, C), hm, worst)
+    y, xh, rstd2 = oln.forward(D.rows("h_mid", R), g2, be2)
+    _check("ln2_out", D.rows("ln2_out", R), y, worst)
+    _check("xhat2", D.rows("xhat2", R), xh, worst)
+    C = cs(4 * h)
+    pre = D.rows("ln2_out", R) @ D.cols("w1", C) + D.vec("b1")[C][None, :]
+    _check("pre_gelu", D.sub("pre_gelu", R, C), pre, worst)
+    _check("gelu", D.sub("gelu", R, C), olayer.gelu(pre), worst)
+    C = cs(h)
+    out = D.sub("h_mid", R, C) + D.rows("gelu", R) @ D.cols("w2", C) + D.vec("b2")[C][None, :]
+    _check("out", D.sub("out", R, C), out, worst)
+
+    # ---- backward ----
+    C4 = cs(4 * h)
+    dgelu = D.rows("d_out", R) @ D.rows("w2", C4).T
+    _check("d_pre_gelu", D.sub("d_pre_gelu", R, C4), dgelu * olayer.gelu_grad(D.sub("pre_gelu", R, C4)), worst)
+    Ch = cs(h)
+    _check("d_w2", D.sub("d_w2", C4, Ch), D.cols("gelu", C4).T @ D.cols("d_out", Ch), worst)
+    _check("d_ln2_out", D.sub("d_ln2_out", R, Ch), D.rows("d_pre_gelu", R) @ D.rows("w1", Ch).T, worst)
+    _check("d_w1", D.sub("d_w1", Ch, C4), D.cols("ln2_out", Ch).T @ D.cols("d_pre_gelu", C4), worst)
+    r2 = to_host(T["rstd2"]).reshape(q, q, rows_b)[R // rows_b, 0, R % rows_b].astype(np.float64)
+    dx2, _, _ = oln.backward(D.rows("d_ln2_out", R), D.rows("xhat2", R), r2, g2)
+    _check("d_h_mid", D.rows("d_h_mid", R), D.rows("d_out", R) + dx2, worst)
+    _check("d_attn", D.sub("d_attn", R, Ch), D.rows("d_h_mid", R) @ D.rows("w_o", Ch).T, worst)
+    Ch2 = cs(h)
+    _check("d_w_o", D.sub("d_w_o", Ch, Ch2), D.cols("attn", Ch).T @ D.cols("d_h_mid", Ch2), worst)
+    for (seq, head) in pairs:
+        rr = np.arange(seq * s, (seq + 1) * s)
+        cc = np.arange(head * 3 * d, (head + 1) * 3 * d)
+        qkv_h = D.sub("qkv", rr, cc)
+        pd = Dev._np(probs_dev[seq // nb, head // nh, (seq % nb) * nh + head % nh])
+        dO = D.sub("d_attn", rr, np.arange(head * d, (head + 1) * d))
+        dQ, dK, dV = oatt.head_backward(qkv_h[:, :d], qkv_h[:, d:2 * d], qkv_h[:, 2 * d:], pd, dO, store=st)
+        _check(f"d_qkv[{seq},{head}]", D.sub("d_qkv", rr, cc), np.concatenate([dQ, dK, dV], axis=1), worst)
+    C3 = cs(3 * h)
+    _check("d_ln1_out", D.sub("d_ln1_out", R, Ch), D.rows("d_qkv", R) @ D.rows("w_qkv", Ch).T, worst)
+    _check("d_w_qkv", D.sub("d_w_qkv", Ch, C3), D.cols("ln1_out", Ch).T @ D.cols("d_qkv", C3), worst)
+    r1v = r1[R // rows_b, 0, R % rows_b].astype(np.float64)
+    dx1, _, _ = oln.backward(D.rows("d_ln1_out", R), D.rows("xhat1", R), r1v, g1)
+    _check("d_x", D.rows("d_x", R), D.rows("d_h_mid", R) + dx1, worst)
+    # vector gradients: device (i, j)'s partial = column sums over its own rows
+    for vname, src, prod in (("d_b2", "d_out", None), ("d_b1", "d_pre_gelu", None), ("d_b_o", "d_h_mid", None),
+                             ("d_b_qkv", "d_qkv", None), ("d_ln2_b", "d_ln2_out", None), ("d_ln2_g", "d_ln2_out", "xhat2"),
+                             ("d_ln1_b", "d_ln1_out", None), ("d_ln1_g", "d_ln1_out", "xhat1")):
+        width = MAT_SHAPES[src](M, h)[1]
+        Cv = cs(width, 32)
+        colv = D.cols(src, Cv)
+        if prod:
+            colv = colv * D.cols(prod, Cv)
+        want = colv.reshape(q, rows_b, len(Cv)).sum(axis=1)                          # [q(i), n]
+        got = to_host(T[vname]).reshape(q, q, width // q)[:, Cv // (width // q), Cv % (width // q)]
+        _check(vname, got, want, worst)
+    print(name, "stage-wise sampled parity:", {k: f"{v:.1e}" for k, v in worst.items()})
+
+    # ---- the timed launch configuration reproduces its blocks bit for bit ----
+    snap = {k: v.clone() for k, v in T.items()}
+    i, j = dev_ij
+    opt.layer_fwd(cfg, lt, i, j, ws)
+    opt.layer_bwd(cfg, lt, i, j, ws)
+    torch.cuda.synchronize()
+    for k, v in T.items():
+        assert torch.equal(v.view(torch.uint8), snap[k].view(torch.uint8)), k
