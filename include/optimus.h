@@ -231,7 +231,14 @@ typedef struct {
 } optimus_layer_tensors;
 
 /* Scratch bytes optimus_layer_fwd / _bwd need in `ws` (attention scores and
- * their gradients for one device, plus split-k partial tiles). */
+ * their gradients for one device, plus split-k partial tiles: one region for
+ * the activation chain and one for the parameter-gradient branch, which
+ * optimus_layer_bwd runs concurrently on a stream of the library's own that
+ * it forks from and joins back into `stream` with events; when the call
+ * returns, every kernel of both is ordered before later work on `stream`.
+ * The library creates that stream (default priority) and its events on the
+ * first call per device; if that first call is made under stream capture and
+ * they cannot be created, the branch runs on `stream` itself.) */
 size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg);
 int optimus_layer_fwd(const optimus_layer_cfg* cfg, const optimus_layer_tensors* t, int i, int j,
                       void* ws, size_t ws_bytes, void* stream);

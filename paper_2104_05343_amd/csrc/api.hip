@@ -286,6 +286,41 @@ void layer_gemms(const optimus_layer_cfg* c, LayerGemm out[12]) {
   out[11] = {OPTIMUS_FORM_ATB, h, M, 3 * h};    // dWqkv = ln1_out^T d_qkv
 }
 
+// The parameter gradients of the backward pass (A^T B products, bias column sums) hang off the chain of activation
+// gradients but nothing in the chain waits for them: they run on a second stream of the library, forked from and
+// joined back into the caller's stream with events (also valid under stream capture: the branch becomes a parallel
+// arm of the graph).  One stream and one set of events per device, created on first use; if they cannot be
+// created (for example because the very first call is made while the caller captures a graph), the branch simply
+// runs on the caller's stream.
+struct SideStream {
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr, ready[3] = {nullptr, nullptr, nullptr};
+  int state = 0;  // 0 = not tried, 1 = usable, -1 = unavailable
+};
+constexpr int kMaxDevices = 64;
+SideStream g_side[kMaxDevices];
+
+SideStream* side_stream() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+  SideStream& x = g_side[dev];
+  if (x.state == 0) {
+    bool ok = hipStreamCreateWithFlags(&x.s, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&x.fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&x.join, hipEventDisableTiming) == hipSuccess;
+    for (int k = 0; k < 3; ++k) ok = ok && hipEventCreateWithFlags(&x.ready[k], hipEventDisableTiming) == hipSuccess;
+    if (!ok) (void)hipGetLastError();
+    x.state = ok ? 1 : -1;
+  }
+  return x.state == 1 ? &x : nullptr;
+}
+// `to` continues only after everything queued on `from` so far
+int stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
+  if (hipEventRecord(ev, from) != hipSuccess) return OPTIMUS_EHIP;
+  if (hipStreamWaitEvent(to, ev, 0) != hipSuccess) return OPTIMUS_EHIP;
+  return OPTIMUS_OK;
+}
+
 size_t layer_gemm_ws(const optimus_layer_cfg* c) {
   LayerGemm g[12];
   layer_gemms(c, g);
@@ -425,7 +460,8 @@ int optimus_attention_bwd(const void* qkv, const void* probs, const void* d_attn
 size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg) {
   AttnDims a;
   if (layer_check(cfg, 0, 0, &a)) return 0;
-  return attn_ws_bytes(a) + layer_gemm_ws(cfg);
+  // scores scratch of attention + split partials of the activation chain + split partials of the gradient branch
+  return attn_ws_bytes(a) + 2 * layer_gemm_ws(cfg);
 }
 
 int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
@@ -446,7 +482,7 @@ int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   void* attn_ws = ws;
   const size_t attn_bytes = attn_ws_bytes(a);
   void* gemm_ws = (char*)ws + attn_bytes;
-  const size_t gemm_bytes = ws_bytes - attn_bytes;
+  const size_t gemm_bytes = layer_gemm_ws(c);
   LnDesc ln;
   if ((rc = ln_desc(M, h, q, i, j, dt, c->eps, &ln))) return rc;
   // a1 = LN1(x)
@@ -495,37 +531,50 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   void* attn_ws = ws;
   const size_t attn_bytes = attn_ws_bytes(a);
   void* gemm_ws = (char*)ws + attn_bytes;
-  const size_t gemm_bytes = ws_bytes - attn_bytes;
+  const size_t gemm_bytes = layer_gemm_ws(c);
   LnDesc ln;
   if ((rc = ln_desc(M, h, q, i, j, dt, c->eps, &ln))) return rc;
+  // gradient branch: its own stream and its own split workspace (see SideStream)
+  SideStream* ss = side_stream();
+  hipStream_t gst = ss ? ss->s : st;
+  void* gstream = (void*)gst;
+  void* grad_ws = ss ? (char*)gemm_ws + gemm_bytes : gemm_ws;
   optimus_epilogue e = {};
   optimus_epilogue e32 = {};
   e32.out_fp32 = 1;
 #define RUN(...) if ((rc = (__VA_ARGS__))) return rc
+#define BRANCH_AFTER_MAIN(EV) if (ss) RUN(stream_after(gst, st, EV))
+  BRANCH_AFTER_MAIN(ss->fork);
   // ---- out = h_mid + gelu W2 + b2 ----
   e = {}; e.gelu_grad_of = t->pre_gelu;  // d_pre = (d_out W2^T) * GeLU'(pre)
   RUN(run_summa(OPTIMUS_FORM_ABT, t->d_out, t->w2, t->d_pre_gelu, M, h, 4 * h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream));
-  RUN(run_summa(OPTIMUS_FORM_ATB, t->gelu, t->d_out, t->d_w2, 4 * h, M, h, q, i, j, dt, &e32, gemm_ws, gemm_bytes, stream));
-  RUN(optimus_bias_grad(t->d_out, t->d_b2, M, h, q, i, j, dt, stream));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->gelu, t->d_out, t->d_w2, 4 * h, M, h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream));
+  RUN(optimus_bias_grad(t->d_out, t->d_b2, M, h, q, i, j, dt, gstream));
   // ---- pre = ln2_out W1 + b1 ----
+  BRANCH_AFTER_MAIN(ss->ready[0]);  // d_pre_gelu is complete
   RUN(run_summa(OPTIMUS_FORM_ABT, t->d_pre_gelu, t->w1, t->d_ln2_out, M, 4 * h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));
-  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln2_out, t->d_pre_gelu, t->d_w1, h, M, 4 * h, q, i, j, dt, &e32, gemm_ws, gemm_bytes, stream));
-  RUN(optimus_bias_grad(t->d_pre_gelu, t->d_b1, M, 4 * h, q, i, j, dt, stream));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln2_out, t->d_pre_gelu, t->d_w1, h, M, 4 * h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream));
+  RUN(optimus_bias_grad(t->d_pre_gelu, t->d_b1, M, 4 * h, q, i, j, dt, gstream));
   // ---- LN2 backward, plus the residual branch: d_h_mid = d_out + LN2'(d_ln2_out) ----
   RUN(ln_backward(t->d_ln2_out, t->xhat2, t->rstd2, t->ln2_g, t->d_out, t->d_h_mid, t->d_ln2_g, t->d_ln2_b, t->bstats2, ln, grid, st));
   // ---- h_mid = x + attn Wo + bo ----
+  BRANCH_AFTER_MAIN(ss->ready[1]);  // d_h_mid is complete
   RUN(run_summa(OPTIMUS_FORM_ABT, t->d_h_mid, t->w_o, t->d_attn, M, h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));
-  RUN(run_summa(OPTIMUS_FORM_ATB, t->attn, t->d_h_mid, t->d_w_o, h, M, h, q, i, j, dt, &e32, gemm_ws, gemm_bytes, stream));
-  RUN(optimus_bias_grad(t->d_h_mid, t->d_b_o, M, h, q, i, j, dt, stream));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->attn, t->d_h_mid, t->d_w_o, h, M, h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream));
+  RUN(optimus_bias_grad(t->d_h_mid, t->d_b_o, M, h, q, i, j, dt, gstream));
   // ---- local attention backward ----
   RUN(run_attention(true, t->qkv, t->probs, nullptr, t->d_attn, t->d_qkv, c->b, c->s, c->h, c->n, q, i, j, c->causal ? 1 : 0, dt,
                     attn_ws, attn_bytes, stream));
   // ---- qkv = ln1_out Wqkv + b ----
+  BRANCH_AFTER_MAIN(ss->ready[2]);  // d_qkv is complete
   RUN(run_summa(OPTIMUS_FORM_ABT, t->d_qkv, t->w_qkv, t->d_ln1_out, M, 3 * h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));
-  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln1_out, t->d_qkv, t->d_w_qkv, h, M, 3 * h, q, i, j, dt, &e32, gemm_ws, gemm_bytes, stream));
-  RUN(optimus_bias_grad(t->d_qkv, t->d_b_qkv, M, 3 * h, q, i, j, dt, stream));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln1_out, t->d_qkv, t->d_w_qkv, h, M, 3 * h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream));
+  RUN(optimus_bias_grad(t->d_qkv, t->d_b_qkv, M, 3 * h, q, i, j, dt, gstream));
   // ---- LN1 backward, plus the residual branch: d_x = d_h_mid + LN1'(d_ln1_out) ----
   RUN(ln_backward(t->d_ln1_out, t->xhat1, t->rstd1, t->ln1_g, t->d_h_mid, t->d_x, t->d_ln1_g, t->d_ln1_b, t->bstats1, ln, grid, st));
+  // the caller's stream owns every result again
+  if (ss) RUN(stream_after(st, gst, ss->join));
+#undef BRANCH_AFTER_MAIN
 #undef RUN
   return OPTIMUS_OK;
 }
