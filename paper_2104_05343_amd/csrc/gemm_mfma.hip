@@ -332,6 +332,81 @@ __device__ __forceinline__ void compute_slab(f32x16 (&acc)[BM / WM / 32][BN / WN
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// ---- coalesced tile stores ----
+// The MFMA accumulator layout gives a lane 4 consecutive columns of one row: stored directly, a wavefront
+// instruction writes 32 rows x 16 bytes, and every 128-byte line of C is completed by eight separate partial
+// writes (measured: 8.5 us to store a 16 MiB block, 1.9 TB/s).  Instead a 32-row chunk of the wavefront's tile goes
+// through a wavefront-private piece of LDS (free after the k-loop) and comes back as 16 bytes per lane with the
+// lanes of a row side by side: whole rows of the tile (128 bytes for 64 bf16 columns) per store.
+// LDS operations of one wavefront execute in order, so no barrier separates the write from the read-back.
+template <int TN>
+struct ChunkBf16 {
+  static constexpr int PITCH = TN * 2 + 8;      // bytes per row: 34 (TN = 64) banks, conflict-free 8-byte writes
+  static constexpr int BYTES = 32 * PITCH;
+  static constexpr int LPR = TN / 8;            // lanes per row on the way out (16 bytes each)
+  static constexpr int RPI = 64 / LPR;          // rows per store instruction
+  static constexpr int NIT = 32 / RPI;
+};
+// write: v[g] = columns ni*32 + g*8 + 4*(lane/32) .. +3 of row (lane % 32) of the chunk, packed as 4 bf16
+template <int TN>
+__device__ __forceinline__ void chunk_write_bf16(char* lds_wave, int ni, const uint2 (&v)[4], int lane) {
+  char* wr = lds_wave + (lane & 31) * ChunkBf16<TN>::PITCH + ((lane >> 5) << 3) + ni * 64;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) *(uint2*)(wr + g * 16) = v[g];
+}
+// read back and store the whole 32 x TN chunk
+template <int TN>
+__device__ __forceinline__ void chunk_flush_bf16(const char* lds_wave, bf16_t* c_chunk, long long ldc, int lane) {
+  using L = ChunkBf16<TN>;
+  const int r0 = lane / L::LPR, c = lane % L::LPR;
+#pragma unroll
+  for (int it = 0; it < L::NIT; ++it) {
+    const int row = it * L::RPI + r0;
+    const char* rd = lds_wave + row * L::PITCH + c * 16;
+    const uint2 lo = *(const uint2*)rd, hi = *(const uint2*)(rd + 8);
+    *(uint4*)(c_chunk + (long long)row * ldc + c * 8) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+  }
+}
+template <int TN>
+__device__ __forceinline__ void store_chunk_bf16(char* lds_wave, bf16_t* c_chunk, long long ldc, const uint2 (&v)[TN / 32][4],
+                                                 int lane) {
+#pragma unroll
+  for (int ni = 0; ni < TN / 32; ++ni) chunk_write_bf16<TN>(lds_wave, ni, v[ni], lane);
+  chunk_flush_bf16<TN>(lds_wave, c_chunk, ldc, lane);
+}
+// same for fp32 output: v[g] = the four floats; rows of TN floats leave as 16 bytes per lane
+template <int TN>
+struct ChunkF32 {
+  static constexpr int PITCH = TN * 4 + 16;
+  static constexpr int BYTES = 32 * PITCH;
+  static constexpr int LPR = TN / 4;
+  static constexpr int RPI = 64 / LPR;
+  static constexpr int NIT = 32 / RPI;
+};
+template <int TN>
+__device__ __forceinline__ void chunk_write_f32(char* lds_wave, int ni, const float4 (&v)[4], int lane) {
+  char* wr = lds_wave + (lane & 31) * ChunkF32<TN>::PITCH + ((lane >> 5) << 4) + ni * 128;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) *(float4*)(wr + g * 32) = v[g];
+}
+template <int TN>
+__device__ __forceinline__ void chunk_flush_f32(const char* lds_wave, float* c_chunk, long long ldc, int lane) {
+  using L = ChunkF32<TN>;
+  const int r0 = lane / L::LPR, c = lane % L::LPR;
+#pragma unroll
+  for (int it = 0; it < L::NIT; ++it) {
+    const int row = it * L::RPI + r0;
+    *(float4*)(c_chunk + (long long)row * ldc + c * 4) = *(const float4*)(lds_wave + row * L::PITCH + c * 16);
+  }
+}
+template <int TN>
+__device__ __forceinline__ void store_chunk_f32(char* lds_wave, float* c_chunk, long long ldc, const float4 (&v)[TN / 32][4],
+                                                int lane) {
+#pragma unroll
+  for (int ni = 0; ni < TN / 32; ++ni) chunk_write_f32<TN>(lds_wave, ni, v[ni], lane);
+  chunk_flush_f32<TN>(lds_wave, c_chunk, ldc, lane);
+}
+
 // wavefronts per SIMD the kernel is compiled for: what two LDS stages of the tile allow on a 160 KiB CU
 template <int BM, int BN, int WM, int WN>
 struct Occ {
@@ -352,8 +427,11 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
   constexpr int THREADS = T::THREADS, NW = T::NW;
   constexpr int TM = T::TM, TN = T::TN, MI = T::MI, NI = T::NI;
   // one ring of four slabs per operand (see read_frag_ring); the ragged path uses the first two slabs as two stages
-  __shared__ __attribute__((aligned(1024))) bf16_t ldsA[(FAST ? NSTAGE : 2) * T::A_ELEMS];
-  __shared__ __attribute__((aligned(1024))) bf16_t ldsB[(FAST ? NSTAGE : 2) * T::B_ELEMS];
+  constexpr int RING = FAST ? NSTAGE : 2;
+  constexpr int LDS_BYTES = RING * (T::A_ELEMS + T::B_ELEMS) * 2;
+  __shared__ __attribute__((aligned(1024))) bf16_t lds_all[RING * (T::A_ELEMS + T::B_ELEMS)];
+  bf16_t* const ldsA = lds_all;
+  bf16_t* const ldsB = lds_all + RING * T::A_ELEMS;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -678,31 +756,66 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
   EpiArgs e = a.epi;
   const long long coff = z1 * a.sC1 + z0 * a.sC0;
   if constexpr (PLAIN) {
-    // this lane's first element: row m0 + wm*TM + lane%32, column n0 + wn*TN + 4*(lane/32)
-    const long long first = coff + (long long)(m0 + wm * TM + (lane & 31)) * e.ldc + n0 + wn * TN + ((lane >> 5) << 2);
+    // Stores go through LDS chunk by chunk (see store_chunk_bf16) when rows of C are 16-byte aligned; after the
+    // last barrier of the k-loop no wavefront reads operand data from LDS any more.
+    const long long tile0 = coff + (long long)(m0 + wm * TM) * e.ldc + n0 + wn * TN;   // first element of the wave tile
+    const bool lines16 = ((e.ldc | coff) & 7) == 0;
+    // this lane's first element when storing directly: row lane%32, column 4*(lane/32)
+    const long long first = tile0 + (long long)(lane & 31) * e.ldc + ((lane >> 5) << 2);
     if (!e.out_fp32) {
-      bf16_t* crow = (bf16_t*)e.C + first;
+      if (lines16) {
+        static_assert(ChunkBf16<TN>::BYTES * NW <= LDS_BYTES, "chunk staging must fit in the operand rings");
+        char* stage = (char*)lds_all + wave * ChunkBf16<TN>::BYTES;
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi) {
+        for (int mi = 0; mi < MI; ++mi) {
+          uint2 v[NI][4];
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+          for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-          for (int g = 0; g < 4; ++g)
-            *(uint2*)(crow + ni * 32 + g * 8) = make_uint2(pack2_bf16(acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1]),
-                                                           pack2_bf16(acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]));
-        crow += 32LL * e.ldc;
+            for (int g = 0; g < 4; ++g)
+              v[ni][g] = make_uint2(pack2_bf16(acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1]),
+                                    pack2_bf16(acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]));
+          store_chunk_bf16<TN>(stage, (bf16_t*)e.C + tile0 + (long long)mi * 32 * e.ldc, e.ldc, v, lane);
+        }
+      } else {
+        bf16_t* crow = (bf16_t*)e.C + first;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+              *(uint2*)(crow + ni * 32 + g * 8) = make_uint2(pack2_bf16(acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1]),
+                                                             pack2_bf16(acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]));
+          crow += 32LL * e.ldc;
+        }
       }
     } else {
-      float* crow = (float*)e.C + first;
+      static_assert(ChunkF32<TN>::BYTES * NW <= LDS_BYTES, "chunk staging must fit in the operand rings");
+      if (((e.ldc | coff) & 3) == 0) {
+        char* stage = (char*)lds_all + wave * ChunkF32<TN>::BYTES;
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi) {
+        for (int mi = 0; mi < MI; ++mi) {
+          float4 v[NI][4];
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+          for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-          for (int g = 0; g < 4; ++g)
-            *(float4*)(crow + ni * 32 + g * 8) =
-                make_float4(acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]);
-        crow += 32LL * e.ldc;
+            for (int g = 0; g < 4; ++g)
+              v[ni][g] = make_float4(acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]);
+          store_chunk_f32<TN>(stage, (float*)e.C + tile0 + (long long)mi * 32 * e.ldc, e.ldc, v, lane);
+        }
+      } else {
+        float* crow = (float*)e.C + first;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+              *(float4*)(crow + ni * 32 + g * 8) =
+                  make_float4(acc[mi][ni][g * 4], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]);
+          crow += 32LL * e.ldc;
+        }
       }
     }
   } else if constexpr (FAST) {
@@ -711,12 +824,16 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
     // none of the inputs, so a load written after a store waits for it, and 16 * MI * NI dependent round trips
     // to memory would cost more than the product itself.
     const float* bias = e.bias ? e.bias + z0 * a.sBias0 + n0 + wn * TN + ((lane >> 5) << 2) : nullptr;
-    float4 b4[NI][4];
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) b4[ni][g] = bias ? *(const float4*)(bias + ni * 32 + g * 8) : make_float4(0.f, 0.f, 0.f, 0.f);
-    const long long first = coff + (long long)(m0 + wm * TM + (lane & 31)) * e.ldc + n0 + wn * TN + ((lane >> 5) << 2);
+    const long long tile0 = coff + (long long)(m0 + wm * TM) * e.ldc + n0 + wn * TN;   // first element of the wave tile
+    const long long first = tile0 + (long long)(lane & 31) * e.ldc + ((lane >> 5) << 2);
+    // results leave through LDS as whole rows of the tile when the rows are 16-byte aligned (see ChunkBf16); the
+    // staging piece of a wavefront holds one chunk of C (bf16 or fp32) and one of the pre-activation
+    const bool lines16 = ((e.ldc | coff) & 7) == 0;
+    constexpr int STAGE_C = ChunkBf16<TN>::BYTES;   // the pre-activation chunk sits behind a bf16 C chunk; an fp32 C chunk uses both
+    constexpr int STAGE = ChunkF32<TN>::BYTES > 2 * STAGE_C ? ChunkF32<TN>::BYTES : 2 * STAGE_C;
+    const bool pre_lines = lines16 && !e.out_fp32;
+    static_assert(STAGE * NW <= LDS_BYTES, "chunk staging must fit in the operand rings");
+    char* stage = (char*)lds_all + wave * STAGE;
     const bf16_t* zrow = e.gelu_grad_of ? (const bf16_t*)e.gelu_grad_of + first : nullptr;
     const bf16_t* rrow = e.residual ? (const bf16_t*)e.residual + first : nullptr;
     bf16_t* prow = e.pre_act ? (bf16_t*)e.pre_act + first : nullptr;
@@ -725,42 +842,70 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
       const long long ro = (long long)mi * 32 * e.ldc;
-      uint2 zz[NI][4], rr[NI][4];
-      if (zrow) {
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+      for (int ni = 0; ni < NI; ++ni) {
+        float4 b4[4];
+        uint2 zz[4], rr[4];
 #pragma unroll
-          for (int g = 0; g < 4; ++g) zz[ni][g] = *(const uint2*)(zrow + ro + ni * 32 + g * 8);
-      }
-      if (rrow) {
+        for (int g = 0; g < 4; ++g) b4[g] = bias ? *(const float4*)(bias + ni * 32 + g * 8) : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (zrow) {
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+          for (int g = 0; g < 4; ++g) zz[g] = *(const uint2*)(zrow + ro + ni * 32 + g * 8);
+        }
+        if (rrow) {
 #pragma unroll
-          for (int g = 0; g < 4; ++g) rr[ni][g] = *(const uint2*)(rrow + ro + ni * 32 + g * 8);
-      }
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
+          for (int g = 0; g < 4; ++g) rr[g] = *(const uint2*)(rrow + ro + ni * 32 + g * 8);
+        }
+        uint2 pv[4];
+        float4 cf[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          float t[4] = {acc[mi][ni][g * 4] * alpha + b4[ni][g].x, acc[mi][ni][g * 4 + 1] * alpha + b4[ni][g].y,
-                        acc[mi][ni][g * 4 + 2] * alpha + b4[ni][g].z, acc[mi][ni][g * 4 + 3] * alpha + b4[ni][g].w};
-          const long long o = ro + ni * 32 + g * 8;
-          if (prow) *(uint2*)(prow + o) = make_uint2(pack2_bf16(t[0], t[1]), pack2_bf16(t[2], t[3]));
+          float t[4] = {acc[mi][ni][g * 4] * alpha + b4[g].x, acc[mi][ni][g * 4 + 1] * alpha + b4[g].y,
+                        acc[mi][ni][g * 4 + 2] * alpha + b4[g].z, acc[mi][ni][g * 4 + 3] * alpha + b4[g].w};
+          if (prow) pv[g] = make_uint2(pack2_bf16(t[0], t[1]), pack2_bf16(t[2], t[3]));
           if (act) gelu4<false>(t);
           if (zrow) {
-            const uint2 w = zz[ni][g];
+            const uint2 w = zz[g];
             const float z[4] = {__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
                                 __uint_as_float(w.y & 0xffff0000u)};
             gelu_grad_mul4<false>(t, z);
           }
           if (rrow) {
-            const uint2 w = rr[ni][g];
+            const uint2 w = rr[g];
             t[0] += __uint_as_float(w.x << 16); t[1] += __uint_as_float(w.x & 0xffff0000u);
             t[2] += __uint_as_float(w.y << 16); t[3] += __uint_as_float(w.y & 0xffff0000u);
           }
-          if (out32) *(float4*)((float*)e.C + first + o) = make_float4(t[0], t[1], t[2], t[3]);
-          else *(uint2*)((bf16_t*)e.C + first + o) = make_uint2(pack2_bf16(t[0], t[1]), pack2_bf16(t[2], t[3]));
+          cf[g] = make_float4(t[0], t[1], t[2], t[3]);
         }
+        if (prow) {
+          if (pre_lines) chunk_write_bf16<TN>(stage + STAGE_C, ni, pv, lane);
+          else {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) *(uint2*)(prow + ro + ni * 32 + g * 8) = pv[g];
+          }
+        }
+        if (out32) {
+          if (lines16) chunk_write_f32<TN>(stage, ni, cf, lane);
+          else {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) *(float4*)((float*)e.C + first + ro + ni * 32 + g * 8) = cf[g];
+          }
+        } else {
+          uint2 cv[4];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) cv[g] = make_uint2(pack2_bf16(cf[g].x, cf[g].y), pack2_bf16(cf[g].z, cf[g].w));
+          if (lines16) chunk_write_bf16<TN>(stage, ni, cv, lane);
+          else {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) *(uint2*)((bf16_t*)e.C + first + ro + ni * 32 + g * 8) = cv[g];
+          }
+        }
+      }
+      if (lines16) {
+        if (prow && pre_lines) chunk_flush_bf16<TN>(stage + STAGE_C, (bf16_t*)e.pre_act + tile0 + ro, e.ldc, lane);
+        if (out32) chunk_flush_f32<TN>(stage, (float*)e.C + tile0 + ro, e.ldc, lane);
+        else chunk_flush_bf16<TN>(stage, (bf16_t*)e.C + tile0 + ro, e.ldc, lane);
+      }
     }
   } else {
     if (e.bias) e.bias += z0 * a.sBias0;
