@@ -561,7 +561,8 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
       // i+1 needs in that order (at B of step i everything up to the group of step i-1 has been issued).
       constexpr int MF = MI * NI;
       constexpr int NF = MI + NI;                                   // fragments per sub-step
-      constexpr int FPS = (NF + MF / 2 - 1) / (MF / 2 > 0 ? MF / 2 : 1);  // fragments requested per MFMA slot
+      constexpr int FSLOTS = MF / 2 > 0 ? MF / 2 : 1;               // the fragment reads go in front of the first MFMAs
+      constexpr int FPS = (NF + FSLOTS - 1) / FSLOTS;               // fragments requested per such slot
       static_assert(BK == 32 && NSTAGE == 4, "the pipeline below is written for two sub-steps per slab, four slabs");
       static_assert(MF <= 16 && FPS <= 3 && PA + PB <= 16, "slot and load lists below");
       constexpr int G_ODD = PA + PB, G_EVEN = PKS;  // loads per group
@@ -973,8 +974,9 @@ static const Variant kVariants[] = {
     {256, 256, 2, 4, true},   // 4: same as 0 (kept so that variant ids stay stable)
     {128, 128, 2, 2, false},  // 5: bounds-checked (ragged shapes)
     {128, 64, 2, 2, true},    // 6: 4 waves, wave tile 64x32: narrow outputs (attention with 64-wide heads)
+    {64, 64, 2, 2, true},     // 7: 4 waves, wave tile 32x32: small blocks that need every CU (least bytes per CU)
 };
-constexpr int kNumVariants = 7;
+constexpr int kNumVariants = 8;
 constexpr int kGuardVariant = 5;
 
 template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST>
@@ -1036,17 +1038,18 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
   // of output), time per slab of one workgroup alone on its CU and its growth per resident workgroup per CU (the
   // loads of all CUs share the L2 fabric)
   struct Cand { int v, per_cu; float fixed_us, out_us_per_mib, slab_us, slab_us_per_resident; };
-  static const Cand cand[5] = {{0, 1, 12.0f, 0.15f, 0.57f, 0.00f},
+  static const Cand cand[6] = {{0, 1, 12.0f, 0.15f, 0.57f, 0.00f},
                                {1, 1, 8.0f, 0.30f, 0.35f, 0.20f},
                                {2, 1, 8.0f, 0.30f, 0.35f, 0.20f},
                                {3, 2, 5.5f, 0.45f, 0.25f, 0.16f},
-                               {6, 4, 4.5f, 0.50f, 0.18f, 0.13f}};
+                               {6, 4, 4.5f, 0.50f, 0.18f, 0.13f},
+                               {7, 5, 4.0f, 0.50f, 0.12f, 0.08f}};
   const long long slabs = (long long)d.nl * (d.Kp / BK);
   const bool splittable = allow_split && d.nl > 1 && !d.skip_upper && !d.k_hi_diag && !d.k_lo_diag;
   const float out_mib = (float)d.Mb * (float)d.Nb * 2.0f / 1048576.0f;
   float best_cost = 0.f;
   bool found = false;
-  for (int ci = 0; ci < 5; ++ci) {
+  for (int ci = 0; ci < 6; ++ci) {
     const Cand& c = cand[ci];
     const int v = c.v;
     if (g_variant >= 0 && g_variant != kGuardVariant && v != (g_variant == 4 ? 0 : g_variant)) continue;
@@ -1133,6 +1136,7 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
     case 3: rc = launch_layout<128, 128, 2, 2, true>(d, ka, nwg, stream); break;
     case 4: rc = launch_layout<256, 256, 2, 4, true>(d, ka, nwg, stream); break;
     case 6: rc = launch_layout<128, 64, 2, 2, true>(d, ka, nwg, stream); break;
+    case 7: rc = launch_layout<64, 64, 2, 2, true>(d, ka, nwg, stream); break;
     default: rc = launch_layout<128, 128, 2, 2, false>(d, ka, nwg, stream); break;
   }
   if (rc != OPTIMUS_OK) return rc;
