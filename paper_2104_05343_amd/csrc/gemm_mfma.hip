@@ -639,32 +639,35 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
       else sb += stepB;                                                                       \
     }                                                                                         \
   } while (0)
-      // S = slab position (0..3) of slab i; the previous step's group refills position (S + 3) & 3
-#define OPTIMUS_STEP_EVEN(S)                                                                                      \
+      // S = slab position (0..3) of slab i; the previous step's group refills position (S + 3) & 3.
+      // ST = 1: steady state, i >= 4 and i + 8 <= nslab at the top of the four steps: every group exists, so every
+      // load is unconditional and every wait count a constant (the conditional form costs about ten scalar branches
+      // per step, a third of the time of a step on the small tiles).
+#define OPTIMUS_STEP_EVEN(S, ST)                                                                                  \
   do {                                                                                                            \
-    OPTIMUS_HALF(fa1, fb1, S, 1, fa0, fb0, true, ((S) + 3) & 3, (G_ODD + 1) / 2, G_ODD / 2, pend);                \
-    if (pend) OPTIMUS_ADVANCE(true);                                                                              \
-    pend = false;                                                                                                 \
+    OPTIMUS_HALF(fa1, fb1, S, 1, fa0, fb0, true, ((S) + 3) & 3, (G_ODD + 1) / 2, G_ODD / 2, ((ST) || pend));      \
+    if ((ST) || pend) OPTIMUS_ADVANCE(true);                                                                      \
+    if (!(ST)) pend = false;                                                                                      \
     if constexpr (PKS > 0) { /* all k-contiguous: slab i+1 came with slab i, nothing to hand over */              \
-      if (i + 2 < nslab) OPTIMUS_WAIT_VMCNT_LGKM0(2 * PKS + PKC2);                                                \
+      if ((ST) || i + 2 < nslab) OPTIMUS_WAIT_VMCNT_LGKM0(2 * PKS + PKC2);                                        \
       else OPTIMUS_WAIT_VMCNT_LGKM0(0);                                                                           \
       OPTIMUS_BARRIER();                                                                                          \
-      pend = i + 4 < nslab;                                                                                       \
+      if (!(ST)) pend = i + 4 < nslab;                                                                            \
     }                                                                                                             \
-    OPTIMUS_HALF(fa0, fb0, (S) + 1, 0, fa1, fb1, false, S, 0, (G_EVEN + 1) / 2, pend);                            \
+    OPTIMUS_HALF(fa0, fb0, (S) + 1, 0, fa1, fb1, false, S, 0, (G_EVEN + 1) / 2, ((ST) || pend));                  \
     ++i;                                                                                                          \
   } while (0)
-#define OPTIMUS_STEP_ODD(S)                                                                                       \
+#define OPTIMUS_STEP_ODD(S, ST)                                                                                   \
   do {                                                                                                            \
-    OPTIMUS_HALF(fa1, fb1, S, 1, fa0, fb0, false, (S) - 1, (G_EVEN + 1) / 2, G_EVEN / 2, pend);                   \
-    if (pend) OPTIMUS_ADVANCE(false);                                                                             \
-    if (i + 3 < nslab) OPTIMUS_WAIT_VMCNT_LGKM0(2 * PKS);                                                         \
+    OPTIMUS_HALF(fa1, fb1, S, 1, fa0, fb0, false, (S) - 1, (G_EVEN + 1) / 2, G_EVEN / 2, ((ST) || pend));         \
+    if (PKS > 0 && ((ST) || pend)) OPTIMUS_ADVANCE(false);                                                        \
+    if ((ST) || i + 3 < nslab) OPTIMUS_WAIT_VMCNT_LGKM0(2 * PKS);                                                 \
     else if (i + 2 < nslab) OPTIMUS_WAIT_VMCNT_LGKM0(PKS);                                                        \
     else OPTIMUS_WAIT_VMCNT_LGKM0(0);                                                                             \
     OPTIMUS_BARRIER();                                                                                            \
-    pend = i + 3 < nslab;                                                                                         \
+    if (!(ST)) pend = i + 3 < nslab;                                                                              \
     /* after the last slab this reads a slab nobody writes any more; the values are never used */                \
-    OPTIMUS_HALF(fa0, fb0, ((S) + 1) & 3, 0, fa1, fb1, true, S, 0, (G_ODD + 1) / 2, pend);                        \
+    OPTIMUS_HALF(fa0, fb0, ((S) + 1) & 3, 0, fa1, fb1, true, S, 0, (G_ODD + 1) / 2, ((ST) || pend));              \
     ++i;                                                                                                          \
   } while (0)
       // prologue: whole groups at once
@@ -683,14 +686,21 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
       load_frags<BM, BN, WM, WN, AKC, BKC>(fa0, fb0, ldsA, ldsB, 0, 0, wm, wn, lane);
       int i = 0;
       while (i + 4 <= nslab) {
-        OPTIMUS_STEP_EVEN(0);
-        OPTIMUS_STEP_ODD(1);
-        OPTIMUS_STEP_EVEN(2);
-        OPTIMUS_STEP_ODD(3);
+        OPTIMUS_STEP_EVEN(0, 0);
+        OPTIMUS_STEP_ODD(1, 0);
+        OPTIMUS_STEP_EVEN(2, 0);
+        OPTIMUS_STEP_ODD(3, 0);
+        while (i + 8 <= nslab) {  // i >= 4 here
+          OPTIMUS_STEP_EVEN(0, 1);
+          OPTIMUS_STEP_ODD(1, 1);
+          OPTIMUS_STEP_EVEN(2, 1);
+          OPTIMUS_STEP_ODD(3, 1);
+          pend = true;  // the last steady step opened a group
+        }
       }
       if (i < nslab) {  // one pair left
-        OPTIMUS_STEP_EVEN(0);
-        OPTIMUS_STEP_ODD(1);
+        OPTIMUS_STEP_EVEN(0, 0);
+        OPTIMUS_STEP_ODD(1, 0);
       }
 #undef OPTIMUS_STEP_EVEN
 #undef OPTIMUS_STEP_ODD
