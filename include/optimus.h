@@ -255,7 +255,7 @@ int64_t optimus_layer_flops(const optimus_layer_cfg* cfg, int what);
 
 /* ---- tuning hooks for benchmark sweeps (no effect on results beyond summation order) ----
  * Force the matrix-core tile variant used by bf16 products: 0 = 256x256, 1 = 256x128, 2 = 128x256,
- * 3 = 128x128, 4 = alias of 0, 5 = bounds-checked 128x128, 6 = 128x64; -1 = automatic.
+ * 3 = 128x128, 4 = alias of 0, 5 = bounds-checked 128x128, 6 = 128x64, 7 = 64x64; -1 = automatic.
  * A variant whose tile does not divide the block falls back to the bounds-checked kernel. */
 void optimus_debug_set_gemm_variant(int v);
 /* The plan of the most recent matrix-core product launched by this process: variant | (panel splits << 8);

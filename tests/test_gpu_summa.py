@@ -101,6 +101,22 @@ def test_bf16_random_blocks(form, q):
 
 
 @pytest.mark.parametrize("form", FORMS)
+@pytest.mark.parametrize("kp", [32, 96, 64, 192, 320])
+def test_bf16_short_and_odd_panel_lengths(form, kp):
+    """Tile-multiple blocks whose panel length is an odd or even number of 32-slabs: odd counts cannot use the
+    pair-wise k-loop and take the bounds-checked kernel; 64 is the shortest fast case (one pair per panel)."""
+    q, mb, nb = 2, 256, 256
+    M, K, N = mb * q, kp * q, nb * q
+    A, B = gemm_inputs(300 + kp, form, M, K, N, "bf16", "n1", "n1")
+    want = summa.product(form, A, B)
+    dC = _run(form, A, B, M, K, N, q, "bf16")
+    _check_blocks(dC, want, M, N, q, TOL["bf16"])
+    dC1 = _run(form, A, B, M, K, N, q, "bf16", 1, 0)
+    _check_blocks(dC1, want, M, N, q, TOL["bf16"], coords={(1, 0)})
+    assert np.array_equal(to_host(dC).reshape(q, q, mb, nb)[1, 0], to_host(dC1).reshape(q, q, mb, nb)[1, 0])
+
+
+@pytest.mark.parametrize("form", FORMS)
 def test_fp32_random_ragged(form):
     q, (mb, kp, nb) = 2, (70, 33, 45)
     M, K, N = mb * q, kp * q, nb * q
@@ -112,7 +128,8 @@ def test_fp32_random_ragged(form):
 @pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("form", FORMS)
 def test_every_tile_variant(form, variant):
-    q, mb, kp, nb = 2, 512, 128, 512
+    # 32 slabs of 32 per block: first cycle, steady-state cycles and last cycle of the k-loop all run
+    q, mb, kp, nb = 2, 512, 512, 512
     M, K, N = mb * q, kp * q, nb * q
     A, B = gemm_inputs(55, form, M, K, N, "bf16", "n1", "n1")
     want = summa.product(form, A, B)
