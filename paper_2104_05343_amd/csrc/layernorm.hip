@@ -214,16 +214,19 @@ int launch_ln_bwd_apply(const void* dY, const void* xhat, const float* rstd, con
 }
 
 // ---- column sums over the rows of a block: dgamma/dbeta partials, bias gradients ----
-// Workgroup = 1024 threads = 128 row lanes x 8 column lanes covering 64 columns (one 128-byte line per row); each thread accumulates 8 adjacent
-// columns (one 16-byte load per row for bf16) over rows ty, ty+128, ...  A wavefront holds 8 row lanes x 8 column
-// lanes: its row lanes are added by three butterfly exchanges, the 16 wavefronts through LDS, both in a fixed order
-// (the result does not depend on the launch).  Narrow column strips and many row lanes keep the chain of dependent
+// Workgroup = 1024 threads = (1024 / CL) row lanes x CL column lanes covering CS_COLS = 8 * CL columns; each thread
+// accumulates 8 adjacent columns (one 16-byte load per row for bf16) over rows ty, ty + 1024 / CL, ...  The row lanes
+// inside a wavefront are added by butterfly exchanges, the 16 wavefronts through LDS, both in a fixed order (the
+// result does not depend on the launch).  Narrow column strips and many row lanes keep the chain of dependent
 // loads short: the matrices here have thousands of rows and only a few hundred columns per block.
-constexpr int CS_COLS = 64, CS_THREADS = 1024, CS_CL = CS_COLS / 8;  // CS_CL column lanes
-template <typename T, bool PROD>
+constexpr int CS_THREADS = 1024;
+// CS_COLS = 64: whole 128-byte lines per row (large blocks, bandwidth matters).  CS_COLS = 32: twice the workgroups
+// and half the rows per lane (small blocks, where the kernel is two dependent memory round trips long).
+template <typename T, bool PROD, int CS_COLS>
 __global__ __launch_bounds__(CS_THREADS) void colsum_kernel(const T* __restrict__ X, const T* __restrict__ W, float* __restrict__ out,
                                                             float* __restrict__ out2, int rows, int cols, int ld, long long sX,
                                                             long long sOut) {
+  constexpr int CS_CL = CS_COLS / 8;  // column lanes
   __shared__ float red[16][CS_COLS];
   __shared__ float red2[16][CS_COLS];
   const int tx = threadIdx.x & (CS_CL - 1), ty = threadIdx.x / CS_CL;
@@ -281,15 +284,28 @@ __global__ __launch_bounds__(CS_THREADS) void colsum_kernel(const T* __restrict_
   }
 }
 
+// strip width from the block shape only (never from the batch): grid mode and device mode then add in the same order
+static bool colsum_narrow(int rows, int cols) { return (long long)rows * cols <= (1LL << 20); }
+
+template <typename T, bool PROD>
+static void colsum_launch(dim3 batch, const T* X, const T* W, float* out, float* out2, int rows, int cols, int ld, long long sX,
+                          long long sOut, hipStream_t stream) {
+  if (colsum_narrow(rows, cols)) {
+    dim3 grid((unsigned)((cols + 31) / 32), batch.y);
+    hipLaunchKernelGGL((colsum_kernel<T, PROD, 32>), grid, dim3(CS_THREADS), 0, stream, X, W, out, out2, rows, cols, ld, sX, sOut);
+  } else {
+    dim3 grid((unsigned)((cols + 63) / 64), batch.y);
+    hipLaunchKernelGGL((colsum_kernel<T, PROD, 64>), grid, dim3(CS_THREADS), 0, stream, X, W, out, out2, rows, cols, ld, sX, sOut);
+  }
+}
+
 int launch_colsum(const void* X, float* out, int rows, int cols, int ld, int nz, long long sX, long long sOut, int dtype,
                   hipStream_t stream) {
-  dim3 grid((unsigned)((cols + CS_COLS - 1) / CS_COLS), (unsigned)nz);
+  dim3 batch(1, (unsigned)nz);
   if (dtype == OPTIMUS_BF16)
-    hipLaunchKernelGGL((colsum_kernel<bf16_t, false>), grid, dim3(CS_THREADS), 0, stream, (const bf16_t*)X, (const bf16_t*)nullptr, out,
-                       (float*)nullptr, rows, cols, ld, sX, sOut);
+    colsum_launch<bf16_t, false>(batch, (const bf16_t*)X, (const bf16_t*)nullptr, out, (float*)nullptr, rows, cols, ld, sX, sOut, stream);
   else
-    hipLaunchKernelGGL((colsum_kernel<float, false>), grid, dim3(CS_THREADS), 0, stream, (const float*)X, (const float*)nullptr, out,
-                       (float*)nullptr, rows, cols, ld, sX, sOut);
+    colsum_launch<float, false>(batch, (const float*)X, (const float*)nullptr, out, (float*)nullptr, rows, cols, ld, sX, sOut, stream);
   return hip_launch_status();
 }
 
@@ -301,15 +317,13 @@ int launch_ln_param_grads(const void* dY, const void* xhat, float* dgamma_part, 
   for (int ii = 0; ii < d.ni && rc == OPTIMUS_OK; ++ii) {
     // the nj blocks of one grid row are contiguous in block-major storage
     const long long first = ((long long)(d.i0 + ii) * d.q + d.j0);
-    dim3 grid((unsigned)((d.cols + CS_COLS - 1) / CS_COLS), (unsigned)d.nj);
+    dim3 batch(1, (unsigned)d.nj);
     if (d.dtype == OPTIMUS_BF16)
-      hipLaunchKernelGGL((colsum_kernel<bf16_t, true>), grid, dim3(CS_THREADS), 0, stream, (const bf16_t*)dY + first * blk,
-                         (const bf16_t*)xhat + first * blk, dbeta_part + first * d.cols, dgamma_part + first * d.cols, d.rows,
-                         d.cols, d.cols, blk, (long long)d.cols);
+      colsum_launch<bf16_t, true>(batch, (const bf16_t*)dY + first * blk, (const bf16_t*)xhat + first * blk, dbeta_part + first * d.cols,
+                                  dgamma_part + first * d.cols, d.rows, d.cols, d.cols, blk, (long long)d.cols, stream);
     else
-      hipLaunchKernelGGL((colsum_kernel<float, true>), grid, dim3(CS_THREADS), 0, stream, (const float*)dY + first * blk,
-                         (const float*)xhat + first * blk, dbeta_part + first * d.cols, dgamma_part + first * d.cols, d.rows,
-                         d.cols, d.cols, blk, (long long)d.cols);
+      colsum_launch<float, true>(batch, (const float*)dY + first * blk, (const float*)xhat + first * blk, dbeta_part + first * d.cols,
+                                 dgamma_part + first * d.cols, d.rows, d.cols, d.cols, blk, (long long)d.cols, stream);
     rc = hip_launch_status();
   }
   return rc;
