@@ -7,8 +7,7 @@
 // arithmetic and no partial C ever goes to HBM (unless the caller asked for a panel split).
 //
 // Tiling: a workgroup of WM*WN wavefronts owns a BM x BN output tile; k advances in slabs of
-// BK = 32 through FOUR LDS stages (three slabs in flight while one is multiplied: the latency
-// of L2/HBM under load is about three slab times).
+// BK = 32 through a ring of FOUR slabs per operand in LDS.
 //   * Full tiles (FAST): every wavefront issues buffer_load_dwordx4 ... lds, which moves 64 x 16
 //     bytes from per-lane offsets straight into one contiguous KiB of LDS without passing
 //     through registers.  The LDS swizzles below are therefore applied on the GLOBAL side:
@@ -16,15 +15,22 @@
 //     (SGPR resource + one 32-bit VGPR offset) is used because 64-bit per-lane addresses were
 //     measured to stall the MFMA pipe twice as much.  Slab hand-over uses s_waitcnt vmcnt(N) and
 //     a bare s_barrier: a fenced barrier would drain the loads in flight.
-//   * Ragged tiles: global -> registers (zero filled outside the operand) -> LDS, same layout.
+//     A k-strided operand moves one slab per step; a k-contiguous operand moves a PAIR of slabs
+//     (64 k = one whole 128-byte line per row) every second step.  The pipeline runs over 16-wide
+//     sub-steps with the fragments of the next sub-step requested between the MFMAs of the
+//     current one, also across slab boundaries; the loads that refill a freed slab are spread one
+//     by one between the MFMAs as well (see the comments at the loop).
+//   * Ragged tiles: global -> registers (zero filled outside the operand) -> LDS, two stages.
 // LDS layouts (conflict free for their readers on the 64-bank, 256 B/clk LDS of this part):
-//   * k-contiguous operand ([rows][k] in memory): rows of 4 sixteen-byte chunks, chunk index
+//   * k-contiguous operand ([rows][k] in memory), fast path: pairs of slabs as rows of 8
+//     sixteen-byte chunks, chunk index XOR ((row >> 1) & 7); ragged path: rows of 4 chunks, chunk
 //     XOR ((row >> 2) & 3); fragments are read with ds_read_b128.
 //   * k-strided operand ([k][cols] in memory: B of A*B, both operands of A^T*B): kept as it is,
 //     32-byte column granules XOR 2*(k & 3); fragments are fetched with the transposing read
 //     ds_read_b64_tr_b16, which hands each lane four consecutive k of one column.
 // The two MFMA operands are swapped (D^T = B^T A^T) so that every lane ends up with four
-// consecutive columns of one output row: 8-byte bf16 stores, and vector loads of the residual.
+// consecutive columns of one output row; results leave through wavefront-private LDS chunks as
+// whole rows of the tile (see ChunkBf16).
 #include "common.hpp"
 #include "epilogue.hpp"
 
@@ -289,14 +295,6 @@ __device__ __forceinline__ void mfma_m(f32x16 (&acc)[MI][NI], const bf16x8 (&fa)
 }
 // slot (0 .. MF-1) in front of whose MFMA load G of GN is issued: spread evenly over the sub-step
 constexpr int dma_slot(int g, int gn, int mf) { return ((2 * g + 1) * mf) / (2 * gn); }
-
-template <int MI, int NI>
-__device__ __forceinline__ void mma_step(f32x16 (&acc)[MI][NI], const bf16x8 (&fa)[MI], const bf16x8 (&fb)[NI]) {
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0);
-}
 
 // One slab of MFMAs from LDS.  Software pipeline over the four 16-wide sub-steps: the fragments of sub-step
 // ks+1 are requested while the MFMAs of sub-step ks run (their operands were requested one sub-step earlier).
