@@ -1043,15 +1043,16 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
   Plan best = {kGuardVariant, 1};
   if (!vec_ok || g_variant == kGuardVariant) return best;  // the fast kernels only have the vector epilogue
   // per candidate: variant id, workgroups resident per CU, fixed cost (launch, prologue, epilogue: us and us per MiB
-  // of output), time per slab of one workgroup alone on its CU and its growth per resident workgroup per CU (the
-  // loads of all CUs share the L2 fabric)
-  struct Cand { int v, per_cu; float fixed_us, out_us_per_mib, slab_us, slab_us_per_resident; };
-  static const Cand cand[6] = {{0, 1, 12.0f, 0.15f, 0.57f, 0.00f},
-                               {1, 1, 8.0f, 0.30f, 0.35f, 0.20f},
-                               {2, 1, 8.0f, 0.30f, 0.35f, 0.20f},
-                               {3, 2, 5.5f, 0.45f, 0.25f, 0.16f},
-                               {6, 4, 4.5f, 0.50f, 0.18f, 0.13f},
-                               {7, 5, 4.0f, 0.50f, 0.12f, 0.08f}};
+  // of output), and the time per slab of one workgroup: alone on the chip (t_lone), with every CU holding one
+  // workgroup (t_full: all CUs' loads share the L2 fabric; the rise is steep only near full occupancy, hence the
+  // square), and the increment per further workgroup resident on the same CU (t_more).  Measured on MI355X.
+  struct Cand { int v, per_cu; float fixed_us, out_us_per_mib, t_lone, t_full, t_more; };
+  static const Cand cand[6] = {{0, 1, 12.0f, 0.15f, 0.54f, 0.64f, 0.00f},
+                               {1, 1, 8.0f, 0.30f, 0.31f, 0.42f, 0.00f},
+                               {2, 1, 8.0f, 0.30f, 0.31f, 0.42f, 0.00f},
+                               {3, 2, 5.5f, 0.45f, 0.20f, 0.25f, 0.21f},
+                               {6, 4, 4.5f, 0.50f, 0.19f, 0.30f, 0.16f},
+                               {7, 5, 4.0f, 0.50f, 0.14f, 0.155f, 0.20f}};
   const long long slabs = (long long)d.nl * (d.Kp / BK);
   const bool splittable = allow_split && d.nl > 1 && !d.skip_upper && !d.k_hi_diag && !d.k_lo_diag;
   const float out_mib = (float)d.Mb * (float)d.Nb * 2.0f / 1048576.0f;
@@ -1068,11 +1069,13 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
       const long long wgs = tiles * sp;
       const long long cap = 256LL * c.per_cu;
       const long long rounds = (wgs + cap - 1) / cap;
-      const float resident = (float)(wgs < cap ? wgs : cap) / 256.0f;
-      const float t_slab = c.slab_us + c.slab_us_per_resident * resident;
+      const long long in_round = wgs < cap ? wgs : cap;
+      const int resident = (int)((in_round + 255) / 256);             // workgroups on the fullest CU
+      const float busy = in_round >= 256 ? 1.0f : (float)in_round / 256.0f;  // share of the CUs in use
+      const float t_slab = c.t_lone + (c.t_full - c.t_lone) * busy * busy + c.t_more * (float)(resident - 1);
       const float per_wg = (float)((((slabs + sp - 1) / sp) + 1) & ~1LL) * t_slab;
-      // split: the combine launch, and the fp32 partial tiles written once and read once
-      const float traffic_us = sp > 1 ? 4.0f + 2.0f * sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f : 0.f;
+      // split: the combine launch, and the fp32 partial tiles read back by it (their writes overlap the products)
+      const float traffic_us = sp > 1 ? 4.0f + (float)sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f : 0.f;
       const float cost = c.fixed_us + c.out_us_per_mib * out_mib + (float)rounds * per_wg + traffic_us;
       if (!found || cost < best_cost) {
         found = true;
