@@ -24,8 +24,10 @@ def _probs_blocks(probs, b, n, q):
     return out
 
 
-# (b, s, h, n, q): several tiles per score matrix, ragged s (multiple of 8 only), d = 64 and 128, q = 1
-CASES = [(4, 64, 64, 4, 2), (2, 328, 256, 2, 2), (2, 256, 128, 2, 1), (4, 136, 128, 8, 4)]
+# (b, s, h, n, q): several tiles per score matrix, ragged s (multiple of 8 only), d = 64 and 128, q = 1,
+# config-4-like s = 1024 with d = 128, and the longest sequence the soft-max kernels accept (s = 4096)
+CASES = [(4, 64, 64, 4, 2), (2, 328, 256, 2, 2), (2, 256, 128, 2, 1), (4, 136, 128, 8, 4), (2, 1024, 256, 2, 2),
+         (1, 4096, 64, 1, 1)]
 
 
 @pytest.mark.parametrize("causal", [True, False])
