@@ -237,8 +237,10 @@ typedef struct {
  * it forks from and joins back into `stream` with events; when the call
  * returns, every kernel of both is ordered before later work on `stream`.
  * The library creates that stream (default priority) and its events on the
- * first call per device; if that first call is made under stream capture and
- * they cannot be created, the branch runs on `stream` itself.) */
+ * first call per device that is not made under stream capture; until then the
+ * branch runs on `stream` itself.  They are shared by all calls on a device:
+ * optimus_layer_bwd must not be called from several host threads at once
+ * for the same device.) */
 size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg);
 int optimus_layer_fwd(const optimus_layer_cfg* cfg, const optimus_layer_tensors* t, int i, int j,
                       void* ws, size_t ws_bytes, void* stream);

@@ -289,9 +289,10 @@ void layer_gemms(const optimus_layer_cfg* c, LayerGemm out[12]) {
 // The parameter gradients of the backward pass (A^T B products, bias column sums) hang off the chain of activation
 // gradients but nothing in the chain waits for them: they run on a second stream of the library, forked from and
 // joined back into the caller's stream with events (also valid under stream capture: the branch becomes a parallel
-// arm of the graph).  One stream and one set of events per device, created on first use; if they cannot be
-// created (for example because the very first call is made while the caller captures a graph), the branch simply
-// runs on the caller's stream.
+// arm of the graph).  One stream and one set of events per device, created on the first call that is not made
+// under stream capture; until then, or if they cannot be created, the branch simply runs on the caller's stream.
+// The stream and events are shared by all calls on a device: concurrent calls from several host threads on one
+// device are not supported.
 struct SideStream {
   hipStream_t s = nullptr;
   hipEvent_t fork = nullptr, join = nullptr, ready[3] = {nullptr, nullptr, nullptr};
@@ -300,11 +301,16 @@ struct SideStream {
 constexpr int kMaxDevices = 64;
 SideStream g_side[kMaxDevices];
 
-SideStream* side_stream() {
+SideStream* side_stream(hipStream_t caller) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
   SideStream& x = g_side[dev];
   if (x.state == 0) {
+    // creating a stream while the caller captures a graph is not allowed (and would invalidate the capture):
+    // stay on the caller's stream for this call and try again on a later one
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(caller, &cs) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    if (cs != hipStreamCaptureStatusNone) return nullptr;
     bool ok = hipStreamCreateWithFlags(&x.s, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&x.fork, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&x.join, hipEventDisableTiming) == hipSuccess;
@@ -535,7 +541,7 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   LnDesc ln;
   if ((rc = ln_desc(M, h, q, i, j, dt, c->eps, &ln))) return rc;
   // gradient branch: its own stream and its own split workspace (see SideStream)
-  SideStream* ss = side_stream();
+  SideStream* ss = side_stream(st);
   hipStream_t gst = ss ? ss->s : st;
   void* gstream = (void*)gst;
   void* grad_ws = ss ? (char*)gemm_ws + gemm_bytes : gemm_ws;

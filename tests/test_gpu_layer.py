@@ -149,3 +149,51 @@ def test_layer_errors():
     with pytest.raises(opt.OptimusError) as e:
         opt.layer_fwd(cfg, opt.make_layer_tensors(T2), -1, -1, ws)
     assert e.value.code == opt.EINVAL
+
+
+def test_first_call_under_graph_capture_then_eager():
+    """In a fresh process the very first layer_fwd/layer_bwd calls are made while a HIP graph is being captured
+    (the library must not create its gradient-branch stream there); replays, then eager calls (which do create it),
+    then a second captured graph with the forked branch: all give the same bits."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = r'''
+import sys
+sys.path.insert(0, ROOT); sys.path.insert(0, ROOT + "/tests")
+import torch
+import paper_2104_05343_amd as opt
+from workloads import LayerShape, layer_inputs
+from layer_util import alloc_layer
+shp = LayerShape(b=4, s=64, h=128, n=4, q=2)
+inp = layer_inputs(3, shp, "bf16", perturb_affine=True)
+cfg, T, lt, ws = alloc_layer(inp, shp, True)
+def step():
+    opt.layer_fwd(cfg, lt, -1, -1, ws)
+    opt.layer_bwd(cfg, lt, -1, -1, ws)
+def snap():
+    torch.cuda.synchronize()
+    return {k: v.clone() for k, v in T.items()}
+def same(a, b):
+    return all(torch.equal(a[k].view(torch.uint8), b[k].view(torch.uint8)) for k in a)
+side = torch.cuda.Stream()
+with torch.cuda.stream(side):
+    g1 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g1):
+        step()
+g1.replay(); r1 = snap()
+g1.replay(); r2 = snap()
+step(); e1 = snap()
+g2 = torch.cuda.CUDAGraph()
+with torch.cuda.graph(g2):
+    step()
+g2.replay(); r3 = snap()
+step(); e2 = snap()
+g2.replay(); r4 = snap()
+assert same(r1, r2) and same(r1, e1) and same(r1, r3) and same(r1, e2) and same(r1, r4)
+assert not any(torch.isnan(v.float()).any().item() for k, v in r1.items() if k in ("out", "d_x", "d_w1", "d_b1"))
+print("capture-first ok")
+'''.replace("ROOT", repr(root))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and "capture-first ok" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
