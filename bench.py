@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="config2", choices=["config2", "config4", "config5"])
     ap.add_argument("--device-coords", default="1,2", help="device (i,j) whose share is timed")
-    ap.add_argument("--gemm-reps", type=int, default=30)
+    ap.add_argument("--gemm-reps", type=int, default=50)
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-config GEMM table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--pmc-probe", action="store_true",
@@ -325,6 +325,16 @@ def main():
         "paper_context": {"training_speedup_vs_megatron_64gpu": 1.48, "inference_speedup_vs_megatron_64gpu": 1.78,
                           "hardware": "64x Quadro RTX 5000, TACC Frontera (other machine: context, not a target)"},
     }
+
+    if not args.no_sweep and args.workload == "config2":
+        # the same forward products launched for the whole grid at once (i = j = -1: all q*q devices' blocks)
+        fwd = [g for g in gemms if g[0] in ("qkv.ab", "mlp_up.ab", "mlp_down.ab")]
+        grid_rows = time_gemms(opt, torch, fwd, q, -1, -1, max(10, args.gemm_reps // 2), 77, rotating=False)
+        for r in grid_rows:   # time_gemms counts one device's flops: the grid launch does q*q times as much
+            r["tflops"] = round(r["tflops"] * q * q, 1)
+            r["pct_peak"] = round(100 * r["tflops"] / PEAK_BF16_TFLOPS, 1)
+            r["devices"] = q * q
+        out["grid_launch"] = grid_rows
 
     if not args.no_sweep:
         from workloads import gemm_cases
