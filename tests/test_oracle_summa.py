@@ -154,3 +154,29 @@ def test_flop_accounting_table1():
     assert linear + attn == flops.forward_mults_per_device(b, s, h, p)
     assert flops.backward_mults_per_device(b, s, h, p) == 3 * (linear + attn)
     assert flops.backward_mults_per_device(b, s, h, p, recompute=False) == 2 * (linear + attn)
+
+
+def _table1():
+    import os
+    rows = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "table1_costs.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, c1, c2 = line.split()
+                rows[name] = (int(c1), int(c2))
+    return rows
+
+
+@pytest.mark.parametrize("b,s,h,p", [(8, 512, 1024, 16), (32, 512, 3072, 64), (8, 1024, 4096, 16), (4, 64, 128, 4)])
+def test_counts_against_the_papers_table1(b, s, h, p):
+    """The coefficients printed in Table 1 (fixture) against the oracle's counts, which are built from the shapes of
+    the layer's products and not from these coefficients."""
+    t = _table1()
+    c1, c2 = t["forward_computation"]
+    assert flops.forward_mults_per_device(b, s, h, p) == (c1 * b * s * h * h + c2 * b * s * s * h) // p
+    c1, c2 = t["backward_computation"]
+    assert flops.backward_mults_per_device(b, s, h, p) == (c1 * b * s * h * h + c2 * b * s * s * h) // p
+    c1, c2 = t["forward_communication"]
+    assert flops.forward_operand_scalars(b, s, h) == c1 * b * s * h + c2 * h * h
+    c1, c2 = t["backward_communication"]
+    assert 3 * flops.forward_operand_scalars(b, s, h) == c1 * b * s * h + c2 * h * h
