@@ -32,6 +32,21 @@ def head_forward(Q, K, V, causal=True):
     return P @ V, P
 
 
+def head_logsumexp(Q, K, causal=True):
+    """Row-wise log-sum-exp of the scaled (and masked) scores of one (sequence, head):
+    L_t = log sum_u exp(S_tu), so that the soft-max row is P_tu = exp(S_tu - L_t).  It is the one
+    per-row number an attention that never stores P (the operator fusion the paper's conclusion
+    proposes) keeps for the backward pass."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    s, d = Q.shape
+    S = (Q @ K.T) / np.sqrt(d)
+    if causal:
+        S = np.where(np.tril(np.ones((s, s), dtype=bool)), S, -np.inf)
+    m = S.max(axis=1)
+    return m + np.log(np.exp(S - m[:, None]).sum(axis=1))
+
+
 def head_backward(Q, K, V, P, dO, store=None):
     """Gradients for one (sequence, head).
 
@@ -85,6 +100,17 @@ def forward(qkv, b, s, n, causal=True, keep_probs=True, store=None):
             if keep_probs:
                 probs[seq, head] = P
     return out, probs
+
+
+def logsumexp(qkv, b, s, n, causal=True):
+    """qkv [b*s, 3h] -> L [b, n, s]: head_logsumexp of every (sequence, head)."""
+    qkv = np.asarray(qkv, dtype=np.float64)
+    out = np.empty((b, n, s))
+    for seq in range(b):
+        for head in range(n):
+            Q, K, _ = split_qkv(qkv, b, s, n, seq, head)
+            out[seq, head] = head_logsumexp(Q, K, causal)
+    return out
 
 
 def backward(qkv, d_attn, b, s, n, causal=True, probs=None, store=None):

@@ -76,3 +76,57 @@ def test_full_forward_is_per_head_loop_and_backward_fd():
         m[idx] -= hstep
         fd = (np.sum(R * att.forward(p, b, s, n, True, False)[0]) - np.sum(R * att.forward(m, b, s, n, True, False)[0])) / (2 * hstep)
         assert abs(fd - dqkv[idx]) < 1e-6, idx
+
+
+def test_logsumexp_closed_forms_brute_force_and_library():
+    """L_t = log sum_u exp(S_tu): brute force, Q = 0 (L_t = log of the number of visible keys),
+    all keys equal, scipy's logsumexp on independently built scores, and P = exp(S - L)."""
+    from scipy.special import logsumexp as sp_lse
+    rng = np.random.default_rng(3)
+    s, d = 9, 4
+    Q, K, V = (rng.standard_normal((s, d)) for _ in range(3))
+    for causal in (True, False):
+        L = att.head_logsumexp(Q, K, causal)
+        for t in range(s):
+            last = t if causal else s - 1
+            sc = [sum(Q[t, e] * K[u, e] for e in range(d)) / math.sqrt(d) for u in range(last + 1)]
+            assert abs(L[t] - math.log(sum(math.exp(v) for v in sc))) < 1e-12
+        S = np.einsum("te,ue->tu", Q, K) / math.sqrt(d)
+        if causal:
+            S[np.triu_indices(s, 1)] = -np.inf
+        assert np.allclose(L, sp_lse(S, axis=1), atol=1e-13)
+        _, P = att.head_forward(Q, K, V, causal)
+        with np.errstate(divide="ignore"):
+            assert np.allclose(np.exp(S - L[:, None]), P, atol=1e-14)
+        L0 = att.head_logsumexp(np.zeros_like(Q), K, causal)
+        want = np.log(np.arange(1, s + 1)) if causal else np.full(s, math.log(s))
+        assert np.allclose(L0, want, atol=1e-14)
+    # all keys equal: every visible score of row t is the same number c_t -> L_t = c_t + log(#visible)
+    Kc = np.tile(rng.standard_normal((1, d)), (s, 1))
+    c = Q @ Kc[0] / math.sqrt(d)
+    assert np.allclose(att.head_logsumexp(Q, Kc, True), c + np.log(np.arange(1, s + 1)), atol=1e-13)
+    # the [b, n, s] wrapper is the per-head loop
+    b, n = 2, 2
+    qkv = rng.standard_normal((b * s, 3 * n * d))
+    Lall = att.logsumexp(qkv, b, s, n, True)
+    Qh, Kh, _ = att.split_qkv(qkv, b, s, n, 1, 0)
+    assert Lall.shape == (b, n, s) and np.array_equal(Lall[1, 0], att.head_logsumexp(Qh, Kh, True))
+
+
+def test_backward_row_term_equals_output_form():
+    """rowsum(dP * P) = rowsum(dO * O): the identity that lets a backward pass without saved P use the saved
+    output instead; and the gradients from probabilities rebuilt as exp(S - L) equal the oracle's."""
+    rng = np.random.default_rng(4)
+    s, d = 8, 5
+    Q, K, V, dO = (rng.standard_normal((s, d)) for _ in range(4))
+    for causal in (True, False):
+        O, P = att.head_forward(Q, K, V, causal)
+        dP = dO @ V.T
+        assert np.allclose((dP * P).sum(axis=1), (dO * O).sum(axis=1), atol=1e-13)
+        S = Q @ K.T / math.sqrt(d)
+        if causal:
+            S[np.triu_indices(s, 1)] = -np.inf
+        with np.errstate(divide="ignore"):
+            P2 = np.exp(S - att.head_logsumexp(Q, K, causal)[:, None])
+        for a_, b_ in zip(att.head_backward(Q, K, V, P, dO), att.head_backward(Q, K, V, P2, dO)):
+            assert np.allclose(a_, b_, atol=1e-13)
