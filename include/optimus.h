@@ -174,6 +174,22 @@ int optimus_attention_bwd(const void* qkv, const void* probs, const void* d_attn
                           size_t ws_bytes, void* stream);
 size_t optimus_attention_workspace_bytes(int b, int s, int h, int n, int q);
 
+/* ---- the same attention without the [s x s] tensors (the operator fusion proposed in Section 6) ----
+ * Same qkv / attn / d_qkv layouts and the same mathematics as above, but neither scores nor probabilities are
+ * ever written to memory, so sequence length is no longer bounded by the [b/q, n/q, s, s] tensor.  The forward
+ * keeps, per query row, lse = log sum_u exp(S_tu) (natural logarithm of the scaled, masked scores):
+ * lse is [q][q][(b/q)*(n/q)][s] fp32 in device order; the backward rebuilds P = exp(S - lse) tile by tile and
+ * uses rowsum(dO * O) for rowsum(dP * P), so it also reads the forward's attn output.
+ * Device memory, all of them; ws (backward only) must hold optimus_attention_fused_workspace_bytes(...) bytes.
+ * bf16 only; head width d = h/n must be 64 or 128 (OPTIMUS_ESHAPE otherwise); any s >= 1 up to 2^20;
+ * requires q | b, q | n, n | h. */
+int optimus_attention_fused_fwd(const void* qkv, void* attn, float* lse, int b, int s, int h, int n, int q,
+                                int i, int j, int causal, int dtype, void* stream);
+int optimus_attention_fused_bwd(const void* qkv, const void* attn, const float* lse, const void* d_attn,
+                                void* d_qkv, int b, int s, int h, int n, int q, int i, int j, int causal,
+                                int dtype, void* ws, size_t ws_bytes, void* stream);
+size_t optimus_attention_fused_workspace_bytes(int b, int s, int h, int n, int q);
+
 /* ---- one transformer layer on device (i, j) (Section 3.2; Eq. 1) ----
  * Wiring: a1 = LN1(x); qkv = a1 Wqkv + b; attn = local attention;
  * h_mid = x + attn Wo + b; a2 = LN2(h_mid); pre = a2 W1 + b; g = GeLU(pre);

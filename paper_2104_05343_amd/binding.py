@@ -72,6 +72,9 @@ SIGNATURES = {
     "optimus_attention_fwd": (_INT, [_P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
     "optimus_attention_bwd": (_INT, [_P, _P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
     "optimus_attention_workspace_bytes": (_SZ, [_INT, _INT, _INT, _INT, _INT]),
+    "optimus_attention_fused_fwd": (_INT, [_P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P]),
+    "optimus_attention_fused_bwd": (_INT, [_P, _P, _P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
+    "optimus_attention_fused_workspace_bytes": (_SZ, [_INT, _INT, _INT, _INT, _INT]),
     "optimus_layer_workspace_bytes": (_SZ, [C.POINTER(LayerCfg)]),
     "optimus_layer_fwd": (_INT, [C.POINTER(LayerCfg), C.POINTER(LayerTensors), _INT, _INT, _P, _SZ, _P]),
     "optimus_layer_bwd": (_INT, [C.POINTER(LayerCfg), C.POINTER(LayerTensors), _INT, _INT, _P, _SZ, _P]),
@@ -212,6 +215,21 @@ def attention_bwd(qkv, probs, d_attn, d_qkv, b, s, h, n, q, i, j, causal, dtype,
     p, nb = _ws(ws)
     _check(lib().optimus_attention_bwd(_ptr(qkv), _ptr(probs), _ptr(d_attn), _ptr(d_qkv), b, s, h, n, q, i, j, int(causal), dtype,
                                        p, nb, _stream(stream)), "optimus_attention_bwd")
+
+
+def attention_fused_workspace_bytes(b, s, h, n, q) -> int:
+    return lib().optimus_attention_fused_workspace_bytes(b, s, h, n, q)
+
+
+def attention_fused_fwd(qkv, attn, lse, b, s, h, n, q, i, j, causal, dtype, stream=None):
+    _check(lib().optimus_attention_fused_fwd(_ptr(qkv), _ptr(attn), _ptr(lse), b, s, h, n, q, i, j, int(causal), dtype,
+                                             _stream(stream)), "optimus_attention_fused_fwd")
+
+
+def attention_fused_bwd(qkv, attn, lse, d_attn, d_qkv, b, s, h, n, q, i, j, causal, dtype, ws, stream=None):
+    p, nb = _ws(ws)
+    _check(lib().optimus_attention_fused_bwd(_ptr(qkv), _ptr(attn), _ptr(lse), _ptr(d_attn), _ptr(d_qkv), b, s, h, n, q, i, j,
+                                             int(causal), dtype, p, nb, _stream(stream)), "optimus_attention_fused_bwd")
 
 
 def layer_workspace_bytes(cfg: LayerCfg) -> int:

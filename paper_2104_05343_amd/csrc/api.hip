@@ -223,6 +223,46 @@ int run_attention(bool bwd, const void* qkv, const void* probs_in, void* probs_o
   return OPTIMUS_OK;
 }
 
+// Fused attention: same block geometry, no [s x s] tensors, head width limited to what the kernels are built for.
+int attn_fused_dims(int b, int s, int h, int n, int q, AttnDims* a) {
+  if (q <= 0 || b <= 0 || s <= 0 || h <= 0 || n <= 0) return OPTIMUS_ESHAPE;
+  if (b % q || n % q || h % n) return OPTIMUS_ESHAPE;
+  a->nb = b / q; a->nh = n / q; a->d = h / n; a->s = s;
+  if (!attn_fused_supported(a->d) || s > (1 << 20)) return OPTIMUS_ESHAPE;
+  a->ld = 3 * h / q; a->ldo = h / q;
+  a->blk_qkv = (long long)a->nb * s * a->ld;
+  a->blk_attn = (long long)a->nb * s * a->ldo;
+  a->nmat = (long long)a->nb * a->nh;
+  a->blk_probs = 0;
+  if (a->nmat > 65535) return OPTIMUS_ESHAPE;
+  return OPTIMUS_OK;
+}
+size_t attn_fused_ws_bytes(const AttnDims& a, int q) { return align256((size_t)q * q * a.nmat * a.s * sizeof(float)); }
+
+int run_attention_fused(bool bwd, const void* qkv, void* attn, float* lse, const void* d_attn, void* d_qkv, int b, int s, int h,
+                        int n, int q, int i, int j, int causal, int dtype, void* ws, size_t ws_bytes, void* stream) {
+  if (dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  AttnDims a;
+  int rc = attn_fused_dims(b, s, h, n, q, &a);
+  if (rc) return rc;
+  if ((rc = check_coords(q, i, j))) return rc;
+  if (bwd && (!ws || ws_bytes < attn_fused_ws_bytes(a, q))) return OPTIMUS_EWORKSPACE;
+  const bool grid = is_grid(i, j);
+  const long long dev = grid ? 0 : (long long)i * q + j;
+  AttnFusedDesc d = {};
+  d.qkv = (const bf16_t*)qkv + dev * a.blk_qkv;
+  d.attn = (bf16_t*)attn + dev * a.blk_attn;
+  d.lse = lse + dev * a.nmat * s;
+  d.d_attn = d_attn ? (const bf16_t*)d_attn + dev * a.blk_attn : nullptr;
+  d.d_qkv = d_qkv ? (bf16_t*)d_qkv + dev * a.blk_qkv : nullptr;
+  d.delta = (float*)ws;
+  d.s = s; d.d = a.d; d.nb = a.nb; d.nh = a.nh; d.ld = a.ld; d.ldo = a.ldo;
+  d.ndev = grid ? q * q : 1;
+  d.dev_qkv = a.blk_qkv; d.dev_attn = a.blk_attn;
+  d.causal = causal;
+  return bwd ? launch_attn_fused_bwd(d, as_stream(stream)) : launch_attn_fused_fwd(d, as_stream(stream));
+}
+
 int ln_desc(int64_t M, int64_t H, int q, int i, int j, int dtype, float eps, LnDesc* d) {
   if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
   if (q <= 0 || M <= 0 || H <= 0 || M % q || H % q) return OPTIMUS_ESHAPE;
@@ -461,6 +501,23 @@ int optimus_attention_bwd(const void* qkv, const void* probs, const void* d_attn
                           int i, int j, int causal, int dtype, void* ws, size_t ws_bytes, void* stream) {
   if (!qkv || !probs || !d_attn || !d_qkv) return OPTIMUS_EINVAL;
   return run_attention(true, qkv, probs, nullptr, d_attn, d_qkv, b, s, h, n, q, i, j, causal ? 1 : 0, dtype, ws, ws_bytes, stream);
+}
+
+size_t optimus_attention_fused_workspace_bytes(int b, int s, int h, int n, int q) {
+  AttnDims a;
+  if (attn_fused_dims(b, s, h, n, q, &a)) return 0;
+  return attn_fused_ws_bytes(a, q);
+}
+int optimus_attention_fused_fwd(const void* qkv, void* attn, float* lse, int b, int s, int h, int n, int q, int i, int j, int causal,
+                                int dtype, void* stream) {
+  if (!qkv || !attn || !lse) return OPTIMUS_EINVAL;
+  return run_attention_fused(false, qkv, attn, lse, nullptr, nullptr, b, s, h, n, q, i, j, causal ? 1 : 0, dtype, nullptr, 0, stream);
+}
+int optimus_attention_fused_bwd(const void* qkv, const void* attn, const float* lse, const void* d_attn, void* d_qkv, int b, int s,
+                                int h, int n, int q, int i, int j, int causal, int dtype, void* ws, size_t ws_bytes, void* stream) {
+  if (!qkv || !attn || !lse || !d_attn || !d_qkv) return OPTIMUS_EINVAL;
+  return run_attention_fused(true, qkv, const_cast<void*>(attn), const_cast<float*>(lse), d_attn, d_qkv, b, s, h, n, q, i, j,
+                             causal ? 1 : 0, dtype, ws, ws_bytes, stream);
 }
 
 size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg) {

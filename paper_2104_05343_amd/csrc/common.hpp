@@ -126,6 +126,22 @@ int launch_softmax_fwd(const float* S, void* P, int nmat, int s, int causal, hip
 // dS = P * (dP - rowsum(dP * P)); dP fp32, P bf16, dS bf16
 int launch_softmax_bwd(const float* dP, const void* P, void* dS, int nmat, int s, int causal, hipStream_t stream);
 
+// Fused local attention (no [s x s] tensor in memory) for ndev consecutive device blocks of one launch.
+struct AttnFusedDesc {
+  const void* qkv;      // first device block, [nb*s x ld] per device
+  void* attn;           // [nb*s x ldo] per device: written by the forward, read by the backward
+  float* lse;           // [ndev][nb*nh][s]: log sum exp of the scaled scores of every row
+  const void* d_attn;   // backward only
+  void* d_qkv;          // backward only
+  float* delta;         // backward scratch [ndev][nb*nh][s]
+  int s, d, nb, nh, ld, ldo, ndev;
+  long long dev_qkv, dev_attn;  // element strides between consecutive device blocks
+  int causal;
+};
+bool attn_fused_supported(int d);
+int launch_attn_fused_fwd(const AttnFusedDesc& d, hipStream_t stream);
+int launch_attn_fused_bwd(const AttnFusedDesc& d, hipStream_t stream);
+
 inline int hip_launch_status() { return hipGetLastError() == hipSuccess ? OPTIMUS_OK : OPTIMUS_EHIP; }
 
 }  // namespace optimus

@@ -51,6 +51,12 @@ def test_host_validation_without_gpu():
     assert L.optimus_attention_fwd(one, one, one, 4, 64, 64, 4, 2, 0, 0, 1, 1, None, 0, None) == opt.EWORKSPACE
     assert L.optimus_attention_fwd(one, one, one, 3, 64, 64, 4, 2, 0, 0, 1, 1, one, 1 << 30, None) == opt.ESHAPE
     assert L.optimus_attention_fwd(one, one, one, 4, 64, 64, 4, 2, 0, 0, 1, 0, one, 1 << 30, None) == opt.EDTYPE
+    assert L.optimus_attention_fused_fwd(one, one, one, 4, 64, 64, 4, 2, 0, 0, 1, 1, None) == opt.ESHAPE      # d = 16
+    assert L.optimus_attention_fused_fwd(one, one, one, 4, 64, 128, 2, 2, 0, 0, 1, 0, None) == opt.EDTYPE
+    assert L.optimus_attention_fused_fwd(one, one, one, 4, 64, 128, 2, 2, 2, 0, 1, 1, None) == opt.ECOORD
+    assert L.optimus_attention_fused_bwd(one, one, one, one, one, 4, 64, 128, 2, 2, 0, 0, 1, 1, None, 0, None) == opt.EWORKSPACE
+    assert L.optimus_attention_fused_workspace_bytes(4, 64, 128, 2, 2) >= 4 * 2 * 64 * 4
+    assert L.optimus_attention_fused_workspace_bytes(4, 64, 64, 4, 2) == 0
 
 
 def test_flop_accounting_matches_table1():
