@@ -203,6 +203,18 @@ def time_bandwidth(opt, torch, b, s, h, n, q, i, j, reps, seed):
     ms = event_time_ms(lambda: opt.attention_bwd(qkv, probs, d_attn, d_qkv, b, s, h, n, q, i, j, True, opt.BF16, aws), reps)
     out["attention_bwd"] = {"us": round(ms * 1e3, 2), "kernels": 5,
                             "noncausal_equiv_tflops": round(2 * att_flops / (ms * 1e-3) / 1e12, 1)}
+    # the same attention without the [s x s] tensors (head widths 64 and 128 only)
+    if d in (64, 128):
+        lse = torch.empty(q * q * nmat * s, dtype=torch.float32, device="cuda:0")
+        fws = torch.empty(opt.attention_fused_workspace_bytes(b, s, h, n, q), dtype=torch.uint8, device="cuda:0")
+        ms = event_time_ms(lambda: opt.attention_fused_fwd(qkv, attn, lse, b, s, h, n, q, i, j, True, opt.BF16), reps)
+        out["attention_fused_fwd"] = {"us": round(ms * 1e3, 2), "kernels": 1,
+                                      "noncausal_equiv_tflops": round(att_flops / (ms * 1e-3) / 1e12, 1),
+                                      "causal_useful_tflops": round(att_flops / 2 / (ms * 1e-3) / 1e12, 1)}
+        ms = event_time_ms(lambda: opt.attention_fused_bwd(qkv, attn, lse, d_attn, d_qkv, b, s, h, n, q, i, j, True, opt.BF16,
+                                                           fws), reps)
+        out["attention_fused_bwd"] = {"us": round(ms * 1e3, 2), "kernels": 2,
+                                      "noncausal_equiv_tflops": round(2 * att_flops / (ms * 1e-3) / 1e12, 1)}
     return out
 
 

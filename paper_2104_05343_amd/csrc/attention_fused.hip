@@ -7,7 +7,7 @@
 // and uses rowsum(dO * O) in place of rowsum(dP * P).
 //
 // Layout of the work (all three kernels): one wavefront owns 32 rows (queries in the forward and dQ kernels, keys in
-// the dK/dV kernel) for the whole loop over blocks of the other index; four wavefronts share the blocks of the other
+// the dK/dV kernel) for the whole loop over blocks of the other index; two or four wavefronts share the blocks of the other
 // operands through LDS (double buffered, one barrier per block).  Every product is v_mfma_f32_32x32x16_bf16 with
 // the operand that carries the wavefront's own rows in the B slot, so that a lane's 16 accumulator values of a 32x32
 // tile all belong to ONE of its rows (lane % 32) and the other 16 live in lane ^ 32: row maxima and sums are 16
@@ -98,16 +98,16 @@ __device__ __forceinline__ f32x16 zero16() {
 }
 
 // Cooperative copy of a [ROWS][D] bf16 tile (rows row0.. of a matrix with leading dimension ld, clamped to the last
-// valid row) global -> registers, and registers -> LDS in one or both layouts.  256 threads.
-template <int ROWS, int D>
+// valid row) global -> registers, and registers -> LDS in one or both layouts, by a workgroup of THREADS threads.
+template <int ROWS, int D, int THREADS>
 struct TileCopy {
-  static constexpr int CH = D / 8, PER = ROWS * CH / 256;
-  static_assert(ROWS * CH % 256 == 0, "tile must divide over 256 threads");
+  static constexpr int CH = D / 8, PER = ROWS * CH / THREADS;
+  static_assert(ROWS * CH % THREADS == 0, "tile must divide over the workgroup");
   u32x4 r[PER];
   __device__ __forceinline__ void load(const bf16_t* base, int ld, int row0, int last_row, int tid) {
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
-      const int c = tid + it * 256;
+      const int c = tid + it * THREADS;
       const int row = min(row0 + c / CH, last_row);
       r[it] = *(const u32x4*)(base + (long long)row * ld + (c % CH) * 8);
     }
@@ -116,7 +116,7 @@ struct TileCopy {
   __device__ __forceinline__ void store(bf16_t* tile_rows, bf16_t* tile_cols, int tid) const {
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
-      const int c = tid + it * 256;
+      const int c = tid + it * THREADS;
       if (ALONG_ROWS) *(u32x4*)(tile_rows + off_kc<D>(c / CH, c % CH)) = r[it];
       if (DOWN_COLS) *(u32x4*)(tile_cols + off_ks<D>(c / CH, (c % CH) * 8)) = r[it];
     }
@@ -124,9 +124,9 @@ struct TileCopy {
 };
 
 // ---------------------------------------------------------------- forward
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fused_fwd_kernel(FusedArgs a) {
-  constexpr int BQ = 128, BKEY = 64, KS = D / 16, DT = D / 32;
+template <int D, bool CAUSAL, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_fused_fwd_kernel(FusedArgs a) {
+  constexpr int BQ = NW * 32, BKEY = 64, KS = D / 16, DT = D / 32, THREADS = NW * 64;
   __shared__ __attribute__((aligned(16))) bf16_t ldsK[2][BKEY * D];
   __shared__ __attribute__((aligned(16))) bf16_t ldsV[2][BKEY * D];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(256) void attn_fused_fwd_kernel(FusedArgs a) {
   for (int dt = 0; dt < DT; ++dt) oacc[dt] = zero16();
   float m_run = -INFINITY, l_run = 0.f;
 
-  TileCopy<BKEY, D> ck, cv;
+  TileCopy<BKEY, D, THREADS> ck, cv;
   ck.load(Kp, a.ld, 0, s - 1, tid);
   cv.load(Vp, a.ld, 0, s - 1, tid);
   ck.template store<true, false>(ldsK[0], nullptr, tid);
@@ -177,36 +177,42 @@ __global__ __launch_bounds__(256) void attn_fused_fwd_kernel(FusedArgs a) {
       }
       // keys of this block past the row's limit exist only in the last blocks of the loop (wave-uniform test)
       const bool need_mask = CAUSAL ? (kbase + BKEY - 1 > q0) : (kbase + BKEY > s);
+      if (need_mask) {
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kbase + t2 * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+            if (key > limit) sacc[t2][r] = -INFINITY;
+          }
+      }
       float mx = -INFINITY;
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kbase + t2 * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          float v = sacc[t2][r] * a.scale_log2;
-          if (need_mask && key > limit) v = -INFINITY;
-          sacc[t2][r] = v;
-          mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t2][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * a.scale_log2;  // the scale is positive: it commutes with the maximum
       const float m_new = fmaxf(m_run, mx);  // finite: block 0 holds key 0, visible to every row
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
       float sum = 0.f;
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(sacc[t2][r] - m_new);
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[t2][r], a.scale_log2, -m_new));  // masked: exp2(-inf) = 0
           sacc[t2][r] = p;
           sum += p;
         }
       sum += __shfl_xor(sum, 32, 64);
-      l_run = l_run * alpha + sum;
-      m_run = m_new;
+      if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {  // some row's maximum moved: rescale what was accumulated
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+        m_run = m_new;
+      }
+      l_run += sum;
       bf16x8 pf[2][2];
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
@@ -244,9 +250,9 @@ __global__ __launch_bounds__(256) void attn_fused_fwd_kernel(FusedArgs a) {
 }
 
 // ---------------------------------------------------------------- backward, dQ (and rowsum(dO * O))
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fused_bwd_dq_kernel(FusedArgs a) {
-  constexpr int BQ = 128, BKEY = 64, KS = D / 16, DT = D / 32;
+template <int D, bool CAUSAL, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dq_kernel(FusedArgs a) {
+  constexpr int BQ = NW * 32, BKEY = 64, KS = D / 16, DT = D / 32, THREADS = NW * 64;
   __shared__ __attribute__((aligned(16))) bf16_t ldsKr[2][BKEY * D];  // K along rows (for S)
   __shared__ __attribute__((aligned(16))) bf16_t ldsKc[2][BKEY * D];  // K down columns (for dQ)
   __shared__ __attribute__((aligned(16))) bf16_t ldsVr[2][BKEY * D];  // V along rows (for dP)
@@ -288,7 +294,7 @@ __global__ __launch_bounds__(256) void attn_fused_bwd_dq_kernel(FusedArgs a) {
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) dqacc[dt] = zero16();
 
-  TileCopy<BKEY, D> ck, cv;
+  TileCopy<BKEY, D, THREADS> ck, cv;
   ck.load(Kp, a.ld, 0, s - 1, tid);
   cv.load(Vp, a.ld, 0, s - 1, tid);
   ck.template store<true, true>(ldsKr[0], ldsKc[0], tid);
@@ -359,9 +365,9 @@ __global__ __launch_bounds__(256) void attn_fused_bwd_dq_kernel(FusedArgs a) {
 
 // ---------------------------------------------------------------- backward, dK and dV
 // One wavefront owns 32 keys; the loop runs over blocks of BQB queries (from the diagonal on when causal).
-template <int D, bool CAUSAL, int BQB>
-__global__ __launch_bounds__(256) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
-  constexpr int BKW = 128, KS = D / 16, DT = D / 32, T2 = BQB / 32;
+template <int D, bool CAUSAL, int BQB, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
+  constexpr int BKW = NW * 32, KS = D / 16, DT = D / 32, T2 = BQB / 32, THREADS = NW * 64;
   __shared__ __attribute__((aligned(16))) bf16_t ldsQr[2][BQB * D];   // Q along rows (for S)
   __shared__ __attribute__((aligned(16))) bf16_t ldsQc[2][BQB * D];   // Q down columns (for dK)
   __shared__ __attribute__((aligned(16))) bf16_t ldsGr[2][BQB * D];   // dO along rows (for dP)
@@ -398,7 +404,7 @@ __global__ __launch_bounds__(256) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
     dkacc[dt] = zero16();
     dvacc[dt] = zero16();
   }
-  TileCopy<BQB, D> cq, cg;
+  TileCopy<BQB, D, THREADS> cq, cg;
   float lreg = 0.f, dreg = 0.f;
   auto gload = [&](int qb) {
     cq.load(Qp, a.ld, qb * BQB, s - 1, tid);
@@ -518,41 +524,45 @@ bool desc_ok(const AttnFusedDesc& d) {
 
 bool attn_fused_supported(int d) { return d == 64 || d == 128; }
 
+namespace {
+// Four wavefronts (128 rows) per workgroup when that still gives every compute unit a workgroup, two otherwise.
+bool use_two_waves(const AttnFusedDesc& d) { return (long long)((d.s + 127) / 128) * d.nb * d.nh * d.ndev < 256; }
+
+template <int D, int NW>
+void fwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
+  const dim3 grid((d.s + NW * 32 - 1) / (NW * 32), d.nb * d.nh, d.ndev), block(NW * 64);
+  if (d.causal) attn_fused_fwd_kernel<D, true, NW><<<grid, block, 0, st>>>(a);
+  else attn_fused_fwd_kernel<D, false, NW><<<grid, block, 0, st>>>(a);
+}
+template <int D, int NW>
+void bwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
+  constexpr int BQB = D == 128 ? 32 : 64;
+  const dim3 grid((d.s + NW * 32 - 1) / (NW * 32), d.nb * d.nh, d.ndev), block(NW * 64);
+  if (d.causal) {
+    attn_fused_bwd_dq_kernel<D, true, NW><<<grid, block, 0, st>>>(a);
+    attn_fused_bwd_dkv_kernel<D, true, BQB, NW><<<grid, block, 0, st>>>(a);
+  } else {
+    attn_fused_bwd_dq_kernel<D, false, NW><<<grid, block, 0, st>>>(a);
+    attn_fused_bwd_dkv_kernel<D, false, BQB, NW><<<grid, block, 0, st>>>(a);
+  }
+}
+}  // namespace
+
 int launch_attn_fused_fwd(const AttnFusedDesc& d, hipStream_t st) {
   if (!desc_ok(d) || !d.qkv || !d.attn || !d.lse) return OPTIMUS_ESHAPE;
   const FusedArgs a = make_args(d);
-  const dim3 grid((d.s + 127) / 128, d.nb * d.nh, d.ndev), block(256);
-  if (d.d == 64) {
-    if (d.causal) attn_fused_fwd_kernel<64, true><<<grid, block, 0, st>>>(a);
-    else attn_fused_fwd_kernel<64, false><<<grid, block, 0, st>>>(a);
-  } else {
-    if (d.causal) attn_fused_fwd_kernel<128, true><<<grid, block, 0, st>>>(a);
-    else attn_fused_fwd_kernel<128, false><<<grid, block, 0, st>>>(a);
-  }
+  const bool two = use_two_waves(d);
+  if (d.d == 64) two ? fwd_launch<64, 2>(a, d, st) : fwd_launch<64, 4>(a, d, st);
+  else two ? fwd_launch<128, 2>(a, d, st) : fwd_launch<128, 4>(a, d, st);
   return hip_launch_status();
 }
 
 int launch_attn_fused_bwd(const AttnFusedDesc& d, hipStream_t st) {
   if (!desc_ok(d) || !d.qkv || !d.attn || !d.lse || !d.d_attn || !d.d_qkv || !d.delta) return OPTIMUS_ESHAPE;
   const FusedArgs a = make_args(d);
-  const dim3 grid((d.s + 127) / 128, d.nb * d.nh, d.ndev), block(256);
-  if (d.d == 64) {
-    if (d.causal) {
-      attn_fused_bwd_dq_kernel<64, true><<<grid, block, 0, st>>>(a);
-      attn_fused_bwd_dkv_kernel<64, true, 64><<<grid, block, 0, st>>>(a);
-    } else {
-      attn_fused_bwd_dq_kernel<64, false><<<grid, block, 0, st>>>(a);
-      attn_fused_bwd_dkv_kernel<64, false, 64><<<grid, block, 0, st>>>(a);
-    }
-  } else {
-    if (d.causal) {
-      attn_fused_bwd_dq_kernel<128, true><<<grid, block, 0, st>>>(a);
-      attn_fused_bwd_dkv_kernel<128, true, 32><<<grid, block, 0, st>>>(a);
-    } else {
-      attn_fused_bwd_dq_kernel<128, false><<<grid, block, 0, st>>>(a);
-      attn_fused_bwd_dkv_kernel<128, false, 32><<<grid, block, 0, st>>>(a);
-    }
-  }
+  const bool two = use_two_waves(d);
+  if (d.d == 64) two ? bwd_launch<64, 2>(a, d, st) : bwd_launch<64, 4>(a, d, st);
+  else two ? bwd_launch<128, 2>(a, d, st) : bwd_launch<128, 4>(a, d, st);
   return hip_launch_status();
 }
 
