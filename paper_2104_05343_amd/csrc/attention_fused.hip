@@ -6,21 +6,30 @@
 // Forward keeps one fp32 number per query row, L = log sum_u exp(S_tu); backward rebuilds P = exp(S - L) tile by tile
 // and uses rowsum(dO * O) in place of rowsum(dP * P).
 //
-// Layout of the work (all three kernels): one wavefront owns 32 rows (queries in the forward and dQ kernels, keys in
-// the dK/dV kernel) for the whole loop over blocks of the other index; two or four wavefronts share the blocks of the other
-// operands through LDS (double buffered, one barrier per block).  Every product is v_mfma_f32_32x32x16_bf16 with
-// the operand that carries the wavefront's own rows in the B slot, so that a lane's 16 accumulator values of a 32x32
-// tile all belong to ONE of its rows (lane % 32) and the other 16 live in lane ^ 32: row maxima and sums are 16
-// in-lane operations plus one exchange.  The accumulator of S^T (or of S in the dK/dV kernel) is already laid out as
-// the B operand of the next product up to a fixed permutation of the contraction index: accumulator slot r of lane
-// group g = lane / 32 is row 8*(r/4) + 4*g + r%4 of the tile, a 16-wide contraction step takes slots 8u..8u+7, i.e.
-// rows {16u + 4g + 0..3, 16u + 8 + 4g + 0..3}.  A contraction may visit its index in any order as long as both
-// operands agree, so the A operand (V, K, dO or Q read "down the columns" with the transposing LDS read
-// ds_read_b64_tr_b16) is simply fetched in that order.  P and dS therefore never leave registers.
+// Work layout (all three kernels).  A workgroup of four wavefronts owns 64 rows (queries in the forward and dQ
+// kernels, keys in the dK/dV kernel).  Wavefront w works on rows 32*(w & 1).. and on every second 64-wide block of the
+// other index (blocks of parity w >> 1): the loop over the other index is the critical path of these launches (the
+// configurations this library is built for give at most two wavefronts per compute unit), so it is cut in two and
+// the two partial results are merged through LDS at the end (soft-max partials by the usual max / sum rule,
+// gradient partials by addition).
 //
-// LDS tiles: [rows][D] bf16, once with 16-byte chunks XOR-swizzled by the row (read along rows with ds_read_b128),
-// once with 32-byte column granules XOR 2*(row & 3) (read down the columns with the transposing read); both are
-// conflict free on the 64-bank LDS of this part.
+// Every product is v_mfma_f32_32x32x16_bf16 with the operand that carries the wavefront's own rows in the B slot, so
+// that a lane's 16 accumulator values of a 32x32 tile all belong to ONE of its rows (lane % 32) and the other 16
+// live in lane ^ 32: row maxima and sums are 16 in-lane operations plus one half-wave swap.  The accumulator of S^T
+// (S in the dK/dV kernel) is already laid out as the B operand of the next product up to a fixed permutation of the
+// contraction index: accumulator slot r of lane group g = lane / 32 is row 8*(r/4) + 4*g + r%4 of the tile, a 16-wide
+// contraction step takes slots 8u..8u+7, i.e. rows {16u + 4g + 0..3, 16u + 8 + 4g + 0..3}.  A contraction may visit
+// its index in any order as long as both operands agree, so the A operand (V, K, dO or Q read "down the columns" with
+// the transposing LDS read ds_read_b64_tr_b16) is simply fetched in that order.  P and dS never leave registers.
+//
+// Blocks of the other index go global -> LDS directly (buffer_load_dwordx4 ... lds, one KiB per wavefront
+// instruction, no registers, no LDS store instructions), two stages, one barrier per pair of blocks.  One LDS copy
+// of a [rows][D] tile serves both ways of reading it: 16-byte chunk c of row r sits at chunk position c ^ g(r) with
+// g(r) = ((r & 3) << 2) | ((r >> 2) & 3) for 256-byte rows (and the analogous 3-bit form for 128-byte rows, which pair
+// up to span the 64 banks).  Reading along the rows (ds_read_b128, 16 consecutive rows, same chunk) sees 16 distinct
+// positions; the transposing read (4 consecutive rows x 4 consecutive chunks at a time) sees 4 x 4 distinct ones.
+// Since the load is direct, the swizzle is applied on the global side: the lane that writes LDS position p fetches
+// the chunk that belongs there.
 #include "common.hpp"
 
 namespace optimus {
@@ -32,9 +41,13 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LN2 = 0.69314718055994530942f;
+constexpr int BLK = 64;     // rows of one block of the looped index
+constexpr int PAIR = 128;   // two blocks (one per parity) are loaded and consumed per loop iteration
+constexpr int NWAVES = 4;
 
 struct FusedArgs {
   const bf16_t* qkv;     // first device block of the launch
@@ -48,34 +61,30 @@ struct FusedArgs {
   float scale, scale_log2;               // 1/sqrt(d), log2(e)/sqrt(d)
 };
 
-// [rows][D] tile read along the rows: 16-byte chunk index XOR a function of the row that takes 16 values (8 for
-// 128-byte rows, which pair up to span the banks) over 16 consecutive rows.
+// ---- LDS tile [rows][D] bf16, chunk position = chunk ^ g(row) ----
 template <int D>
-__device__ __forceinline__ int off_kc(int row, int chunk) {
-  constexpr int CH = D / 8;
-  const int swz = CH >= 16 ? (row & 15) : ((row / (16 / CH)) & (CH - 1));
-  return row * D + ((chunk ^ swz) << 3);
+__device__ __forceinline__ int swz(int row) {
+  static_assert(D == 64 || D == 128, "head widths built");
+  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
 }
-// [rows][D] tile read down the columns with the transposing read: 32-byte granule XOR 2*(row & 3).
 template <int D>
-__device__ __forceinline__ int off_ks(int row, int col) {
-  return row * D + ((((col >> 4) ^ (((row & 3) << 1) & (D / 16 - 1)))) << 4) + (col & 15);
-}
+__device__ __forceinline__ int tile_off(int row, int chunk) { return row * D + ((chunk ^ swz<D>(row)) << 3); }
 
 // A-operand fragment along the rows: lane holds row (row0 + lane%32), contraction elements 16*ks + 8*(lane/32) + 0..7.
 template <int D>
 __device__ __forceinline__ bf16x8 frag_rows(const bf16_t* tile, int row0, int ks, int lane) {
-  return *(const bf16x8*)(tile + off_kc<D>(row0 + (lane & 31), ks * 2 + (lane >> 5)));
+  return *(const bf16x8*)(tile + tile_off<D>(row0 + (lane & 31), ks * 2 + (lane >> 5)));
 }
 // A-operand fragment down the columns in accumulator order: lane holds column (col0 + lane%32) and the tile rows
-// row0 + 4g + {0..3} and row0 + 8 + 4g + {0..3}, g = lane/32 (row0 a multiple of 16).
+// row0 + 4g + {0..3} and row0 + 8 + 4g + {0..3}, g = lane/32 (row0 a multiple of 16, col0 of 32).
 template <int D>
 __device__ __forceinline__ bf16x8 frag_cols_acc_order(const bf16_t* tile, int row0, int col0, int lane) {
   const int lg = lane & 15;
-  const int col = col0 + (((lane >> 4) & 1) << 4) + ((lg & 3) << 2);
+  const int col = col0 + (((lane >> 4) & 1) << 4) + ((lg & 3) << 2);  // 4 consecutive columns from here
   const int row = row0 + ((lane >> 5) << 2) + (lg >> 2);
-  const bf16_t* p0 = tile + off_ks<D>(row, col);
-  const bf16_t* p1 = p0 + 8 * D;  // row + 8: same (row & 3), same swizzle term
+  const bf16_t* p0 = tile + tile_off<D>(row, col >> 3) + (col & 7);
+  const bf16_t* p1 = tile + tile_off<D>(row + 8, col >> 3) + (col & 7);
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -97,55 +106,95 @@ __device__ __forceinline__ f32x16 zero16() {
   return z;
 }
 
-// Cooperative copy of a [ROWS][D] bf16 tile (rows row0.. of a matrix with leading dimension ld, clamped to the last
-// valid row) global -> registers, and registers -> LDS in one or both layouts, by a workgroup of THREADS threads.
-template <int ROWS, int D, int THREADS>
-struct TileCopy {
-  static constexpr int CH = D / 8, PER = ROWS * CH / THREADS;
-  static_assert(ROWS * CH % THREADS == 0, "tile must divide over the workgroup");
-  u32x4 r[PER];
-  __device__ __forceinline__ void load(const bf16_t* base, int ld, int row0, int last_row, int tid) {
+// The value of the other half-wave's lane (lane ^ 32) combined with the own one.
+__device__ __forceinline__ float halfwave_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halfwave_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// ---- direct global -> LDS copy of a PAIR x D tile (rows row0 .. row0 + 127 of a [s][ld] matrix) by four wavefronts ----
+__device__ __forceinline__ i32x4 make_rsrc(const bf16_t* base) {  // raw buffer, 2 GiB window (offsets used are far below)
+  const unsigned long long p = (unsigned long long)base;  // wave-uniform by construction; say so to the compiler
+  const int lo = __builtin_amdgcn_readfirstlane((int)(unsigned)p);
+  const int hi = __builtin_amdgcn_readfirstlane((int)(unsigned)((p >> 32) & 0xffffu));
+  return i32x4{lo, hi, (int)0x80000000u, 0x00020000};
+}
+template <int D>
+struct PairLoader {
+  static constexpr int CH = D / 8, ROWS_PER_KIB = 64 / CH, PIECES = PAIR * D * 2 / 1024, PER = PIECES / NWAVES;
+  static_assert(PIECES % NWAVES == 0, "tile must divide over the wavefronts");
+  unsigned off[PER];  // byte offsets of this lane's chunks for a tile that lies entirely inside the matrix
+  int ld, wave, lane;
+  __device__ __forceinline__ void init(int ld_, int wave_, int lane_) {
+    ld = ld_; wave = wave_; lane = lane_;
 #pragma unroll
-    for (int it = 0; it < PER; ++it) {
-      const int c = tid + it * THREADS;
-      const int row = min(row0 + c / CH, last_row);
-      r[it] = *(const u32x4*)(base + (long long)row * ld + (c % CH) * 8);
-    }
+    for (int it = 0; it < PER; ++it) off[it] = offset_of(it, 0, 0x7fffffff, 0);
   }
-  template <bool ALONG_ROWS, bool DOWN_COLS>
-  __device__ __forceinline__ void store(bf16_t* tile_rows, bf16_t* tile_cols, int tid) const {
+  // LDS position p = lane of KiB piece (wave*PER + it) is (row, chunk position lane % CH): fetch chunk pos ^ g(row).
+  // The source row is clamped to the last row of the matrix (rows past the end are only ever multiplied by zeros).
+  __device__ __forceinline__ unsigned offset_of(int it, int row0, int last_row, int base_row) const {
+    const int row = (wave * PER + it) * ROWS_PER_KIB + lane / CH;
+    const int chunk = (lane % CH) ^ swz<D>(row);
+    const int src = min(row0 + row, last_row) - base_row;
+    return (unsigned)(src * ld + chunk * 8) * 2u;
+  }
+  // mat: row 0 of the [s][ld] matrix (already offset to the head's columns); tile: LDS destination, PAIR * D elements
+  __device__ __forceinline__ void issue(const bf16_t* mat, int row0, int s, bf16_t* tile) const {
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)tile;
+    if (row0 + PAIR <= s) {
+      const i32x4 rsrc = make_rsrc(mat + (long long)row0 * ld);
 #pragma unroll
-    for (int it = 0; it < PER; ++it) {
-      const int c = tid + it * THREADS;
-      if (ALONG_ROWS) *(u32x4*)(tile_rows + off_kc<D>(c / CH, c % CH)) = r[it];
-      if (DOWN_COLS) *(u32x4*)(tile_cols + off_ks<D>(c / CH, (c % CH) * 8)) = r[it];
+      for (int it = 0; it < PER; ++it) {
+        const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)(wave * PER + it) * 1024u);
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off[it]), "s"(rsrc), "s"(m0v) : "memory");
+      }
+    } else {  // the tile reaches past the last row: clamp (wave-uniform branch, taken for the last pair only)
+      const int base_row = max(0, s - PAIR);
+      const i32x4 rsrc = make_rsrc(mat + (long long)base_row * ld);
+#pragma unroll
+      for (int it = 0; it < PER; ++it) {
+        const unsigned o = offset_of(it, row0, s - 1, base_row);
+        const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)(wave * PER + it) * 1024u);
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(o), "s"(rsrc), "s"(m0v) : "memory");
+      }
     }
   }
 };
 
+// all direct loads of this wavefront have landed, then the workgroup meets
+__device__ __forceinline__ void wait_loads_and_barrier() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+}
+
 // ---------------------------------------------------------------- forward
-template <int D, bool CAUSAL, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_fused_fwd_kernel(FusedArgs a) {
-  constexpr int BQ = NW * 32, BKEY = 64, KS = D / 16, DT = D / 32, THREADS = NW * 64;
-  __shared__ __attribute__((aligned(16))) bf16_t ldsK[2][BKEY * D];
-  __shared__ __attribute__((aligned(16))) bf16_t ldsV[2][BKEY * D];
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_fused_fwd_kernel(FusedArgs a) {
+  constexpr int KS = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];  // [stage][K, V][pair tile]
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rg = wave & 1, par = wave >> 1;
   const int tile = gridDim.x - 1 - blockIdx.x;  // the tiles with the longest causal loops start first
   const int mat = blockIdx.y, dev = blockIdx.z, s = a.s;
   const int seq = mat / a.nh, head = mat % a.nh;
   const bf16_t* Qp = a.qkv + dev * a.dev_qkv + (long long)seq * s * a.ld + head * 3 * D;
   const bf16_t* Kp = Qp + D;
   const bf16_t* Vp = Qp + 2 * D;
-  const int q0 = tile * BQ + wave * 32;
+  const int q0 = tile * BLK + rg * 32;
   const int query = q0 + (lane & 31);
   const int qrow = min(query, s - 1);
   bf16x8 qf[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(Qp + (long long)qrow * a.ld + ks * 16 + g * 8);
-  const int wg_hi = min(tile * BQ + BQ, s) - 1;  // last query row of the workgroup
-  const int nkb = CAUSAL ? wg_hi / BKEY + 1 : (s + BKEY - 1) / BKEY;
-  const int wave_nkb = q0 >= s ? 0 : (CAUSAL ? min(q0 + 31, s - 1) / BKEY + 1 : nkb);
+  const int wg_hi = min(tile * BLK + BLK, s) - 1;  // last query row of the workgroup
+  const int nkb = CAUSAL ? wg_hi / BLK + 1 : (s + BLK - 1) / BLK;
+  const int n_it = (nkb + 1) / 2;
+  const int wave_nkb = q0 >= s ? 0 : (CAUSAL ? min(q0 + 31, s - 1) / BLK + 1 : nkb);
   const int limit = CAUSAL ? qrow : s - 1;  // last key this lane's row may see
 
   f32x16 oacc[DT];
@@ -153,30 +202,32 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_fwd_kernel(FusedArgs a) {
   for (int dt = 0; dt < DT; ++dt) oacc[dt] = zero16();
   float m_run = -INFINITY, l_run = 0.f;
 
-  TileCopy<BKEY, D, THREADS> ck, cv;
-  ck.load(Kp, a.ld, 0, s - 1, tid);
-  cv.load(Vp, a.ld, 0, s - 1, tid);
-  ck.template store<true, false>(ldsK[0], nullptr, tid);
-  cv.template store<false, true>(nullptr, ldsV[0], tid);
-  __syncthreads();
-  for (int kb = 0; kb < nkb; ++kb) {
-    const int buf = kb & 1;
-    if (kb + 1 < nkb) {
-      ck.load(Kp, a.ld, (kb + 1) * BKEY, s - 1, tid);
-      cv.load(Vp, a.ld, (kb + 1) * BKEY, s - 1, tid);
+  PairLoader<D> ldr;
+  ldr.init(a.ld, wave, lane);
+  ldr.issue(Kp, 0, s, lds[0][0]);
+  ldr.issue(Vp, 0, s, lds[0][1]);
+  wait_loads_and_barrier();
+  for (int it = 0; it < n_it; ++it) {
+    const int st = it & 1;
+    if (it + 1 < n_it) {
+      ldr.issue(Kp, (it + 1) * PAIR, s, lds[st ^ 1][0]);
+      ldr.issue(Vp, (it + 1) * PAIR, s, lds[st ^ 1][1]);
     }
+    const int kb = 2 * it + par;
     if (kb < wave_nkb) {
-      const int kbase = kb * BKEY;
+      const bf16_t* tK = lds[st][0] + par * BLK * D;
+      const bf16_t* tV = lds[st][1] + par * BLK * D;
+      const int kbase = kb * BLK;
       f32x16 sacc[2];
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
         sacc[t2] = zero16();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          sacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(ldsK[buf], t2 * 32, ks, lane), qf[ks], sacc[t2], 0, 0, 0);
+          sacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(tK, t2 * 32, ks, lane), qf[ks], sacc[t2], 0, 0, 0);
       }
       // keys of this block past the row's limit exist only in the last blocks of the loop (wave-uniform test)
-      const bool need_mask = CAUSAL ? (kbase + BKEY - 1 > q0) : (kbase + BKEY > s);
+      const bool need_mask = CAUSAL ? (kbase + BLK - 1 > q0) : (kbase + BLK > s);
       if (need_mask) {
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
@@ -191,8 +242,10 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_fwd_kernel(FusedArgs a) {
       for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t2][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * a.scale_log2;  // the scale is positive: it commutes with the maximum
-      const float m_new = fmaxf(m_run, mx);  // finite: block 0 holds key 0, visible to every row
+      mx = halfwave_max(mx) * a.scale_log2;  // the scale is positive: it commutes with the maximum
+      // Every block a wavefront works on holds a visible key for each of its rows (the first key of a block is
+      // never past the wavefront's first row), so m_new is finite.
+      const float m_new = fmaxf(m_run, mx);
       float sum = 0.f;
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
@@ -202,7 +255,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_fwd_kernel(FusedArgs a) {
           sacc[t2][r] = p;
           sum += p;
         }
-      sum += __shfl_xor(sum, 32, 64);
+      sum = halfwave_sum(sum);
       if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {  // some row's maximum moved: rescale what was accumulated
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         l_run *= alpha;
@@ -225,46 +278,59 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_fwd_kernel(FusedArgs a) {
         for (int u = 0; u < 2; ++u)
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt)
-            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_acc_order<D>(ldsV[buf], t2 * 32 + u * 16, dt * 32, lane),
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_acc_order<D>(tV, t2 * 32 + u * 16, dt * 32, lane),
                                                                pf[t2][u], oacc[dt], 0, 0, 0);
     }
-    if (kb + 1 < nkb) {
-      ck.template store<true, false>(ldsK[buf ^ 1], nullptr, tid);
-      cv.template store<false, true>(nullptr, ldsV[buf ^ 1], tid);
-    }
-    __syncthreads();
+    wait_loads_and_barrier();
   }
-  if (wave_nkb > 0 && query < s) {
-    const float inv = 1.0f / l_run;
+  // merge the two parities: the odd one hands (m, l, O) over through LDS (all tiles are free after the last barrier)
+  float* xch = (float*)&lds[0][0][0] + rg * (DT * 16 + 2) * 64;
+  if (par == 1) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) xch[(dt * 16 + r) * 64 + lane] = oacc[dt][r];
+    xch[(DT * 16) * 64 + lane] = m_run;
+    xch[(DT * 16 + 1) * 64 + lane] = l_run;
+  }
+  __syncthreads();
+  if (par == 0 && wave_nkb > 0 && query < s) {
+    const float m1 = xch[(DT * 16) * 64 + lane], l1 = xch[(DT * 16 + 1) * 64 + lane];
+    const float m = fmaxf(m_run, m1);  // m_run is finite: block 0 belongs to this parity
+    const float a0 = __builtin_amdgcn_exp2f(m_run - m), a1 = __builtin_amdgcn_exp2f(m1 - m);  // a1 = 0 if the other had no block
+    const float l = l_run * a0 + l1 * a1;
+    const float inv = 1.0f / l;
+    const float w0 = a0 * inv, w1 = a1 * inv;
     bf16_t* Op = a.attn + dev * a.dev_attn + ((long long)seq * s + query) * a.ldo + head * D;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        u32x2 w = {pack2_bf16(oacc[dt][4 * c] * inv, oacc[dt][4 * c + 1] * inv),
-                   pack2_bf16(oacc[dt][4 * c + 2] * inv, oacc[dt][4 * c + 3] * inv)};
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = oacc[dt][4 * c + e] * w0 + xch[(dt * 16 + 4 * c + e) * 64 + lane] * w1;
+        u32x2 w = {pack2_bf16(o[0], o[1]), pack2_bf16(o[2], o[3])};
         *(u32x2*)(Op + dt * 32 + 8 * c + 4 * g) = w;
       }
-    if (g == 0) a.lse[dev * a.dev_vec + (long long)mat * s + query] = (m_run + __log2f(l_run)) * LN2;
+    if (g == 0) a.lse[dev * a.dev_vec + (long long)mat * s + query] = (m + __log2f(l)) * LN2;
   }
 }
 
 // ---------------------------------------------------------------- backward, dQ (and rowsum(dO * O))
-template <int D, bool CAUSAL, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dq_kernel(FusedArgs a) {
-  constexpr int BQ = NW * 32, BKEY = 64, KS = D / 16, DT = D / 32, THREADS = NW * 64;
-  __shared__ __attribute__((aligned(16))) bf16_t ldsKr[2][BKEY * D];  // K along rows (for S)
-  __shared__ __attribute__((aligned(16))) bf16_t ldsKc[2][BKEY * D];  // K down columns (for dQ)
-  __shared__ __attribute__((aligned(16))) bf16_t ldsVr[2][BKEY * D];  // V along rows (for dP)
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_fused_bwd_dq_kernel(FusedArgs a) {
+  constexpr int KS = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];  // [stage][K, V][pair tile]
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rg = wave & 1, par = wave >> 1;
   const int tile = gridDim.x - 1 - blockIdx.x;
   const int mat = blockIdx.y, dev = blockIdx.z, s = a.s;
   const int seq = mat / a.nh, head = mat % a.nh;
   const bf16_t* Qp = a.qkv + dev * a.dev_qkv + (long long)seq * s * a.ld + head * 3 * D;
   const bf16_t* Kp = Qp + D;
   const bf16_t* Vp = Qp + 2 * D;
-  const int q0 = tile * BQ + wave * 32;
+  const int q0 = tile * BLK + rg * 32;
   const int query = q0 + (lane & 31);
   const int qrow = min(query, s - 1);
   const long long orow = dev * a.dev_attn + ((long long)seq * s + qrow) * a.ldo + head * D;
@@ -282,32 +348,35 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dq_kernel(FusedArgs a)
       delta += __uint_as_float(gw[w] << 16) * __uint_as_float(ow[w] << 16) +
                __uint_as_float(gw[w] & 0xffff0000u) * __uint_as_float(ow[w] & 0xffff0000u);
   }
-  delta += __shfl_xor(delta, 32, 64);
-  if (g == 0 && query < s) a.delta[vrow] = delta;
+  delta = halfwave_sum(delta);
+  if (par == 0 && g == 0 && query < s) a.delta[vrow] = delta;
   const float lse2 = a.lse[vrow] * LOG2E;
-  const int wg_hi = min(tile * BQ + BQ, s) - 1;
-  const int nkb = CAUSAL ? wg_hi / BKEY + 1 : (s + BKEY - 1) / BKEY;
-  const int wave_nkb = q0 >= s ? 0 : (CAUSAL ? min(q0 + 31, s - 1) / BKEY + 1 : nkb);
+  const int wg_hi = min(tile * BLK + BLK, s) - 1;
+  const int nkb = CAUSAL ? wg_hi / BLK + 1 : (s + BLK - 1) / BLK;
+  const int n_it = (nkb + 1) / 2;
+  const int wave_nkb = q0 >= s ? 0 : (CAUSAL ? min(q0 + 31, s - 1) / BLK + 1 : nkb);
   const int limit = CAUSAL ? qrow : s - 1;
 
   f32x16 dqacc[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) dqacc[dt] = zero16();
 
-  TileCopy<BKEY, D, THREADS> ck, cv;
-  ck.load(Kp, a.ld, 0, s - 1, tid);
-  cv.load(Vp, a.ld, 0, s - 1, tid);
-  ck.template store<true, true>(ldsKr[0], ldsKc[0], tid);
-  cv.template store<true, false>(ldsVr[0], nullptr, tid);
-  __syncthreads();
-  for (int kb = 0; kb < nkb; ++kb) {
-    const int buf = kb & 1;
-    if (kb + 1 < nkb) {
-      ck.load(Kp, a.ld, (kb + 1) * BKEY, s - 1, tid);
-      cv.load(Vp, a.ld, (kb + 1) * BKEY, s - 1, tid);
+  PairLoader<D> ldr;
+  ldr.init(a.ld, wave, lane);
+  ldr.issue(Kp, 0, s, lds[0][0]);
+  ldr.issue(Vp, 0, s, lds[0][1]);
+  wait_loads_and_barrier();
+  for (int it = 0; it < n_it; ++it) {
+    const int st = it & 1;
+    if (it + 1 < n_it) {
+      ldr.issue(Kp, (it + 1) * PAIR, s, lds[st ^ 1][0]);
+      ldr.issue(Vp, (it + 1) * PAIR, s, lds[st ^ 1][1]);
     }
+    const int kb = 2 * it + par;
     if (kb < wave_nkb) {
-      const int kbase = kb * BKEY;
+      const bf16_t* tK = lds[st][0] + par * BLK * D;
+      const bf16_t* tV = lds[st][1] + par * BLK * D;
+      const int kbase = kb * BLK;
       f32x16 sacc[2], pacc[2];
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
@@ -315,17 +384,17 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dq_kernel(FusedArgs a)
         pacc[t2] = zero16();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          sacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(ldsKr[buf], t2 * 32, ks, lane), qf[ks], sacc[t2], 0, 0, 0);
-          pacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(ldsVr[buf], t2 * 32, ks, lane), dof[ks], pacc[t2], 0, 0, 0);
+          sacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(tK, t2 * 32, ks, lane), qf[ks], sacc[t2], 0, 0, 0);
+          pacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(tV, t2 * 32, ks, lane), dof[ks], pacc[t2], 0, 0, 0);
         }
       }
-      const bool need_mask = CAUSAL ? (kbase + BKEY - 1 > q0) : (kbase + BKEY > s);
+      const bool need_mask = CAUSAL ? (kbase + BLK - 1 > q0) : (kbase + BLK > s);
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = kbase + t2 * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          float p = __builtin_amdgcn_exp2f(sacc[t2][r] * a.scale_log2 - lse2);
+          float p = __builtin_amdgcn_exp2f(fmaf(sacc[t2][r], a.scale_log2, -lse2));
           if (need_mask && key > limit) p = 0.f;
           sacc[t2][r] = p * (pacc[t2][r] - delta);  // dS^T
         }
@@ -341,41 +410,45 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dq_kernel(FusedArgs a)
         for (int u = 0; u < 2; ++u)
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt)
-            dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_acc_order<D>(ldsKc[buf], t2 * 32 + u * 16, dt * 32, lane),
+            dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_acc_order<D>(tK, t2 * 32 + u * 16, dt * 32, lane),
                                                                 dsf[t2][u], dqacc[dt], 0, 0, 0);
     }
-    if (kb + 1 < nkb) {
-      ck.template store<true, true>(ldsKr[buf ^ 1], ldsKc[buf ^ 1], tid);
-      cv.template store<true, false>(ldsVr[buf ^ 1], nullptr, tid);
-    }
-    __syncthreads();
+    wait_loads_and_barrier();
   }
-  if (wave_nkb > 0 && query < s) {
+  float* xch = (float*)&lds[0][0][0] + rg * (DT * 16) * 64;
+  if (par == 1) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) xch[(dt * 16 + r) * 64 + lane] = dqacc[dt][r];
+  }
+  __syncthreads();
+  if (par == 0 && wave_nkb > 0 && query < s) {
     bf16_t* dQp = a.d_qkv + dev * a.dev_qkv + ((long long)seq * s + query) * a.ld + head * 3 * D;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        u32x2 w = {pack2_bf16(dqacc[dt][4 * c] * a.scale, dqacc[dt][4 * c + 1] * a.scale),
-                   pack2_bf16(dqacc[dt][4 * c + 2] * a.scale, dqacc[dt][4 * c + 3] * a.scale)};
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (dqacc[dt][4 * c + e] + xch[(dt * 16 + 4 * c + e) * 64 + lane]) * a.scale;
+        u32x2 w = {pack2_bf16(o[0], o[1]), pack2_bf16(o[2], o[3])};
         *(u32x2*)(dQp + dt * 32 + 8 * c + 4 * g) = w;
       }
   }
 }
 
 // ---------------------------------------------------------------- backward, dK and dV
-// One wavefront owns 32 keys; the loop runs over blocks of BQB queries (from the diagonal on when causal).
-template <int D, bool CAUSAL, int BQB, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
-  constexpr int BKW = NW * 32, KS = D / 16, DT = D / 32, T2 = BQB / 32, THREADS = NW * 64;
-  __shared__ __attribute__((aligned(16))) bf16_t ldsQr[2][BQB * D];   // Q along rows (for S)
-  __shared__ __attribute__((aligned(16))) bf16_t ldsQc[2][BQB * D];   // Q down columns (for dK)
-  __shared__ __attribute__((aligned(16))) bf16_t ldsGr[2][BQB * D];   // dO along rows (for dP)
-  __shared__ __attribute__((aligned(16))) bf16_t ldsGc[2][BQB * D];   // dO down columns (for dV)
-  __shared__ __attribute__((aligned(16))) float ldsL[2][BQB];         // lse * log2(e) of the block's queries
-  __shared__ __attribute__((aligned(16))) float ldsD[2][BQB];         // rowsum(dO * O)
+// A wavefront owns 32 keys and every second block of 64 queries (from the diagonal on when causal).
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
+  constexpr int KS = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];  // [stage][Q, dO][pair tile]
+  __shared__ __attribute__((aligned(16))) float ldsL[2][PAIR];           // lse * log2(e) of the pair's queries
+  __shared__ __attribute__((aligned(16))) float ldsD[2][PAIR];           // rowsum(dO * O)
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rg = wave & 1, par = wave >> 1;
   const int tile = blockIdx.x;  // early key tiles have the longest causal loops
   const int mat = blockIdx.y, dev = blockIdx.z, s = a.s;
   const int seq = mat / a.nh, head = mat % a.nh;
@@ -385,7 +458,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dkv_kernel(FusedArgs a
   const bf16_t* Gp = a.d_attn + dev * a.dev_attn + (long long)seq * s * a.ldo + head * D;
   const float* Lp = a.lse + dev * a.dev_vec + (long long)mat * s;
   const float* Dp = a.delta + dev * a.dev_vec + (long long)mat * s;
-  const int k0 = tile * BKW + wave * 32;
+  const int k0 = tile * BLK + rg * 32;
   const int key = k0 + (lane & 31);
   const int krow = min(key, s - 1);
   bf16x8 kf[KS], vf[KS];
@@ -394,9 +467,10 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dkv_kernel(FusedArgs a
     kf[ks] = *(const bf16x8*)(Kp + (long long)krow * a.ld + ks * 16 + g * 8);
     vf[ks] = *(const bf16x8*)(Vp + (long long)krow * a.ld + ks * 16 + g * 8);
   }
-  const int nqb = (s + BQB - 1) / BQB;
-  const int qb_lo = CAUSAL ? (tile * BKW) / BQB : 0;           // first block with a query >= the first key
-  const int wave_qb_lo = k0 >= s ? nqb : (CAUSAL ? k0 / BQB : 0);
+  const int nqb = (s + BLK - 1) / BLK;
+  const int qb_lo = CAUSAL ? tile : 0;  // first block with a query >= the workgroup's first key (blocks are 64 = its rows)
+  const int n_it = (nqb - qb_lo + 1) / 2;
+  const bool wave_valid = k0 < s;
 
   f32x16 dkacc[DT], dvacc[DT];
 #pragma unroll
@@ -404,62 +478,58 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dkv_kernel(FusedArgs a
     dkacc[dt] = zero16();
     dvacc[dt] = zero16();
   }
-  TileCopy<BQB, D, THREADS> cq, cg;
-  float lreg = 0.f, dreg = 0.f;
-  auto gload = [&](int qb) {
-    cq.load(Qp, a.ld, qb * BQB, s - 1, tid);
-    cg.load(Gp, a.ldo, qb * BQB, s - 1, tid);
-    if (tid < BQB) {
-      const int row = min(qb * BQB + tid, s - 1);
-      lreg = Lp[row] * LOG2E;
-      dreg = Dp[row];
+  PairLoader<D> ldq, ldg;
+  ldq.init(a.ld, wave, lane);
+  ldg.init(a.ldo, wave, lane);
+  auto load_pair = [&](int it, int st) {
+    const int row0 = (qb_lo + 2 * it) * BLK;
+    ldq.issue(Qp, row0, s, lds[st][0]);
+    ldg.issue(Gp, row0, s, lds[st][1]);
+    if (tid < PAIR) {
+      const int row = min(row0 + tid, s - 1);
+      ldsL[st][tid] = Lp[row] * LOG2E;
+      ldsD[st][tid] = Dp[row];
     }
   };
-  auto lstore = [&](int buf) {
-    cq.template store<true, true>(ldsQr[buf], ldsQc[buf], tid);
-    cg.template store<true, true>(ldsGr[buf], ldsGc[buf], tid);
-    if (tid < BQB) {
-      ldsL[buf][tid] = lreg;
-      ldsD[buf][tid] = dreg;
-    }
-  };
-  if (qb_lo < nqb) {
-    gload(qb_lo);
-    lstore(qb_lo & 1);
-  }
-  __syncthreads();
-  for (int qb = qb_lo; qb < nqb; ++qb) {
-    const int buf = qb & 1;
-    if (qb + 1 < nqb) gload(qb + 1);
-    if (qb >= wave_qb_lo) {
-      const int qbase = qb * BQB;
-      f32x16 sacc[T2], pacc[T2];
+  load_pair(0, 0);
+  wait_loads_and_barrier();
+  for (int it = 0; it < n_it; ++it) {
+    const int st = it & 1;
+    if (it + 1 < n_it) load_pair(it + 1, st ^ 1);
+    const int qb = qb_lo + 2 * it + par;
+    if (wave_valid && qb < nqb) {
+      const bf16_t* tQ = lds[st][0] + par * BLK * D;
+      const bf16_t* tG = lds[st][1] + par * BLK * D;
+      const float* tL = ldsL[st] + par * BLK;
+      const float* tD = ldsD[st] + par * BLK;
+      const int qbase = qb * BLK;
+      f32x16 sacc[2], pacc[2];
 #pragma unroll
-      for (int t2 = 0; t2 < T2; ++t2) {
+      for (int t2 = 0; t2 < 2; ++t2) {
         sacc[t2] = zero16();
         pacc[t2] = zero16();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          sacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(ldsQr[buf], t2 * 32, ks, lane), kf[ks], sacc[t2], 0, 0, 0);
-          pacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(ldsGr[buf], t2 * 32, ks, lane), vf[ks], pacc[t2], 0, 0, 0);
+          sacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(tQ, t2 * 32, ks, lane), kf[ks], sacc[t2], 0, 0, 0);
+          pacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(tG, t2 * 32, ks, lane), vf[ks], pacc[t2], 0, 0, 0);
         }
       }
-      // masked: queries before the key (causal, only in the blocks that touch the diagonal) and padding queries
-      const bool need_mask = (CAUSAL && qbase < k0 + 31) || (qbase + BQB > s);
-      bf16x8 pf[T2][2], dsf[T2][2];
+      // masked: queries before the key (causal, only in the block on the diagonal) and padding queries
+      const bool need_mask = (CAUSAL && qbase < k0 + 31) || (qbase + BLK > s);
+      bf16x8 pf[2][2], dsf[2][2];
 #pragma unroll
-      for (int t2 = 0; t2 < T2; ++t2) {
+      for (int t2 = 0; t2 < 2; ++t2) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int qi = t2 * 32 + 8 * c + 4 * g;
-          const float4 l4 = *(const float4*)(&ldsL[buf][qi]);
-          const float4 d4 = *(const float4*)(&ldsD[buf][qi]);
+          const float4 l4 = *(const float4*)(tL + qi);
+          const float4 d4 = *(const float4*)(tD + qi);
           const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * c + e;
             const int qy = qbase + qi + e;
-            float p = __builtin_amdgcn_exp2f(sacc[t2][r] * a.scale_log2 - lv[e]);
+            float p = __builtin_amdgcn_exp2f(fmaf(sacc[t2][r], a.scale_log2, -lv[e]));
             if (need_mask && (qy >= s || (CAUSAL && qy < key))) p = 0.f;
             sacc[t2][r] = p;
             pacc[t2][r] = p * (pacc[t2][r] - dv[e]);  // dS
@@ -471,30 +541,45 @@ __global__ __launch_bounds__(NW * 64) void attn_fused_bwd_dkv_kernel(FusedArgs a
         dsf[t2][1] = pack_acc<1>(pacc[t2]);
       }
 #pragma unroll
-      for (int t2 = 0; t2 < T2; ++t2)
+      for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt) {
-            dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_acc_order<D>(ldsGc[buf], t2 * 32 + u * 16, dt * 32, lane),
+            dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_acc_order<D>(tG, t2 * 32 + u * 16, dt * 32, lane),
                                                                 pf[t2][u], dvacc[dt], 0, 0, 0);
-            dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_acc_order<D>(ldsQc[buf], t2 * 32 + u * 16, dt * 32, lane),
+            dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_acc_order<D>(tQ, t2 * 32 + u * 16, dt * 32, lane),
                                                                 dsf[t2][u], dkacc[dt], 0, 0, 0);
           }
     }
-    if (qb + 1 < nqb) lstore(buf ^ 1);
-    __syncthreads();
+    wait_loads_and_barrier();
   }
-  if (key < s) {
+  float* xch = (float*)&lds[0][0][0] + rg * (2 * DT * 16) * 64;
+  if (par == 1) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        xch[(dt * 16 + r) * 64 + lane] = dkacc[dt][r];
+        xch[((DT + dt) * 16 + r) * 64 + lane] = dvacc[dt][r];
+      }
+  }
+  __syncthreads();
+  if (par == 0 && key < s) {
     bf16_t* dKp = a.d_qkv + dev * a.dev_qkv + ((long long)seq * s + key) * a.ld + head * 3 * D + D;
     bf16_t* dVp = dKp + D;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        u32x2 wk = {pack2_bf16(dkacc[dt][4 * c] * a.scale, dkacc[dt][4 * c + 1] * a.scale),
-                    pack2_bf16(dkacc[dt][4 * c + 2] * a.scale, dkacc[dt][4 * c + 3] * a.scale)};
-        u32x2 wv = {pack2_bf16(dvacc[dt][4 * c], dvacc[dt][4 * c + 1]), pack2_bf16(dvacc[dt][4 * c + 2], dvacc[dt][4 * c + 3])};
+        float k4[4], v4[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          k4[e] = (dkacc[dt][4 * c + e] + xch[(dt * 16 + 4 * c + e) * 64 + lane]) * a.scale;
+          v4[e] = dvacc[dt][4 * c + e] + xch[((DT + dt) * 16 + 4 * c + e) * 64 + lane];
+        }
+        u32x2 wk = {pack2_bf16(k4[0], k4[1]), pack2_bf16(k4[2], k4[3])};
+        u32x2 wv = {pack2_bf16(v4[0], v4[1]), pack2_bf16(v4[2], v4[3])};
         *(u32x2*)(dKp + dt * 32 + 8 * c + 4 * g) = wk;
         *(u32x2*)(dVp + dt * 32 + 8 * c + 4 * g) = wv;
       }
@@ -517,52 +602,45 @@ bool desc_ok(const AttnFusedDesc& d) {
   if (d.s < 1 || d.nb < 1 || d.nh < 1 || d.ndev < 1 || d.ndev > 65535) return false;
   if ((long long)d.nb * d.nh > 65535) return false;
   if (d.ld % 8 || d.ldo % 8 || d.ld < 3 * d.d * d.nh || d.ldo < d.d * d.nh) return false;
+  if ((long long)PAIR * d.ld * 2 >= (1ll << 31)) return false;  // per-lane byte offsets inside a pair tile are 32-bit
   return true;
+}
+
+template <int D>
+void fwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
+  const dim3 grid((d.s + BLK - 1) / BLK, d.nb * d.nh, d.ndev), block(NWAVES * 64);
+  if (d.causal) attn_fused_fwd_kernel<D, true><<<grid, block, 0, st>>>(a);
+  else attn_fused_fwd_kernel<D, false><<<grid, block, 0, st>>>(a);
+}
+template <int D>
+void bwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
+  const dim3 grid((d.s + BLK - 1) / BLK, d.nb * d.nh, d.ndev), block(NWAVES * 64);
+  if (d.causal) {
+    attn_fused_bwd_dq_kernel<D, true><<<grid, block, 0, st>>>(a);
+    attn_fused_bwd_dkv_kernel<D, true><<<grid, block, 0, st>>>(a);
+  } else {
+    attn_fused_bwd_dq_kernel<D, false><<<grid, block, 0, st>>>(a);
+    attn_fused_bwd_dkv_kernel<D, false><<<grid, block, 0, st>>>(a);
+  }
 }
 
 }  // namespace
 
 bool attn_fused_supported(int d) { return d == 64 || d == 128; }
 
-namespace {
-// Four wavefronts (128 rows) per workgroup when that still gives every compute unit a workgroup, two otherwise.
-bool use_two_waves(const AttnFusedDesc& d) { return (long long)((d.s + 127) / 128) * d.nb * d.nh * d.ndev < 256; }
-
-template <int D, int NW>
-void fwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
-  const dim3 grid((d.s + NW * 32 - 1) / (NW * 32), d.nb * d.nh, d.ndev), block(NW * 64);
-  if (d.causal) attn_fused_fwd_kernel<D, true, NW><<<grid, block, 0, st>>>(a);
-  else attn_fused_fwd_kernel<D, false, NW><<<grid, block, 0, st>>>(a);
-}
-template <int D, int NW>
-void bwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
-  constexpr int BQB = D == 128 ? 32 : 64;
-  const dim3 grid((d.s + NW * 32 - 1) / (NW * 32), d.nb * d.nh, d.ndev), block(NW * 64);
-  if (d.causal) {
-    attn_fused_bwd_dq_kernel<D, true, NW><<<grid, block, 0, st>>>(a);
-    attn_fused_bwd_dkv_kernel<D, true, BQB, NW><<<grid, block, 0, st>>>(a);
-  } else {
-    attn_fused_bwd_dq_kernel<D, false, NW><<<grid, block, 0, st>>>(a);
-    attn_fused_bwd_dkv_kernel<D, false, BQB, NW><<<grid, block, 0, st>>>(a);
-  }
-}
-}  // namespace
-
 int launch_attn_fused_fwd(const AttnFusedDesc& d, hipStream_t st) {
   if (!desc_ok(d) || !d.qkv || !d.attn || !d.lse) return OPTIMUS_ESHAPE;
   const FusedArgs a = make_args(d);
-  const bool two = use_two_waves(d);
-  if (d.d == 64) two ? fwd_launch<64, 2>(a, d, st) : fwd_launch<64, 4>(a, d, st);
-  else two ? fwd_launch<128, 2>(a, d, st) : fwd_launch<128, 4>(a, d, st);
+  if (d.d == 64) fwd_launch<64>(a, d, st);
+  else fwd_launch<128>(a, d, st);
   return hip_launch_status();
 }
 
 int launch_attn_fused_bwd(const AttnFusedDesc& d, hipStream_t st) {
   if (!desc_ok(d) || !d.qkv || !d.attn || !d.lse || !d.d_attn || !d.d_qkv || !d.delta) return OPTIMUS_ESHAPE;
   const FusedArgs a = make_args(d);
-  const bool two = use_two_waves(d);
-  if (d.d == 64) two ? bwd_launch<64, 2>(a, d, st) : bwd_launch<64, 4>(a, d, st);
-  else two ? bwd_launch<128, 2>(a, d, st) : bwd_launch<128, 4>(a, d, st);
+  if (d.d == 64) bwd_launch<64>(a, d, st);
+  else bwd_launch<128>(a, d, st);
   return hip_launch_status();
 }
 
