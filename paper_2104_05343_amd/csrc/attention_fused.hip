@@ -23,7 +23,10 @@
 // the transposing LDS read ds_read_b64_tr_b16) is simply fetched in that order.  P and dS never leave registers.
 //
 // Blocks of the other index go global -> LDS directly (buffer_load_dwordx4 ... lds, one KiB per wavefront
-// instruction, no registers, no LDS store instructions), two stages, one barrier per pair of blocks.  One LDS copy
+// instruction, no registers, no LDS store instructions), two stages, one barrier per pair of blocks; the pieces of the
+// next pair are issued in one go at the top of an iteration (spreading them between the matrix instructions was
+// measured slower here: at 64 KiB per iteration and compute unit the loop runs at the rate the memory path delivers,
+// about 27 B/clk per compute unit with every unit loading, wherever the issue slots are).  One LDS copy
 // of a [rows][D] tile serves both ways of reading it: 16-byte chunk c of row r sits at chunk position c ^ g(r) with
 // g(r) = ((r & 3) << 2) | ((r >> 2) & 3) for 256-byte rows (and the analogous 3-bit form for 128-byte rows, which pair
 // up to span the 64 banks).  Reading along the rows (ds_read_b128, 16 consecutive rows, same chunk) sees 16 distinct
@@ -244,8 +247,13 @@ __global__ __launch_bounds__(256) void attn_fused_fwd_kernel(FusedArgs a) {
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t2][r]);
       mx = halfwave_max(mx) * a.scale_log2;  // the scale is positive: it commutes with the maximum
       // Every block a wavefront works on holds a visible key for each of its rows (the first key of a block is
-      // never past the wavefront's first row), so m_new is finite.
-      const float m_new = fmaxf(m_run, mx);
+      // never past the wavefront's first row), so mx is finite.
+      // The running maximum only has to keep exp2 in range, not to be the true maximum: it follows the block
+      // maximum only when that is more than 2^8 above it (wave-uniform decision), which spares the rescaling of
+      // the accumulators in nearly every block.  p <= 2^8 then; the normalisation by l and the log-sum-exp
+      // m + log2(l) are unchanged by the choice of m.
+      const bool move = __builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0;
+      const float m_new = move ? fmaxf(m_run, mx) : m_run;
       float sum = 0.f;
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
@@ -256,7 +264,7 @@ __global__ __launch_bounds__(256) void attn_fused_fwd_kernel(FusedArgs a) {
           sum += p;
         }
       sum = halfwave_sum(sum);
-      if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {  // some row's maximum moved: rescale what was accumulated
+      if (move) {  // rescale what was accumulated
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         l_run *= alpha;
 #pragma unroll
