@@ -286,6 +286,30 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    # the same step with the attention that keeps no [s x s] tensor (cfg.fused_attention = 1), reported beside it
+    fused_step = None
+    if (h // n) in (64, 128):
+        cfg_f, T_f, lt_f, ws_f = harness.alloc_layer(bits, vecs, b, s, h, n, q, causal=True, fused_attention=True, share=T)
+        opt.layer_fwd(cfg_f, lt_f, -1, -1, ws_f)
+        opt.layer_bwd(cfg_f, lt_f, -1, -1, ws_f)
+        torch.cuda.synchronize()
+
+        def step_f():
+            opt.layer_fwd(cfg_f, lt_f, di, dj, ws_f)
+            opt.layer_bwd(cfg_f, lt_f, di, dj, ws_f)
+        run_f, graphed_f = capture(step_f, 1)
+        for _ in range(args.warmup):
+            run_f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run_f()
+        torch.cuda.synchronize()
+        fused_step = {"ms_per_step": round((time.perf_counter() - t0) * 1e3 / args.steps, 4),
+                      "launch": "HIP graph replay" if graphed_f else "eager launches",
+                      "what": "same layer step with cfg.fused_attention = 1 (no probs tensor; lse saved)"}
+        del T_f, lt_f, ws_f, run_f
+
     gemms = layer_gemm_list(b, s, h)
     summa_flops = sum(opt.gemm_flops(M, K, N, q) for (_, _, M, K, N) in gemms)
     layer_flops = opt.layer_flops(cfg, 0) + opt.layer_flops(cfg, 1)
@@ -332,6 +356,7 @@ def main():
                         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
                         "sum_of_12_gemm_kernels_us": round(sum_us, 1), "gemm_only_tflops": round(gemm_only_tflops, 1),
                         "gemm_only_pct_peak": round(100 * gemm_only_tflops / PEAK_BF16_TFLOPS, 1)},
+        "step_fused_attention": fused_step,
         "gemms": gemm_rows,
         "bandwidth_kernels": bw,
         "paper_context": {"training_speedup_vs_megatron_64gpu": 1.48, "inference_speedup_vs_megatron_64gpu": 1.78,

@@ -206,6 +206,8 @@ typedef struct {
   float eps;
   int causal;
   int dtype; /* OPTIMUS_BF16 only */
+  int fused_attention; /* 0: scores and probabilities in memory (probs saved for the backward pass);
+                          1: optimus_attention_fused_* (lse saved instead; needs h/n = 64 or 128) */
 } optimus_layer_cfg;
 
 typedef struct {
@@ -224,7 +226,7 @@ typedef struct {
   /* forward tensors, written by optimus_layer_fwd, read by optimus_layer_bwd */
   void* ln1_out; void* xhat1; float* rstd1; float* stats1; /* [M x h], [M x h], [q][q][M/q], [q][q][M/q][2] */
   void* qkv;      /* [M x 3h] */
-  void* probs;    /* [q][q][(b/q)(n/q)][s][s] */
+  void* probs;    /* [q][q][(b/q)(n/q)][s][s]; unused (may be NULL) with fused_attention */
   void* attn;     /* [M x h]  */
   void* h_mid;    /* [M x h]  */
   void* ln2_out; void* xhat2; float* rstd2; float* stats2;
@@ -244,10 +246,12 @@ typedef struct {
   float* d_w_qkv; float* d_w_o; float* d_w1; float* d_w2;         /* fp32, block-major, weight shapes */
   float* d_b_qkv; float* d_b_o; float* d_b1; float* d_b2;         /* fp32 partials [q][q][N/q]        */
   float* d_ln1_g; float* d_ln1_b; float* d_ln2_g; float* d_ln2_b; /* fp32 partials [q][q][h/q]        */
+  float* lse;     /* [q][q][(b/q)(n/q)][s] fp32, forward tensor; only with fused_attention (else may be NULL) */
 } optimus_layer_tensors;
 
 /* Scratch bytes optimus_layer_fwd / _bwd need in `ws` (attention scores and
- * their gradients for one device, plus split-k partial tiles: one region for
+ * their gradients for one device -- with fused_attention only one fp32 per
+ * query row --, plus split-k partial tiles: one region for
  * the activation chain and one for the parameter-gradient branch, which
  * optimus_layer_bwd runs concurrently on a stream of the library's own that
  * it forks from and joins back into `stream` with events; when the call

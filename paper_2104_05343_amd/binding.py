@@ -33,7 +33,7 @@ class Epilogue(C.Structure):
 
 class LayerCfg(C.Structure):
     _fields_ = [("b", C.c_int), ("s", C.c_int), ("h", C.c_int), ("n", C.c_int), ("q", C.c_int),
-                ("eps", C.c_float), ("causal", C.c_int), ("dtype", C.c_int)]
+                ("eps", C.c_float), ("causal", C.c_int), ("dtype", C.c_int), ("fused_attention", C.c_int)]
 
 
 LAYER_TENSOR_FIELDS = [
@@ -43,6 +43,7 @@ LAYER_TENSOR_FIELDS = [
     "d_out", "d_pre_gelu", "d_ln2_out", "d_h_mid", "d_attn", "d_qkv", "d_ln1_out", "d_x",
     "bstats1", "bstats2", "d_w_qkv", "d_w_o", "d_w1", "d_w2", "d_b_qkv", "d_b_o", "d_b1", "d_b2",
     "d_ln1_g", "d_ln1_b", "d_ln2_g", "d_ln2_b",
+    "lse",
 ]
 
 

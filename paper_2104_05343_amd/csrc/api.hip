@@ -301,7 +301,7 @@ int ln_backward(const void* dY, const void* xhat, const float* rstd, const float
 int layer_check(const optimus_layer_cfg* c, int i, int j, AttnDims* a) {
   if (!c) return OPTIMUS_EINVAL;
   if (c->dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
-  int rc = attn_dims(c->b, c->s, c->h, c->n, c->q, a);
+  int rc = c->fused_attention ? attn_fused_dims(c->b, c->s, c->h, c->n, c->q, a) : attn_dims(c->b, c->s, c->h, c->n, c->q, a);
   if (rc) return rc;
   if (c->h % c->q) return OPTIMUS_ESHAPE;
   if ((long long)c->b * c->s > 0x7fffffffLL) return OPTIMUS_ESHAPE;
@@ -396,7 +396,7 @@ const char* optimus_error_string(int code) {
   }
 }
 
-int optimus_abi_version(void) { return 1; }
+int optimus_abi_version(void) { return 2; }
 
 int optimus_pack_blocks(const void* src, void* dst, int64_t R, int64_t C, int q, int elem_bytes, void* stream) {
   if (!src || !dst || src == dst) return OPTIMUS_EINVAL;
@@ -520,11 +520,27 @@ int optimus_attention_fused_bwd(const void* qkv, const void* attn, const float* 
                              causal ? 1 : 0, dtype, ws, ws_bytes, stream);
 }
 
+size_t layer_attn_ws(const optimus_layer_cfg* c, const AttnDims& a) {
+  return c->fused_attention ? attn_fused_ws_bytes(a, c->q) : attn_ws_bytes(a);
+}
+int layer_attention(bool bwd, const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
+                    void* stream) {
+  const int causal = c->causal ? 1 : 0;
+  if (c->fused_attention)
+    return run_attention_fused(bwd, t->qkv, t->attn, t->lse, bwd ? t->d_attn : nullptr, bwd ? t->d_qkv : nullptr, c->b, c->s, c->h,
+                               c->n, c->q, i, j, causal, c->dtype, ws, ws_bytes, stream);
+  if (bwd)
+    return run_attention(true, t->qkv, t->probs, nullptr, t->d_attn, t->d_qkv, c->b, c->s, c->h, c->n, c->q, i, j, causal, c->dtype,
+                         ws, ws_bytes, stream);
+  return run_attention(false, t->qkv, nullptr, t->probs, nullptr, t->attn, c->b, c->s, c->h, c->n, c->q, i, j, causal, c->dtype, ws,
+                       ws_bytes, stream);
+}
+
 size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg) {
   AttnDims a;
   if (layer_check(cfg, 0, 0, &a)) return 0;
   // scores scratch of attention + split partials of the activation chain + split partials of the gradient branch
-  return attn_ws_bytes(a) + 2 * layer_gemm_ws(cfg);
+  return layer_attn_ws(cfg, a) + 2 * layer_gemm_ws(cfg);
 }
 
 int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
@@ -534,7 +550,8 @@ int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   if (rc) return rc;
   if (!t) return OPTIMUS_EINVAL;
   if (!t->x || !t->ln1_g || !t->ln1_b || !t->w_qkv || !t->b_qkv || !t->w_o || !t->b_o || !t->ln2_g || !t->ln2_b || !t->w1 ||
-      !t->b1 || !t->w2 || !t->b2 || !t->ln1_out || !t->xhat1 || !t->rstd1 || !t->stats1 || !t->qkv || !t->probs || !t->attn ||
+      !t->b1 || !t->w2 || !t->b2 || !t->ln1_out || !t->xhat1 || !t->rstd1 || !t->stats1 || !t->qkv ||
+      !(c->fused_attention ? (const void*)t->lse : (const void*)t->probs) || !t->attn ||
       !t->h_mid || !t->ln2_out || !t->xhat2 || !t->rstd2 || !t->stats2 || !t->pre_gelu || !t->gelu || !t->out)
     return OPTIMUS_EINVAL;
   if (!ws || ws_bytes < optimus_layer_workspace_bytes(c)) return OPTIMUS_EWORKSPACE;
@@ -543,7 +560,7 @@ int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   const bool grid = is_grid(i, j);
   hipStream_t st = as_stream(stream);
   void* attn_ws = ws;
-  const size_t attn_bytes = attn_ws_bytes(a);
+  const size_t attn_bytes = layer_attn_ws(c, a);
   void* gemm_ws = (char*)ws + attn_bytes;
   const size_t gemm_bytes = layer_gemm_ws(c);
   LnDesc ln;
@@ -555,9 +572,7 @@ int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   e.bias = t->b_qkv;
   if ((rc = run_summa(OPTIMUS_FORM_AB, t->ln1_out, t->w_qkv, t->qkv, M, h, 3 * h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream))) return rc;
   // local attention
-  if ((rc = run_attention(false, t->qkv, nullptr, t->probs, nullptr, t->attn, c->b, c->s, c->h, c->n, q, i, j, c->causal ? 1 : 0, dt,
-                          attn_ws, attn_bytes, stream)))
-    return rc;
+  if ((rc = layer_attention(false, c, t, i, j, attn_ws, attn_bytes, stream))) return rc;
   // h_mid = x + attn Wo + b
   e = {};
   e.bias = t->b_o; e.residual = t->x;
@@ -581,7 +596,8 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   if (rc) return rc;
   if (!t) return OPTIMUS_EINVAL;
   if (!t->x || !t->ln1_g || !t->w_qkv || !t->w_o || !t->ln2_g || !t->w1 || !t->w2 || !t->ln1_out || !t->xhat1 || !t->rstd1 ||
-      !t->qkv || !t->probs || !t->attn || !t->ln2_out || !t->xhat2 || !t->rstd2 || !t->pre_gelu || !t->gelu || !t->d_out ||
+      !t->qkv || !(c->fused_attention ? (const void*)t->lse : (const void*)t->probs) || !t->attn || !t->ln2_out || !t->xhat2 ||
+      !t->rstd2 || !t->pre_gelu || !t->gelu || !t->d_out ||
       !t->d_pre_gelu || !t->d_ln2_out || !t->d_h_mid || !t->d_attn || !t->d_qkv || !t->d_ln1_out || !t->d_x || !t->bstats1 ||
       !t->bstats2 || !t->d_w_qkv || !t->d_w_o || !t->d_w1 || !t->d_w2 || !t->d_b_qkv || !t->d_b_o || !t->d_b1 || !t->d_b2 ||
       !t->d_ln1_g || !t->d_ln1_b || !t->d_ln2_g || !t->d_ln2_b)
@@ -592,7 +608,7 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   const bool grid = is_grid(i, j);
   hipStream_t st = as_stream(stream);
   void* attn_ws = ws;
-  const size_t attn_bytes = attn_ws_bytes(a);
+  const size_t attn_bytes = layer_attn_ws(c, a);
   void* gemm_ws = (char*)ws + attn_bytes;
   const size_t gemm_bytes = layer_gemm_ws(c);
   LnDesc ln;
@@ -626,8 +642,7 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   RUN(run_summa(OPTIMUS_FORM_ATB, t->attn, t->d_h_mid, t->d_w_o, h, M, h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream));
   RUN(optimus_bias_grad(t->d_h_mid, t->d_b_o, M, h, q, i, j, dt, gstream));
   // ---- local attention backward ----
-  RUN(run_attention(true, t->qkv, t->probs, nullptr, t->d_attn, t->d_qkv, c->b, c->s, c->h, c->n, q, i, j, c->causal ? 1 : 0, dt,
-                    attn_ws, attn_bytes, stream));
+  RUN(layer_attention(true, c, t, i, j, attn_ws, attn_bytes, stream));
   // ---- qkv = ln1_out Wqkv + b ----
   BRANCH_AFTER_MAIN(ss->ready[2]);  // d_qkv is complete
   RUN(run_summa(OPTIMUS_FORM_ABT, t->d_qkv, t->w_qkv, t->d_ln1_out, M, 3 * h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));

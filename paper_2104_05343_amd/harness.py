@@ -39,17 +39,19 @@ def layer_shapes(b, s, h):
     }
 
 
-def alloc_layer(inputs_bits: dict, vectors: dict, b, s, h, n, q, causal=True, eps=1e-5):
+def alloc_layer(inputs_bits: dict, vectors: dict, b, s, h, n, q, causal=True, eps=1e-5, fused_attention=False, share=None):
     """inputs_bits: name -> uint16 bf16 patterns of the six input matrices (row-major);
-    vectors: name -> fp32 numpy vectors.  Returns (cfg, tensors dict, LayerTensors, workspace)."""
+    vectors: name -> fp32 numpy vectors.  Returns (cfg, tensors dict, LayerTensors, workspace).
+    With ``fused_attention`` the layer keeps lse [q][q][(b/q)(n/q)][s] instead of probs.  ``share``: a tensors dict
+    of an earlier call whose inputs and parameters are reused instead of uploaded again."""
     shapes = layer_shapes(b, s, h)
     M = b * s
     T = {}
     for name in ("x", "w_qkv", "w_o", "w1", "w2", "d_out"):
         R, C = shapes[name]
-        T[name] = pack_matrix(upload_bf16_bits(inputs_bits[name]), R, C, q)
+        T[name] = share[name] if share is not None else pack_matrix(upload_bf16_bits(inputs_bits[name]), R, C, q)
     for name, v in vectors.items():
-        T[name] = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(DEV)
+        T[name] = share[name] if share is not None else torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(DEV)
     for name, (R, C) in shapes.items():
         if name in T:
             continue
@@ -57,13 +59,16 @@ def alloc_layer(inputs_bits: dict, vectors: dict, b, s, h, n, q, causal=True, ep
         T[name] = torch.zeros(R * C, dtype=dt, device=DEV)
     rows = M // q
     nmat = (b // q) * (n // q)
-    T["probs"] = torch.zeros(q * q * nmat * s * s, dtype=torch.bfloat16, device=DEV)
+    if fused_attention:
+        T["lse"] = torch.zeros(q * q * nmat * s, dtype=torch.float32, device=DEV)
+    else:
+        T["probs"] = torch.zeros(q * q * nmat * s * s, dtype=torch.bfloat16, device=DEV)
     for name in ("rstd1", "rstd2"):
         T[name] = torch.zeros(q * q * rows, dtype=torch.float32, device=DEV)
     for name in ("stats1", "stats2", "bstats1", "bstats2"):
         T[name] = torch.zeros(q * q * rows * 2, dtype=torch.float32, device=DEV)
     for name, mult in {"d_b_qkv": 3, "d_b_o": 1, "d_b1": 4, "d_b2": 1, "d_ln1_g": 1, "d_ln1_b": 1, "d_ln2_g": 1, "d_ln2_b": 1}.items():
         T[name] = torch.zeros(q * q * (mult * h // q), dtype=torch.float32, device=DEV)
-    cfg = opt.LayerCfg(b, s, h, n, q, eps, 1 if causal else 0, opt.BF16)
+    cfg = opt.LayerCfg(b, s, h, n, q, eps, 1 if causal else 0, opt.BF16, 1 if fused_attention else 0)
     ws = torch.empty(opt.layer_workspace_bytes(cfg), dtype=torch.uint8, device=DEV)
     return cfg, T, opt.make_layer_tensors(T), ws

@@ -26,8 +26,9 @@ FWD_OUT = ["ln1_out", "xhat1", "qkv", "attn", "h_mid", "ln2_out", "xhat2", "pre_
 BWD_OUT = ["d_pre_gelu", "d_ln2_out", "d_h_mid", "d_attn", "d_qkv", "d_ln1_out", "d_x"]
 
 
-def alloc_layer(inp, shp, causal=True, eps=1e-5, fill=float("nan")):
-    """Upload inputs (block-major) and allocate every other tensor of optimus_layer_tensors."""
+def alloc_layer(inp, shp, causal=True, eps=1e-5, fill=float("nan"), fused=False):
+    """Upload inputs (block-major) and allocate every other tensor of optimus_layer_tensors.  With ``fused`` the
+    layer uses the attention that keeps no [s x s] tensor: no ``probs`` is allocated, ``lse`` is."""
     M, h, q = shp.M, shp.h, shp.q
     dev = "cuda:0"
     T = {}
@@ -42,14 +43,17 @@ def alloc_layer(inp, shp, causal=True, eps=1e-5, fill=float("nan")):
         T[name] = torch.full((r * c,), fill, dtype=torch.float32 if name in FP32_MATS else torch.bfloat16, device=dev)
     rows = M // q
     nmat = (shp.b // q) * (shp.n // q)
-    T["probs"] = torch.full((q * q * nmat * shp.s * shp.s,), fill, dtype=torch.bfloat16, device=dev)
+    if fused:
+        T["lse"] = torch.full((q * q * nmat * shp.s,), fill, dtype=torch.float32, device=dev)
+    else:
+        T["probs"] = torch.full((q * q * nmat * shp.s * shp.s,), fill, dtype=torch.bfloat16, device=dev)
     for name in ("rstd1", "rstd2"):
         T[name] = torch.full((q * q * rows,), fill, dtype=torch.float32, device=dev)
     for name in ("stats1", "stats2", "bstats1", "bstats2"):
         T[name] = torch.full((q * q * rows * 2,), fill, dtype=torch.float32, device=dev)
     for name, mult in VEC_PART.items():
         T[name] = torch.full((q * q * (mult * h // q),), fill, dtype=torch.float32, device=dev)
-    cfg = opt.LayerCfg(shp.b, shp.s, shp.h, shp.n, shp.q, eps, 1 if causal else 0, opt.BF16)
+    cfg = opt.LayerCfg(shp.b, shp.s, shp.h, shp.n, shp.q, eps, 1 if causal else 0, opt.BF16, 1 if fused else 0)
     ws = torch.empty(opt.layer_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
     return cfg, T, opt.make_layer_tensors(T), ws
 

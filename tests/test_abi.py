@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_error_strings_and_version():
-    assert opt.abi_version() == 1
+    assert opt.abi_version() == 2
     for code in range(7):
         assert isinstance(opt.error_string(code), str) and opt.error_string(code)
     assert "unknown" in opt.error_string(99)

@@ -84,6 +84,64 @@ def test_layer_grid_and_device_mode(shp, causal):
         assert torch.equal(a, b), f"{k} changed between grid mode and device mode"
 
 
+# head widths 64 and 128 (what the attention without [s x s] tensors is built for), ragged s, q = 1, 2
+FUSED = [LayerShape(b=4, s=72, h=256, n=4, q=2), LayerShape(b=2, s=136, h=256, n=2, q=2),
+         LayerShape(b=2, s=128, h=128, n=2, q=1)]
+
+
+@pytest.mark.parametrize("shp", FUSED, ids=lambda s: f"b{s.b}s{s.s}h{s.h}n{s.n}q{s.q}")
+@pytest.mark.parametrize("causal", [True, False])
+def test_layer_with_fused_attention(shp, causal):
+    """The layer with cfg.fused_attention = 1: same oracles, same tolerances; no probs tensor, lse instead."""
+    from oracle import attention as oatt
+    from workloads import round_to_bf16
+    inp = layer_inputs(13, shp, "bf16", perturb_affine=True)
+    for k in ("w_qkv", "w_o", "w1", "w2"):
+        inp[k] = round_to_bf16(inp[k] * 4.0)
+    (fe, be), (fs, bs) = _oracles(inp, shp, causal)
+    cfg, T, lt, ws = alloc_layer(inp, shp, causal, fused=True)
+    assert "probs" not in T and cfg.fused_attention == 1
+    opt.layer_fwd(cfg, lt, -1, -1, ws)
+    opt.layer_bwd(cfg, lt, -1, -1, ws)
+    torch.cuda.synchronize()
+    # whole chain against the exact oracle (the storage-aware oracle models the stored probabilities of the other
+    # attention path, so it is used only up to the attention's input here)
+    w_e = _compare_all(T, shp, inp, fe, be, TOL_EXACT_CHAIN)
+    print("fused: max err vs exact oracle %.2e" % max(w_e.values()))
+    for k in ("ln1_out", "xhat1", "qkv"):
+        assert rel_frobenius(fetch(T, k, shp), fs[k]) <= TOL, k
+    # the attention stage by itself, from the values the device stored for its inputs, to the per-stage tolerance
+    qkv_dev = fetch(T, "qkv", shp)
+    attn_o, _ = oatt.forward(qkv_dev, shp.b, shp.s, shp.n, causal, keep_probs=False)
+    assert rel_frobenius(fetch(T, "attn", shp), attn_o) <= TOL
+    dqkv_o = oatt.backward(qkv_dev, fetch(T, "d_attn", shp), shp.b, shp.s, shp.n, causal)
+    assert rel_frobenius(fetch(T, "d_qkv", shp), dqkv_o) <= TOL
+    # the saved row statistic, against the oracle's log-sum-exp of the qkv the device stored
+    q, nb, nh = shp.q, shp.b // shp.q, shp.n // shp.q
+    L = oatt.logsumexp(qkv_dev, shp.b, shp.s, shp.n, causal)
+    got = to_host(T["lse"]).reshape(q, q, nb * nh, shp.s)
+    for i in range(q):
+        for j in range(q):
+            want = L[i * nb:(i + 1) * nb, j * nh:(j + 1) * nh].reshape(nb * nh, shp.s)
+            assert rel_frobenius(got[i, j], want) <= 1e-5
+    snap = {k: v.clone() for k, v in T.items()}
+    i, j = shp.q - 1, 0
+    opt.layer_fwd(cfg, lt, i, j, ws)
+    opt.layer_bwd(cfg, lt, i, j, ws)
+    torch.cuda.synchronize()
+    for k, v in T.items():
+        assert torch.equal(v.view(torch.uint8), snap[k].view(torch.uint8)), f"{k} changed between grid mode and device mode"
+
+
+def test_layer_fused_attention_rejects_other_head_widths():
+    shp = LayerShape(b=4, s=64, h=128, n=4, q=2)   # h/n = 32
+    cfg = opt.LayerCfg(shp.b, shp.s, shp.h, shp.n, shp.q, 1e-5, 1, opt.BF16, 1)
+    assert opt.layer_workspace_bytes(cfg) == 0
+    with pytest.raises(opt.OptimusError) as e:
+        opt.layer_fwd(cfg, opt.make_layer_tensors({}), 0, 0, None)
+    assert e.value.code == opt.ESHAPE
+
+
 def test_layer_device_mode_writes_only_its_blocks():
     shp = LayerShape(b=4, s=64, h=128, n=4, q=2)
     inp = layer_inputs(12, shp, "bf16", perturb_affine=True)
