@@ -267,6 +267,41 @@ int optimus_layer_fwd(const optimus_layer_cfg* cfg, const optimus_layer_tensors*
 int optimus_layer_bwd(const optimus_layer_cfg* cfg, const optimus_layer_tensors* t, int i, int j,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* ---- a stack of identical layers with distributed activation checkpointing and pre-allocated buffers
+ *      (Section 3.2.3 "memory pre-allocation and checkpointing" and its figure; Table 1's backward rows) ----
+ * Forward keeps only the input of every layer (checkpoint[l], [M x h] block-major each: b*s*h/p elements per device
+ * and layer); all layers share ONE set of forward tensors (forward buffer), ONE set of activation gradients
+ * (backward buffer), two [M x h] slots for the gradient passed between consecutive layers (conjunction buffer) and
+ * the workspace.  Backward recomputes layer l's forward pass from checkpoint[l] (without its last product, which
+ * no gradient needs), then runs optimus_layer_bwd on it, for l = L-1 .. 0.
+ * grads[l] says where layer l's parameter gradients go (layouts as in optimus_layer_tensors); entries may all
+ * point into one parameter-gradient buffer if the caller consumes them in `done`, which is called on the host
+ * after layer l's backward kernels have been enqueued (stream-ordered work enqueued from it sees the gradients and
+ * precedes the next layer's; may be NULL).
+ * These calls compute every device's share (grid mode): buffers that all layers share cannot keep the peers' blocks
+ * of every layer resident.  x, out, d_out, d_x: [M x h] block-major device memory; buffers: device memory of at least
+ * the sizes optimus_stack_sizes_of reports (256-byte aligned); params / grads: host arrays of n_layers entries of
+ * device pointers.  The caller's out and d_x must not alias the buffers. */
+typedef struct {
+  const float* ln1_g; const float* ln1_b; const void* w_qkv; const float* b_qkv; const void* w_o; const float* b_o;
+  const float* ln2_g; const float* ln2_b; const void* w1; const float* b1; const void* w2; const float* b2;
+} optimus_layer_params;
+typedef struct {
+  float* d_w_qkv; float* d_w_o; float* d_w1; float* d_w2; float* d_b_qkv; float* d_b_o; float* d_b1; float* d_b2;
+  float* d_ln1_g; float* d_ln1_b; float* d_ln2_g; float* d_ln2_b;
+} optimus_layer_grads;
+typedef struct { size_t workspace, forward, backward, param_grad, conjunction, checkpoint; } optimus_stack_sizes;
+typedef struct { void* workspace; void* forward; void* backward; void* conjunction; void* checkpoint; } optimus_stack_buffers;
+typedef void (*optimus_layer_done_fn)(int layer, void* user);
+int optimus_stack_sizes_of(const optimus_layer_cfg* cfg, int n_layers, optimus_stack_sizes* out);
+/* Lays one layer's parameter gradients out in a buffer of optimus_stack_sizes.param_grad bytes. */
+int optimus_layer_grads_in(const optimus_layer_cfg* cfg, void* param_grad, optimus_layer_grads* out);
+int optimus_stack_fwd(const optimus_layer_cfg* cfg, int n_layers, const optimus_layer_params* params, const void* x,
+                      const optimus_stack_buffers* buf, void* out, void* stream);
+int optimus_stack_bwd(const optimus_layer_cfg* cfg, int n_layers, const optimus_layer_params* params,
+                      const optimus_layer_grads* grads, const void* d_out, const optimus_stack_buffers* buf, void* d_x,
+                      optimus_layer_done_fn done, void* user, void* stream);
+
 /* ---- flop accounting (Table 1) ----
  * optimus_gemm_flops: 2*(M/q)*K*(N/q), one device's share of one product.
  * optimus_layer_flops: one device's share of a layer; what = 0 forward,

@@ -51,6 +51,30 @@ class LayerTensors(C.Structure):
     _fields_ = [(name, C.c_void_p) for name in LAYER_TENSOR_FIELDS]
 
 
+LAYER_PARAM_FIELDS = ["ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2"]
+LAYER_GRAD_FIELDS = ["d_w_qkv", "d_w_o", "d_w1", "d_w2", "d_b_qkv", "d_b_o", "d_b1", "d_b2",
+                     "d_ln1_g", "d_ln1_b", "d_ln2_g", "d_ln2_b"]
+
+
+class LayerParams(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in LAYER_PARAM_FIELDS]
+
+
+class LayerGrads(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in LAYER_GRAD_FIELDS]
+
+
+class StackSizes(C.Structure):
+    _fields_ = [(name, C.c_size_t) for name in ("workspace", "forward", "backward", "param_grad", "conjunction", "checkpoint")]
+
+
+class StackBuffers(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in ("workspace", "forward", "backward", "conjunction", "checkpoint")]
+
+
+LAYER_DONE_FN = C.CFUNCTYPE(None, C.c_int, C.c_void_p)
+
+
 _lib = None
 
 _I64, _INT, _P, _SZ, _F = C.c_int64, C.c_int, C.c_void_p, C.c_size_t, C.c_float
@@ -76,6 +100,11 @@ SIGNATURES = {
     "optimus_attention_fused_fwd": (_INT, [_P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P]),
     "optimus_attention_fused_bwd": (_INT, [_P, _P, _P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
     "optimus_attention_fused_workspace_bytes": (_SZ, [_INT, _INT, _INT, _INT, _INT]),
+    "optimus_stack_sizes_of": (_INT, [C.POINTER(LayerCfg), _INT, C.POINTER(StackSizes)]),
+    "optimus_layer_grads_in": (_INT, [C.POINTER(LayerCfg), _P, C.POINTER(LayerGrads)]),
+    "optimus_stack_fwd": (_INT, [C.POINTER(LayerCfg), _INT, C.POINTER(LayerParams), _P, C.POINTER(StackBuffers), _P, _P]),
+    "optimus_stack_bwd": (_INT, [C.POINTER(LayerCfg), _INT, C.POINTER(LayerParams), C.POINTER(LayerGrads), _P,
+                                 C.POINTER(StackBuffers), _P, LAYER_DONE_FN, _P, _P]),
     "optimus_layer_workspace_bytes": (_SZ, [C.POINTER(LayerCfg)]),
     "optimus_layer_fwd": (_INT, [C.POINTER(LayerCfg), C.POINTER(LayerTensors), _INT, _INT, _P, _SZ, _P]),
     "optimus_layer_bwd": (_INT, [C.POINTER(LayerCfg), C.POINTER(LayerTensors), _INT, _INT, _P, _SZ, _P]),
@@ -253,6 +282,53 @@ def layer_fwd(cfg: LayerCfg, t: LayerTensors, i, j, ws, stream=None):
 def layer_bwd(cfg: LayerCfg, t: LayerTensors, i, j, ws, stream=None):
     p, nb = _ws(ws)
     _check(lib().optimus_layer_bwd(C.byref(cfg), C.byref(t), i, j, p, nb, _stream(stream)), "optimus_layer_bwd")
+
+
+def stack_sizes(cfg: LayerCfg, n_layers: int) -> StackSizes:
+    out = StackSizes()
+    _check(lib().optimus_stack_sizes_of(C.byref(cfg), n_layers, C.byref(out)), "optimus_stack_sizes_of")
+    return out
+
+
+def layer_grads_in(cfg: LayerCfg, param_grad) -> LayerGrads:
+    out = LayerGrads()
+    _check(lib().optimus_layer_grads_in(C.byref(cfg), _ptr(param_grad), C.byref(out)), "optimus_layer_grads_in")
+    return out
+
+
+def make_layer_params(tensors: dict) -> LayerParams:
+    p = LayerParams()
+    for name in LAYER_PARAM_FIELDS:
+        setattr(p, name, _ptr(tensors[name]))
+    return p
+
+
+def make_layer_grads(tensors: dict) -> LayerGrads:
+    g = LayerGrads()
+    for name in LAYER_GRAD_FIELDS:
+        setattr(g, name, _ptr(tensors[name]))
+    return g
+
+
+def make_stack_buffers(workspace, forward, backward, conjunction, checkpoint) -> StackBuffers:
+    return StackBuffers(_ptr(workspace), _ptr(forward), _ptr(backward), _ptr(conjunction), _ptr(checkpoint))
+
+
+def stack_fwd(cfg: LayerCfg, params, x, buf: StackBuffers, out, stream=None):
+    """params: list of LayerParams, one per layer."""
+    arr = (LayerParams * len(params))(*params)
+    _check(lib().optimus_stack_fwd(C.byref(cfg), len(params), arr, _ptr(x), C.byref(buf), _ptr(out), _stream(stream)),
+           "optimus_stack_fwd")
+
+
+def stack_bwd(cfg: LayerCfg, params, grads, d_out, buf: StackBuffers, d_x, done=None, stream=None):
+    """params / grads: lists of LayerParams / LayerGrads, one per layer; done(layer) is called on the host after each
+    layer's backward kernels have been enqueued."""
+    pa = (LayerParams * len(params))(*params)
+    ga = (LayerGrads * len(grads))(*grads)
+    cb = LAYER_DONE_FN((lambda layer, user: done(layer)) if done is not None else 0)
+    _check(lib().optimus_stack_bwd(C.byref(cfg), len(params), pa, ga, _ptr(d_out), C.byref(buf), _ptr(d_x), cb, None,
+                                   _stream(stream)), "optimus_stack_bwd")
 
 
 def gemm_flops(M, K, N, q) -> int:

@@ -543,8 +543,13 @@ size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg) {
   return layer_attn_ws(cfg, a) + 2 * layer_gemm_ws(cfg);
 }
 
-int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
-                      void* stream) {
+}  // extern "C"
+
+// The forward pass; with skip_out the last product (out = h_mid + gelu W2 + b2) is left out: no gradient needs it, so a
+// forward pass that is recomputed inside a backward pass with activation checkpointing stops before it (the third
+// of the memory-management remarks at the end of Section 3.2.3).
+int optimus::layer_forward(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
+                           void* stream, bool skip_out) {
   AttnDims a;
   int rc = layer_check(c, i, j, &a);
   if (rc) return rc;
@@ -552,7 +557,7 @@ int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   if (!t->x || !t->ln1_g || !t->ln1_b || !t->w_qkv || !t->b_qkv || !t->w_o || !t->b_o || !t->ln2_g || !t->ln2_b || !t->w1 ||
       !t->b1 || !t->w2 || !t->b2 || !t->ln1_out || !t->xhat1 || !t->rstd1 || !t->stats1 || !t->qkv ||
       !(c->fused_attention ? (const void*)t->lse : (const void*)t->probs) || !t->attn ||
-      !t->h_mid || !t->ln2_out || !t->xhat2 || !t->rstd2 || !t->stats2 || !t->pre_gelu || !t->gelu || !t->out)
+      !t->h_mid || !t->ln2_out || !t->xhat2 || !t->rstd2 || !t->stats2 || !t->pre_gelu || !t->gelu || (!skip_out && !t->out))
     return OPTIMUS_EINVAL;
   if (!ws || ws_bytes < optimus_layer_workspace_bytes(c)) return OPTIMUS_EWORKSPACE;
   const int q = c->q, dt = c->dtype;
@@ -583,10 +588,18 @@ int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   e = {};
   e.bias = t->b1; e.pre_act = t->pre_gelu; e.act = 1;
   if ((rc = run_summa(OPTIMUS_FORM_AB, t->ln2_out, t->w1, t->gelu, M, h, 4 * h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream))) return rc;
+  if (skip_out) return OPTIMUS_OK;
   // out = h_mid + g W2 + b
   e = {};
   e.bias = t->b2; e.residual = t->h_mid;
   return run_summa(OPTIMUS_FORM_AB, t->gelu, t->w2, t->out, M, 4 * h, h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream);
+}
+
+extern "C" {
+
+int optimus_layer_fwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
+                      void* stream) {
+  return layer_forward(c, t, i, j, ws, ws_bytes, stream, false);
 }
 
 int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,

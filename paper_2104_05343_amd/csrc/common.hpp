@@ -142,6 +142,10 @@ bool attn_fused_supported(int d);
 int launch_attn_fused_fwd(const AttnFusedDesc& d, hipStream_t stream);
 int launch_attn_fused_bwd(const AttnFusedDesc& d, hipStream_t stream);
 
+// optimus_layer_fwd, optionally without its last product (used by the checkpointed stack's recomputation)
+int layer_forward(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
+                  void* stream, bool skip_out);
+
 inline int hip_launch_status() { return hipGetLastError() == hipSuccess ? OPTIMUS_OK : OPTIMUS_EHIP; }
 
 }  // namespace optimus

@@ -59,6 +59,24 @@ def test_host_validation_without_gpu():
     assert L.optimus_attention_fused_workspace_bytes(4, 64, 64, 4, 2) == 0
 
 
+def test_stack_sizes_host_only():
+    """Buffer sizes of the checkpointed stack (host arithmetic): the checkpoint region is L inputs of b*s*h bf16, the
+    conjunction buffer two of them, and a bad configuration is refused."""
+    cfg = opt.LayerCfg(8, 512, 1024, 16, 4, 1e-5, 1, opt.BF16)
+    act = 8 * 512 * 1024 * 2
+    sz = opt.stack_sizes(cfg, 24)
+    assert sz.checkpoint == 24 * act and sz.conjunction == 2 * act
+    assert sz.workspace == opt.layer_workspace_bytes(cfg)
+    assert sz.forward >= 12 * act + 16 * 2 * 4 * 512 * 512 * 2        # 12 activation-sized units + probabilities
+    assert sz.backward >= 11 * act and sz.param_grad >= 12 * 1024 * 1024 * 4
+    fused = opt.LayerCfg(8, 512, 1024, 16, 4, 1e-5, 1, opt.BF16, 1)
+    assert opt.stack_sizes(fused, 24).forward < sz.forward
+    for bad_cfg, L in ((opt.LayerCfg(3, 64, 128, 4, 2, 1e-5, 1, opt.BF16), 2), (cfg, 0)):
+        with pytest.raises(opt.OptimusError) as e:
+            opt.stack_sizes(bad_cfg, L)
+        assert e.value.code == opt.ESHAPE
+
+
 def test_flop_accounting_matches_table1():
     # forward = 2*(12 b s h^2 + 2 b s^2 h)/p flops, backward (no recompute) twice that
     cfg = opt.LayerCfg(8, 1024, 4096, 32, 4, 1e-5, 1, opt.BF16)
