@@ -218,6 +218,36 @@ def time_bandwidth(opt, torch, b, s, h, n, q, i, j, reps, seed):
     return out
 
 
+def time_stack(opt, torch, harness, cfg, T, b, s, h, n, q, layers, reps):
+    """A stack of `layers` identical layers run for the WHOLE q*q grid on the one GPU (grid mode: shared buffers
+    cannot keep the peers' blocks of every layer resident), with activation checkpointing: forward keeps the layer
+    inputs only, backward recomputes each layer (without its last product) before its gradients.  Timed beside the
+    same layers with every tensor kept (no recomputation), and the buffer bytes of both."""
+    M = b * s
+    P = [opt.make_layer_params(T)] * layers          # the same (resident) parameters for every layer: timing only
+    sz = opt.stack_sizes(cfg, layers)
+    raw = {k: torch.empty(getattr(sz, k), dtype=torch.uint8, device="cuda:0")
+           for k in ("workspace", "forward", "backward", "conjunction", "checkpoint", "param_grad")}
+    buf = opt.make_stack_buffers(raw["workspace"], raw["forward"], raw["backward"], raw["conjunction"], raw["checkpoint"])
+    G = [opt.layer_grads_in(cfg, raw["param_grad"])] * layers
+    out_t = torch.empty(M * h, dtype=torch.bfloat16, device="cuda:0")
+    dx_t = torch.empty(M * h, dtype=torch.bfloat16, device="cuda:0")
+    fwd_ms = event_time_ms(lambda: opt.stack_fwd(cfg, P, T["x"], buf, out_t), reps)
+    bwd_ms = event_time_ms(lambda: opt.stack_bwd(cfg, P, G, T["d_out"], buf, dx_t), reps)
+    lt = opt.make_layer_tensors(T)
+    ws = torch.empty(opt.layer_workspace_bytes(cfg), dtype=torch.uint8, device="cuda:0")
+    lf_ms = event_time_ms(lambda: opt.layer_fwd(cfg, lt, -1, -1, ws), reps)
+    lb_ms = event_time_ms(lambda: opt.layer_bwd(cfg, lt, -1, -1, ws), reps)
+    kept = layers * (sz.forward + M * h * 2) + sz.backward + sz.conjunction + sz.workspace + sz.param_grad
+    ckpt = sz.forward + sz.backward + sz.conjunction + sz.workspace + sz.param_grad + sz.checkpoint
+    return {"layers": layers, "mode": f"grid (all {q * q} devices' work on one GPU)",
+            "fwd_ms": round(fwd_ms, 3), "bwd_with_recompute_ms": round(bwd_ms, 3),
+            "no_checkpoint_fwd_ms": round(layers * lf_ms, 3), "no_checkpoint_bwd_ms": round(layers * lb_ms, 3),
+            "bwd_over_fwd": round(bwd_ms / fwd_ms, 2),
+            "buffer_bytes": {k: int(getattr(sz, k)) for k, _ in sz._fields_},
+            "bytes_checkpointed_total": int(ckpt), "bytes_all_activations_kept_total": int(kept)}
+
+
 def pmc_probe(opt, torch, gemm, q, i, j):
     """A 256 MiB device copy (known traffic: 256 MiB read, 256 MiB written), then the given product, then the
     LayerNorm kernels at config-4 block size, each a few times; profiled with rocprofv3 --pmc FETCH_SIZE and, in a
@@ -363,6 +393,8 @@ def main():
                           "hardware": "64x Quadro RTX 5000, TACC Frontera (other machine: context, not a target)"},
     }
 
+    if not args.no_sweep and args.workload == "config2":
+        out["stack"] = time_stack(opt, torch, harness, cfg, T, b, s, h, n, q, layers=4, reps=max(3, args.steps // 10))
     if not args.no_sweep and args.workload == "config2":
         # the same forward products launched for the whole grid at once (i = j = -1: all q*q devices' blocks)
         fwd = [g for g in gemms if g[0] in ("qkv.ab", "mlp_up.ab", "mlp_down.ab")]
