@@ -70,6 +70,20 @@ int optimus_pack_blocks(const void* src_rowmajor, void* dst_blockmajor, int64_t 
 int optimus_unpack_blocks(const void* src_blockmajor, void* dst_rowmajor, int64_t R, int64_t C,
                           int q, int elem_bytes, void* stream);
 
+/* ---- the same algorithms step by step, from the COMPUTING device (Algorithms 1-3 as printed) ----
+ * optimus_summa_step: what device (i, j) multiplies in step l, as one dense fp32 [M/q x N/q] block c_temp:
+ *   AB : A_il B_lj           (both received; accumulated on the same device into C_ij)
+ *   ABT: A_ij (B_lj)^T       (B_lj received along column j; reduced within row i onto device (i, l) -> C_il)
+ *   ATB: (A_il)^T B_ij       (A_il received along row i; reduced within column j onto device (l, j) -> C_lj)
+ * optimus_summa_reduce: the reduce onto its root: adds `count` consecutive partial blocks c_temps[0..count) in
+ * index order (the order of the reducing grid index) and writes block (root_i, root_j) of the block-major
+ * [M x N] matrix C in `dtype`.  Partials in memory are what the owner-view entry points above avoid; these two
+ * exist so that the printed algorithms can be replayed and compared with them.  Operand layouts as above. */
+int optimus_summa_step(int form, const void* A, const void* B, float* c_temp, int64_t M, int64_t K, int64_t N,
+                       int q, int i, int j, int l, int dtype, void* stream);
+int optimus_summa_reduce(const float* c_temps, int count, void* C, int64_t M, int64_t N, int q, int root_i,
+                         int root_j, int dtype, void* stream);
+
 /* ---- the three SUMMA products (Section 2.4, Algorithms 1-3, Eq. 1-3) ----
  * (M, N) is always the logical OUTPUT shape and K the logical contraction
  * length; all three must be positive multiples of q.  A, B, C are block-major.

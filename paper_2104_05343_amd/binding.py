@@ -89,6 +89,8 @@ SIGNATURES = {
     "optimus_summa_atb": (_INT, _SUMMA_ARGS),
     "optimus_summa_workspace_bytes": (_SZ, [_INT, _I64, _I64, _I64, _INT, _INT, _INT, _INT]),
     "optimus_summa_ex": (_INT, [_INT, _P, _P, _P, _I64, _I64, _I64, _INT, _INT, _INT, _INT, C.POINTER(Epilogue), _P, _SZ, _P]),
+    "optimus_summa_step": (_INT, [_INT, _P, _P, _P, _I64, _I64, _I64, _INT, _INT, _INT, _INT, _INT, _P]),
+    "optimus_summa_reduce": (_INT, [_P, _INT, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
     "optimus_bias_grad": (_INT, [_P, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
     "optimus_layernorm2d_stats": (_INT, [_P, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
     "optimus_layernorm2d": (_INT, [_P, _P, _P, _P, _P, _P, _P, _I64, _I64, _INT, _INT, _INT, _F, _INT, _P]),
@@ -229,6 +231,18 @@ def layernorm2d_bwd(dY, xhat, rstd, gamma, dres, dX, dgamma_part, dbeta_part, st
     _check(lib().optimus_layernorm2d_bwd(_ptr(dY), _ptr(xhat), _ptr(rstd), _ptr(gamma), _ptr(dres), _ptr(dX), _ptr(dgamma_part),
                                          _ptr(dbeta_part), _ptr(stats), M, H, q, i, j, dtype, _stream(stream)),
            "optimus_layernorm2d_bwd")
+
+
+def summa_step(form, A, B, c_temp, M, K, N, q, i, j, l, dtype, stream=None):
+    """form: 'ab' | 'abt' | 'atb' or the OPTIMUS_FORM_* code."""
+    f = {"ab": 0, "abt": 1, "atb": 2}.get(form, form)
+    _check(lib().optimus_summa_step(f, _ptr(A), _ptr(B), _ptr(c_temp), M, K, N, q, i, j, l, dtype, _stream(stream)),
+           "optimus_summa_step")
+
+
+def summa_reduce(c_temps, count, Cmat, M, N, q, root_i, root_j, dtype, stream=None):
+    _check(lib().optimus_summa_reduce(_ptr(c_temps), count, _ptr(Cmat), M, N, q, root_i, root_j, dtype, _stream(stream)),
+           "optimus_summa_reduce")
 
 
 def attention_workspace_bytes(b, s, h, n, q) -> int:

@@ -438,6 +438,45 @@ size_t optimus_summa_workspace_bytes(int form, int64_t M, int64_t K, int64_t N, 
   return gemm_partials_bytes(d, s);
 }
 
+// One step of Algorithms 1-3 as the COMPUTING device (i, j) sees it (the owner view above fuses the q steps).
+int optimus_summa_step(int form, const void* A, const void* B, float* c_temp, int64_t M, int64_t K, int64_t N, int q, int i,
+                       int j, int l, int dtype, void* stream) {
+  if (!A || !B || !c_temp) return OPTIMUS_EINVAL;
+  if (form < 0 || form > 2) return OPTIMUS_EINVAL;
+  if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  int rc = check_mkn(M, K, N, q);
+  if (rc) return rc;
+  if (i < 0 || j < 0 || l < 0 || i >= q || j >= q || l >= q) return OPTIMUS_ECOORD;
+  const int Mb = (int)(M / q), Nb = (int)(N / q), Kp = (int)(K / q);
+  const long long blkA = (long long)Mb * Kp, blkB = (long long)Kp * Nb;
+  const size_t es = esize(dtype);
+  GemmDesc d = {};
+  d.Mb = Mb; d.Nb = Nb; d.Kp = Kp; d.nl = 1; d.dtype = dtype; d.nz0 = 1; d.nz1 = 1; d.alpha = 1.0f; d.splits = 1;
+  d.ldc = Nb; d.out_fp32 = dtype == OPTIMUS_BF16 ? 1 : 0; d.C = c_temp;
+  if (form == OPTIMUS_FORM_AB) {          // A_il [Mb x Kp] (received along row i) times B_lj [Kp x Nb] (along column j)
+    d.A = off(A, ((long long)i * q + l) * blkA, es); d.a_kcontig = 1; d.lda = Kp;
+    d.B = off(B, ((long long)l * q + j) * blkB, es); d.b_kcontig = 0; d.ldb = Nb;
+  } else if (form == OPTIMUS_FORM_ABT) {  // own A_ij [Mb x Kp] times (B_lj)^T, B_lj [Nb x Kp] received along column j
+    d.A = off(A, ((long long)i * q + j) * blkA, es); d.a_kcontig = 1; d.lda = Kp;
+    d.B = off(B, ((long long)l * q + j) * blkB, es); d.b_kcontig = 1; d.ldb = Kp;
+  } else {                                // (A_il)^T, A_il [Kp x Mb] received along row i, times own B_ij [Kp x Nb]
+    d.A = off(A, ((long long)i * q + l) * blkA, es); d.a_kcontig = 0; d.lda = Mb;
+    d.B = off(B, ((long long)i * q + j) * blkB, es); d.b_kcontig = 0; d.ldb = Nb;
+  }
+  return launch_gemm(d, as_stream(stream));
+}
+
+int optimus_summa_reduce(const float* c_temps, int count, void* C, int64_t M, int64_t N, int q, int root_i, int root_j,
+                         int dtype, void* stream) {
+  if (!c_temps || !C) return OPTIMUS_EINVAL;
+  if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  if (q <= 0 || M <= 0 || N <= 0 || M % q || N % q || count < 1 || count > 65536) return OPTIMUS_ESHAPE;
+  if (root_i < 0 || root_j < 0 || root_i >= q || root_j >= q) return OPTIMUS_ECOORD;
+  const long long blk = (M / q) * (N / q);
+  return launch_reduce_partials(c_temps, off(C, ((long long)root_i * q + root_j) * blk, esize(dtype)), blk, count, dtype,
+                                as_stream(stream));
+}
+
 int optimus_bias_grad(const void* dY, float* dbias_part, int64_t M, int64_t N, int q, int i, int j, int dtype, void* stream) {
   if (!dY || !dbias_part) return OPTIMUS_EINVAL;
   if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;

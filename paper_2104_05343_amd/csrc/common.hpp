@@ -99,6 +99,7 @@ int gemm_last_plan();
 // element-wise / reduction kernels
 int launch_pack(const void* src, void* dst, long long R, long long C, int q, int elem_bytes, bool unpack,
                 hipStream_t stream);
+int launch_reduce_partials(const float* parts, void* dst, long long n, int count, int dtype, hipStream_t stream);
 int launch_colsum(const void* X, float* out, int rows, int cols, int ld, int nz, long long sX, long long sOut,
                   int dtype, hipStream_t stream);
 
