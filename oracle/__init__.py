@@ -16,4 +16,4 @@ the design notes and shared by both sides): row order of M = b*s, head-major
 column order of the 3h projection, pre-LayerNorm wiring with two residuals,
 exact-erf GeLU, eps = 1e-5.
 """
-from . import blocks, summa, layernorm, attention, layer, metrics, flops  # noqa: F401
+from . import blocks, summa, layernorm, attention, layer, metrics, flops, stack, model_ends  # noqa: F401

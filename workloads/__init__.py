@@ -11,5 +11,6 @@ from .inputs import (  # noqa: F401
     gemm_inputs,
     layer_inputs,
     LayerShape,
+    token_inputs,
 )
 from .configs import CONFIGS, GemmCase, gemm_cases  # noqa: F401

@@ -127,3 +127,15 @@ def layer_inputs(seed: int, shp: LayerShape, dtype: str = "bf16", perturb_affine
         # vectors are stored in fp32 on the device but kept bf16-representable
         t[name] = _store(v, dtype)
     return t
+
+
+def token_inputs(seed: int, b: int, s: int, v: int):
+    """Token indices [b*s] (int32, sequence-major rows) and next-token labels [b*s] with the rank-frequency shape of
+    text: index r is drawn with probability proportional to 1/(r + 1) (Zipf), so a few rows of the embedding table
+    collect many gradient rows and most collect none."""
+    rng = np.random.default_rng(seed)
+    p = 1.0 / np.arange(1, v + 1)
+    p /= p.sum()
+    tokens = rng.choice(v, size=b * s, p=p).astype(np.int32)
+    labels = rng.choice(v, size=b * s, p=p).astype(np.int32)
+    return tokens, labels
