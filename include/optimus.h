@@ -316,6 +316,36 @@ int optimus_stack_bwd(const optimus_layer_cfg* cfg, int n_layers, const optimus_
                       const optimus_layer_grads* grads, const void* d_out, const optimus_stack_buffers* buf, void* d_x,
                       optimus_layer_done_fn done, void* user, void* stream);
 
+/* ---- the ends of the model in the 2D partition (Section 3.2.1, last paragraph; Section 3.2.2, cross entropy) ----
+ * tokens / labels: int32 [b*s] (rows sequence-major, as everywhere): grid row i owns entries i*M/q ..; every device of
+ * a grid row reads the same ones.  Indices outside [0, v) are clamped into range (no error is raised from a kernel).
+ * table: block-major [v x h] (block (l, j) = rows l*v/q.., columns j*h/q..).
+ * optimus_embedding_fwd(i, j): x_ij[t] = table[tokens[t]] restricted to columns j, i.e. the paper's one-hot product
+ *   sum_l onehot_il table_lj (Algorithm 1) as a row gather; x block-major [M x h]; bit-exact copy.
+ * optimus_embedding_bwd(l, j): the owner's block of the table gradient, d_table_lj = sum_i onehot_il^T dX_ij (the
+ *   A^T B form, Algorithm 3, reduced within column j onto (l, j)); reads ALL token indices and the blocks (i, j) of
+ *   d_x of every i (resident peers); d_table fp32 block-major [v x h], block (l, j) written completely (zeros where
+ *   no token refers to a row); sums in fp32 in the order of the tokens (deterministic).
+ * lm-head logits = hidden table^T: optimus_summa_abt(hidden, table, logits, M, h, v, ...).
+ * Cross entropy over logits block-major [M x v] (a row spans the q devices of a grid row):
+ *   stats fp32 [q][q][M/q][2]: entry (i, l) = (max, sum exp(x - max)) over device (i, l)'s columns;
+ *   optimus_cross_entropy2d_stats(i, l) writes that partial only; optimus_cross_entropy2d(i, j) computes its own
+ *   partial, combines the q partials of row i in the order l = 0..q-1 (peers' partials resident, as with LayerNorm),
+ *   and writes loss[i][j][t] = log sum_k exp(x_tk) - x_t,label and lse[i][j][t] (both fp32 [q][q][M/q]; the q
+ *   devices of a row write identical values).  optimus_cross_entropy2d_bwd(i, j):
+ *   d_logits_ij = scale * (exp(x - lse) - [column == label]) in the logits' dtype (the soft-max is rebuilt from lse
+ *   instead of being saved).  i = j = -1 runs every device.  dtype fp32 or bf16. */
+int optimus_embedding_fwd(const int32_t* tokens, const void* table, void* x, int64_t M, int64_t v, int64_t h,
+                          int q, int i, int j, int dtype, void* stream);
+int optimus_embedding_bwd(const int32_t* tokens, const void* d_x, float* d_table, int64_t M, int64_t v, int64_t h,
+                          int q, int l, int j, int dtype, void* stream);
+int optimus_cross_entropy2d_stats(const void* logits, float* stats, int64_t M, int64_t v, int q, int i, int l,
+                                  int dtype, void* stream);
+int optimus_cross_entropy2d(const void* logits, const int32_t* labels, float* loss, float* lse, float* stats,
+                            int64_t M, int64_t v, int q, int i, int j, int dtype, void* stream);
+int optimus_cross_entropy2d_bwd(const void* logits, const int32_t* labels, const float* lse, void* d_logits,
+                                float scale, int64_t M, int64_t v, int q, int i, int j, int dtype, void* stream);
+
 /* ---- flop accounting (Table 1) ----
  * optimus_gemm_flops: 2*(M/q)*K*(N/q), one device's share of one product.
  * optimus_layer_flops: one device's share of a layer; what = 0 forward,

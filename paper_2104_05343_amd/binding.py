@@ -102,6 +102,11 @@ SIGNATURES = {
     "optimus_attention_fused_fwd": (_INT, [_P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P]),
     "optimus_attention_fused_bwd": (_INT, [_P, _P, _P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
     "optimus_attention_fused_workspace_bytes": (_SZ, [_INT, _INT, _INT, _INT, _INT]),
+    "optimus_embedding_fwd": (_INT, [_P, _P, _P, _I64, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
+    "optimus_embedding_bwd": (_INT, [_P, _P, _P, _I64, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
+    "optimus_cross_entropy2d_stats": (_INT, [_P, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
+    "optimus_cross_entropy2d": (_INT, [_P, _P, _P, _P, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
+    "optimus_cross_entropy2d_bwd": (_INT, [_P, _P, _P, _P, _F, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
     "optimus_stack_sizes_of": (_INT, [C.POINTER(LayerCfg), _INT, C.POINTER(StackSizes)]),
     "optimus_layer_grads_in": (_INT, [C.POINTER(LayerCfg), _P, C.POINTER(LayerGrads)]),
     "optimus_stack_fwd": (_INT, [C.POINTER(LayerCfg), _INT, C.POINTER(LayerParams), _P, C.POINTER(StackBuffers), _P, _P]),
@@ -296,6 +301,31 @@ def layer_fwd(cfg: LayerCfg, t: LayerTensors, i, j, ws, stream=None):
 def layer_bwd(cfg: LayerCfg, t: LayerTensors, i, j, ws, stream=None):
     p, nb = _ws(ws)
     _check(lib().optimus_layer_bwd(C.byref(cfg), C.byref(t), i, j, p, nb, _stream(stream)), "optimus_layer_bwd")
+
+
+def embedding_fwd(tokens, table, x, M, v, h, q, i, j, dtype, stream=None):
+    _check(lib().optimus_embedding_fwd(_ptr(tokens), _ptr(table), _ptr(x), M, v, h, q, i, j, dtype, _stream(stream)),
+           "optimus_embedding_fwd")
+
+
+def embedding_bwd(tokens, d_x, d_table, M, v, h, q, l, j, dtype, stream=None):
+    _check(lib().optimus_embedding_bwd(_ptr(tokens), _ptr(d_x), _ptr(d_table), M, v, h, q, l, j, dtype, _stream(stream)),
+           "optimus_embedding_bwd")
+
+
+def cross_entropy2d_stats(logits, stats, M, v, q, i, l, dtype, stream=None):
+    _check(lib().optimus_cross_entropy2d_stats(_ptr(logits), _ptr(stats), M, v, q, i, l, dtype, _stream(stream)),
+           "optimus_cross_entropy2d_stats")
+
+
+def cross_entropy2d(logits, labels, loss, lse, stats, M, v, q, i, j, dtype, stream=None):
+    _check(lib().optimus_cross_entropy2d(_ptr(logits), _ptr(labels), _ptr(loss), _ptr(lse), _ptr(stats), M, v, q, i, j, dtype,
+                                         _stream(stream)), "optimus_cross_entropy2d")
+
+
+def cross_entropy2d_bwd(logits, labels, lse, d_logits, scale, M, v, q, i, j, dtype, stream=None):
+    _check(lib().optimus_cross_entropy2d_bwd(_ptr(logits), _ptr(labels), _ptr(lse), _ptr(d_logits), float(scale), M, v, q, i, j,
+                                             dtype, _stream(stream)), "optimus_cross_entropy2d_bwd")
 
 
 def stack_sizes(cfg: LayerCfg, n_layers: int) -> StackSizes:

@@ -263,6 +263,18 @@ int run_attention_fused(bool bwd, const void* qkv, void* attn, float* lse, const
   return bwd ? launch_attn_fused_bwd(d, as_stream(stream)) : launch_attn_fused_fwd(d, as_stream(stream));
 }
 
+int end_desc(int64_t M, int64_t v, int64_t h, int q, int i, int j, int dtype, EndDesc* d) {
+  if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  if (q <= 0 || M <= 0 || v <= 0 || h <= 0 || M % q || v % q || h % q) return OPTIMUS_ESHAPE;
+  if (M > 0x7fffffff || v > 0x7fffffff || h > 0x7fffffff) return OPTIMUS_ESHAPE;
+  int rc = check_coords(q, i, j);
+  if (rc) return rc;
+  d->rows = (int)(M / q); d->vb = (int)(v / q); d->hb = (int)(h / q); d->q = q; d->v = (int)v; d->dtype = dtype;
+  if (is_grid(i, j)) { d->i0 = 0; d->ni = q; d->j0 = 0; d->nj = q; }
+  else { d->i0 = i; d->ni = 1; d->j0 = j; d->nj = 1; }
+  return OPTIMUS_OK;
+}
+
 int ln_desc(int64_t M, int64_t H, int q, int i, int j, int dtype, float eps, LnDesc* d) {
   if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
   if (q <= 0 || M <= 0 || H <= 0 || M % q || H % q) return OPTIMUS_ESHAPE;
@@ -573,6 +585,48 @@ int layer_attention(bool bwd, const optimus_layer_cfg* c, const optimus_layer_te
                          ws, ws_bytes, stream);
   return run_attention(false, t->qkv, nullptr, t->probs, nullptr, t->attn, c->b, c->s, c->h, c->n, c->q, i, j, causal, c->dtype, ws,
                        ws_bytes, stream);
+}
+
+int optimus_embedding_fwd(const int32_t* tokens, const void* table, void* x, int64_t M, int64_t v, int64_t h, int q, int i, int j,
+                          int dtype, void* stream) {
+  if (!tokens || !table || !x) return OPTIMUS_EINVAL;
+  EndDesc d;
+  int rc = end_desc(M, v, h, q, i, j, dtype, &d);
+  if (rc) return rc;
+  return launch_embedding_fwd(tokens, table, x, d, as_stream(stream));
+}
+int optimus_embedding_bwd(const int32_t* tokens, const void* d_x, float* d_table, int64_t M, int64_t v, int64_t h, int q, int l,
+                          int j, int dtype, void* stream) {
+  if (!tokens || !d_x || !d_table) return OPTIMUS_EINVAL;
+  EndDesc d;
+  int rc = end_desc(M, v, h, q, l, j, dtype, &d);
+  if (rc) return rc;
+  return launch_embedding_bwd(tokens, d_x, d_table, d, as_stream(stream));
+}
+int optimus_cross_entropy2d_stats(const void* logits, float* stats, int64_t M, int64_t v, int q, int i, int l, int dtype,
+                                  void* stream) {
+  if (!logits || !stats) return OPTIMUS_EINVAL;
+  EndDesc d;
+  int rc = end_desc(M, v, q, q, i, l, dtype, &d);
+  if (rc) return rc;
+  return launch_ce_stats(logits, stats, d, as_stream(stream));
+}
+int optimus_cross_entropy2d(const void* logits, const int32_t* labels, float* loss, float* lse, float* stats, int64_t M, int64_t v,
+                            int q, int i, int j, int dtype, void* stream) {
+  if (!logits || !labels || !loss || !lse || !stats) return OPTIMUS_EINVAL;
+  EndDesc d;
+  int rc = end_desc(M, v, q, q, i, j, dtype, &d);
+  if (rc) return rc;
+  if ((rc = launch_ce_stats(logits, stats, d, as_stream(stream)))) return rc;   // own partial (all partials in grid mode)
+  return launch_ce_finalize(logits, labels, stats, loss, lse, d, as_stream(stream));
+}
+int optimus_cross_entropy2d_bwd(const void* logits, const int32_t* labels, const float* lse, void* d_logits, float scale, int64_t M,
+                                int64_t v, int q, int i, int j, int dtype, void* stream) {
+  if (!logits || !labels || !lse || !d_logits) return OPTIMUS_EINVAL;
+  EndDesc d;
+  int rc = end_desc(M, v, q, q, i, j, dtype, &d);
+  if (rc) return rc;
+  return launch_ce_bwd(logits, labels, lse, d_logits, scale, d, as_stream(stream));
 }
 
 size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg) {

@@ -143,6 +143,20 @@ bool attn_fused_supported(int d);
 int launch_attn_fused_fwd(const AttnFusedDesc& d, hipStream_t stream);
 int launch_attn_fused_bwd(const AttnFusedDesc& d, hipStream_t stream);
 
+// model ends (embedding, cross entropy) on the devices i0..i0+ni-1 x j0..j0+nj-1 of the grid
+struct EndDesc {
+  int rows, vb, hb, q, v;   // M/q, v/q, h/q, grid size, vocabulary size
+  int i0, ni, j0, nj;
+  int dtype;
+};
+int launch_embedding_fwd(const int* tokens, const void* table, void* out, const EndDesc& d, hipStream_t stream);
+int launch_embedding_bwd(const int* tokens, const void* dX, float* d_table, const EndDesc& d, hipStream_t stream);
+int launch_ce_stats(const void* logits, float* stats, const EndDesc& d, hipStream_t stream);
+int launch_ce_finalize(const void* logits, const int* labels, const float* stats, float* loss, float* lse, const EndDesc& d,
+                       hipStream_t stream);
+int launch_ce_bwd(const void* logits, const int* labels, const float* lse, void* d_logits, float scale, const EndDesc& d,
+                  hipStream_t stream);
+
 // optimus_layer_fwd, optionally without its last product (used by the checkpointed stack's recomputation)
 int layer_forward(const optimus_layer_cfg* c, const optimus_layer_tensors* t, int i, int j, void* ws, size_t ws_bytes,
                   void* stream, bool skip_out);

@@ -1,0 +1,217 @@
+// The two ends of the model around the layer stack in the 2D partition (Sections 3.2.1 / 3.2.2 of the paper):
+//   * embedding: the paper's "one-hot matrix times embedding table" product is a row gather.  Device (i, j) holds the
+//     token indices of grid row i (every device of a row has them) and the table block (l, j) of every l is resident:
+//     out_ij[t] = table block (tok / (v/q), j), row tok % (v/q).  Pure copy: bit exact, HBM bound.
+//   * embedding gradient: d_table_lj = sum_i one_hot_il^T dX_ij, the A^T B form reduced within column j onto its owner
+//     (l, j).  Computed as the owner sees it: a workgroup owns 128 table rows x 256 columns of the block as an fp32
+//     accumulator in LDS, scans ALL token indices in order (the test "does this token fall into my rows" is uniform
+//     over the workgroup), adds the matching rows of dX and writes its piece once.  No atomics, fixed order (grid row,
+//     then position): deterministic, and rows that no token refers to are written as zeros.
+//   * cross entropy H = log(sum_i exp(x_i)) - x_label over a logits row that spans the q devices of a grid row: each
+//     device reduces its v/q columns to (max, sum exp(x - max)) -- the maximum is subtracted for range, which does
+//     not change the value --, the q partials are combined in the order l = 0..q-1 (the row all-reduce), and the
+//     device computes the loss and keeps L = log sum exp per row.  Backward: q_j - [j = label] with
+//     q_j = exp(x_j - L) recomputed from the saved L (the paper saves the soft-max itself: v/2 times the bytes).
+// The lm-head logits are the C = A B^T product of the hidden states with the table: optimus_summa_abt.
+#include "common.hpp"
+
+namespace optimus {
+namespace {
+
+__device__ __forceinline__ float wave_sum_f(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max_f(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+template <typename T> __device__ __forceinline__ float ldf(const T* p);
+template <> __device__ __forceinline__ float ldf<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <> __device__ __forceinline__ float ldf<float>(const float* p) { return *p; }
+template <typename T> __device__ __forceinline__ void stf(T* p, float v);
+template <> __device__ __forceinline__ void stf<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+template <> __device__ __forceinline__ void stf<float>(float* p, float v) { *p = v; }
+
+__device__ __forceinline__ int clamp_token(int t, int v) { return min(max(t, 0), v - 1); }
+
+struct EndArgs {
+  int rows;        // M/q: rows of a block
+  int vb, hb;      // v/q, h/q
+  int q, v;
+  int i0, ni, j0, nj;  // devices handled: grid rows i0.., grid columns j0..
+};
+
+// ---- embedding forward: one wavefront per output row; 16-byte copies when the block width allows ----
+template <typename T>
+__global__ __launch_bounds__(256) void embedding_fwd_kernel(const int* __restrict__ tokens, const T* __restrict__ table,
+                                                            T* __restrict__ out, EndArgs a) {
+  const int lane = threadIdx.x & 63;
+  const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.rows) return;
+  const int dev = blockIdx.y;
+  const int i = a.i0 + dev / a.nj, j = a.j0 + dev % a.nj;
+  const int tok = clamp_token(tokens[(long long)i * a.rows + r], a.v);
+  const int l = tok / a.vb, tr = tok % a.vb;
+  const T* src = table + (((long long)l * a.q + j) * a.vb + tr) * a.hb;
+  T* dst = out + (((long long)i * a.q + j) * a.rows + r) * a.hb;
+  constexpr int VN = 16 / sizeof(T);
+  if (a.hb % VN == 0) {
+    for (int c = lane * VN; c < a.hb; c += 64 * VN) *(uint4*)(dst + c) = *(const uint4*)(src + c);
+  } else {
+    for (int c = lane; c < a.hb; c += 64) dst[c] = src[c];
+  }
+}
+
+// ---- embedding backward (owner view): workgroup = EB_ROWS table rows x 256 columns of block (l, j) ----
+constexpr int EB_ROWS = 128, EB_COLS = 256, EB_CHUNK = 1024;
+template <typename T>
+__global__ __launch_bounds__(256) void embedding_bwd_kernel(const int* __restrict__ tokens, const T* __restrict__ dX,
+                                                            float* __restrict__ d_table, EndArgs a) {
+  __shared__ float acc[EB_ROWS * EB_COLS];
+  __shared__ int tk[EB_CHUNK];
+  const int tid = threadIdx.x;
+  const int dev = blockIdx.z;
+  const int l = a.i0 + dev / a.nj, j = a.j0 + dev % a.nj;
+  const int r0 = blockIdx.y * EB_ROWS;                  // first table row (inside block l) of this workgroup
+  const int nr = min(EB_ROWS, a.vb - r0);
+  const int c = blockIdx.x * EB_COLS + tid;             // column inside the block
+  const bool col_ok = c < a.hb;
+  for (int k = tid; k < EB_ROWS * EB_COLS; k += 256) acc[k] = 0.f;
+  const int lo = l * a.vb + r0, hi = lo + nr;           // token indices that land in this workgroup's rows
+  const long long total = (long long)a.q * a.rows;      // all tokens, grid row after grid row
+  for (long long base = 0; base < total; base += EB_CHUNK) {
+    __syncthreads();
+    for (int k = tid; k < EB_CHUNK; k += 256) tk[k] = base + k < total ? clamp_token(tokens[base + k], a.v) : -1;
+    __syncthreads();
+    const int n = (int)min((long long)EB_CHUNK, total - base);
+    for (int k = 0; k < n; ++k) {
+      const int tok = tk[k];
+      if (tok >= lo && tok < hi && col_ok) {            // uniform over the workgroup except for the column guard
+        const long long t = base + k;
+        const long long i = t / a.rows, rr = t % a.rows;
+        acc[(tok - lo) * EB_COLS + tid] += ldf<T>(dX + ((i * a.q + j) * a.rows + rr) * a.hb + c);
+      }
+    }
+  }
+  __syncthreads();
+  if (col_ok) {
+    float* dst = d_table + (((long long)l * a.q + j) * a.vb + r0) * a.hb + c;
+    for (int r = 0; r < nr; ++r) dst[(long long)r * a.hb] = acc[r * EB_COLS + tid];
+  }
+}
+
+// ---- cross entropy ----
+// partial statistics of one block: (max, sum exp(x - max)) per row; one wavefront per row
+template <typename T>
+__global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ logits, float* __restrict__ stats, EndArgs a) {
+  const int lane = threadIdx.x & 63;
+  const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.rows) return;
+  const int dev = blockIdx.y;
+  const int i = a.i0 + dev / a.nj, j = a.j0 + dev % a.nj;
+  const long long blk = (long long)i * a.q + j;
+  const T* src = logits + (blk * a.rows + r) * a.vb;
+  float m = -INFINITY, s = 0.f;
+  for (int c = lane; c < a.vb; c += 64) {
+    const float x = ldf<T>(src + c);
+    if (x > m) { s = s * __expf(m - x) + 1.0f; m = x; }   // exp(-inf - x) = 0 on the first element
+    else if (m > -INFINITY) s += __expf(x - m);               // (a row of -inf entries contributes nothing)
+  }
+  const float mw = wave_max_f(m);
+  s = wave_sum_f(m == -INFINITY ? 0.f : s * __expf(m - mw));
+  if (lane == 0) {
+    stats[(blk * a.rows + r) * 2] = mw;
+    stats[(blk * a.rows + r) * 2 + 1] = s;
+  }
+}
+
+// combine the q partials of a grid row in the order l = 0..q-1; loss and log-sum-exp per row of device (i, j)
+template <typename T>
+__global__ __launch_bounds__(256) void ce_finalize_kernel(const T* __restrict__ logits, const int* __restrict__ labels,
+                                                          const float* __restrict__ stats, float* __restrict__ loss,
+                                                          float* __restrict__ lse, EndArgs a) {
+  const long long r = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (r >= a.rows) return;
+  const int dev = blockIdx.y;
+  const int i = a.i0 + dev / a.nj, j = a.j0 + dev % a.nj;
+  float m = -INFINITY;
+  for (int l = 0; l < a.q; ++l) m = fmaxf(m, stats[(((long long)i * a.q + l) * a.rows + r) * 2]);
+  float s = 0.f;
+  for (int l = 0; l < a.q; ++l) {
+    const float* p = stats + (((long long)i * a.q + l) * a.rows + r) * 2;
+    s += p[1] * __expf(p[0] - m);
+  }
+  const float L = m + __logf(s);
+  const int lab = clamp_token(labels[(long long)i * a.rows + r], a.v);
+  const float xl = ldf<T>(logits + ((((long long)i * a.q + lab / a.vb) * a.rows + r) * a.vb + lab % a.vb));
+  const long long o = ((long long)i * a.q + j) * a.rows + r;
+  lse[o] = L;
+  loss[o] = L - xl;
+}
+
+// d_logits = scale * (exp(x - L) - [column == label]); one wavefront per row of a block
+template <typename T>
+__global__ __launch_bounds__(256) void ce_bwd_kernel(const T* __restrict__ logits, const int* __restrict__ labels,
+                                                     const float* __restrict__ lse, T* __restrict__ d_logits, float scale, EndArgs a) {
+  const int lane = threadIdx.x & 63;
+  const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.rows) return;
+  const int dev = blockIdx.y;
+  const int i = a.i0 + dev / a.nj, j = a.j0 + dev % a.nj;
+  const long long blk = (long long)i * a.q + j;
+  const T* src = logits + (blk * a.rows + r) * a.vb;
+  T* dst = d_logits + (blk * a.rows + r) * a.vb;
+  const float L = lse[blk * a.rows + r];
+  const int lab = clamp_token(labels[(long long)i * a.rows + r], a.v) - j * a.vb;   // label column inside this block, if any
+  for (int c = lane; c < a.vb; c += 64) {
+    const float qv = __expf(ldf<T>(src + c) - L);
+    stf<T>(dst + c, scale * (qv - (c == lab ? 1.0f : 0.0f)));
+  }
+}
+
+}  // namespace
+
+int launch_embedding_fwd(const int* tokens, const void* table, void* out, const EndDesc& d, hipStream_t st) {
+  EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
+  const dim3 grid((d.rows + 3) / 4, d.ni * d.nj);
+  if (d.dtype == OPTIMUS_BF16) embedding_fwd_kernel<bf16_t><<<grid, 256, 0, st>>>(tokens, (const bf16_t*)table, (bf16_t*)out, a);
+  else embedding_fwd_kernel<float><<<grid, 256, 0, st>>>(tokens, (const float*)table, (float*)out, a);
+  return hip_launch_status();
+}
+int launch_embedding_bwd(const int* tokens, const void* dX, float* d_table, const EndDesc& d, hipStream_t st) {
+  EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
+  const dim3 grid((d.hb + EB_COLS - 1) / EB_COLS, (d.vb + EB_ROWS - 1) / EB_ROWS, d.ni * d.nj);
+  if (grid.y > 65535 || grid.z > 65535) return OPTIMUS_ESHAPE;
+  if (d.dtype == OPTIMUS_BF16) embedding_bwd_kernel<bf16_t><<<grid, 256, 0, st>>>(tokens, (const bf16_t*)dX, d_table, a);
+  else embedding_bwd_kernel<float><<<grid, 256, 0, st>>>(tokens, (const float*)dX, d_table, a);
+  return hip_launch_status();
+}
+int launch_ce_stats(const void* logits, float* stats, const EndDesc& d, hipStream_t st) {
+  EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
+  const dim3 grid((d.rows + 3) / 4, d.ni * d.nj);
+  if (d.dtype == OPTIMUS_BF16) ce_stats_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)logits, stats, a);
+  else ce_stats_kernel<float><<<grid, 256, 0, st>>>((const float*)logits, stats, a);
+  return hip_launch_status();
+}
+int launch_ce_finalize(const void* logits, const int* labels, const float* stats, float* loss, float* lse, const EndDesc& d,
+                       hipStream_t st) {
+  EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
+  const dim3 grid((d.rows + 255) / 256, d.ni * d.nj);
+  if (d.dtype == OPTIMUS_BF16) ce_finalize_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)logits, labels, stats, loss, lse, a);
+  else ce_finalize_kernel<float><<<grid, 256, 0, st>>>((const float*)logits, labels, stats, loss, lse, a);
+  return hip_launch_status();
+}
+int launch_ce_bwd(const void* logits, const int* labels, const float* lse, void* d_logits, float scale, const EndDesc& d,
+                  hipStream_t st) {
+  EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
+  const dim3 grid((d.rows + 3) / 4, d.ni * d.nj);
+  if (d.dtype == OPTIMUS_BF16)
+    ce_bwd_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)logits, labels, lse, (bf16_t*)d_logits, scale, a);
+  else ce_bwd_kernel<float><<<grid, 256, 0, st>>>((const float*)logits, labels, lse, (float*)d_logits, scale, a);
+  return hip_launch_status();
+}
+
+}  // namespace optimus

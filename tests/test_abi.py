@@ -57,6 +57,12 @@ def test_host_validation_without_gpu():
     assert L.optimus_attention_fused_bwd(one, one, one, one, one, 4, 64, 128, 2, 2, 0, 0, 1, 1, None, 0, None) == opt.EWORKSPACE
     assert L.optimus_attention_fused_workspace_bytes(4, 64, 128, 2, 2) >= 4 * 2 * 64 * 4
     assert L.optimus_attention_fused_workspace_bytes(4, 64, 64, 4, 2) == 0
+    assert L.optimus_embedding_fwd(one, one, one, 64, 510, 128, 4, 0, 0, 1, None) == opt.ESHAPE
+    assert L.optimus_embedding_bwd(one, one, one, 64, 512, 128, 4, 4, 0, 1, None) == opt.ECOORD
+    assert L.optimus_cross_entropy2d(one, one, one, one, one, 64, 512, 4, 0, 0, 9, None) == opt.EDTYPE
+    assert L.optimus_cross_entropy2d_bwd(one, one, one, None, 1.0, 64, 512, 4, 0, 0, 1, None) == opt.EINVAL
+    assert L.optimus_summa_step(1, one, one, one, 32, 64, 256, 2, 0, 0, 2, 1, None) == opt.ECOORD
+    assert L.optimus_summa_reduce(one, 0, one, 32, 64, 2, 0, 0, 1, None) == opt.ESHAPE
 
 
 def test_stack_sizes_host_only():

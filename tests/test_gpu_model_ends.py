@@ -1,0 +1,200 @@
+"""GPU parity: 2D embedding (forward bit-exact, table gradient), lm-head logits and 2D cross entropy (loss, row
+log-sum-exp, logits gradient) against the fp64 oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2104_05343_amd as opt
+from oracle import model_ends as me
+from oracle.metrics import rel_frobenius
+from workloads import round_to_bf16, token_inputs
+from gpu_util import mat_to_dev, mat_to_host, to_host, empty, dt
+
+pytestmark = pytest.mark.gpu
+TOL = {"bf16": 5e-3, "fp32": 1e-5}
+TOL_F32 = 1e-5   # fp32 results (table gradient, loss, log-sum-exp) of bf16-representable inputs
+
+
+def _ints(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda:0")
+
+
+def _draw(rng, shape, dtype, scale=1.0):
+    x = (rng.standard_normal(shape) * scale).astype(np.float32)
+    return round_to_bf16(x) if dtype == "bf16" else x
+
+
+# (b, s, v, h, q): table blocks of more than one 128-row piece with a ragged last piece, block widths above 256 and
+# not a multiple of 8 (scalar copy path), q = 1, 2, 4
+CASES = [(4, 64, 512, 128, 2), (8, 96, 1000, 192, 4), (2, 50, 600, 72, 2), (4, 32, 768, 1280, 4), (2, 40, 300, 64, 1)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("b,s,v,h,q", CASES)
+def test_embedding_forward_and_table_gradient(b, s, v, h, q, dtype):
+    rng = np.random.default_rng(v + h)
+    M = b * s
+    tokens, _ = token_inputs(v, b, s, v)
+    table = _draw(rng, (v, h), dtype)
+    d_x = _draw(rng, (M, h), dtype)
+    dT, dTok = mat_to_dev(table, q, dtype), _ints(tokens)
+    X = empty(M * h, dtype)
+    opt.embedding_fwd(dTok, dT, X, M, v, h, q, -1, -1, dt(dtype))
+    torch.cuda.synchronize()
+    assert np.array_equal(mat_to_host(X, M, h, q), me.embedding(tokens, table).astype(np.float32))      # a copy: exact
+    # one device: its block only, same bits
+    i, j = q - 1, 0
+    X1 = empty(M * h, dtype)
+    opt.embedding_fwd(dTok, dT, X1, M, v, h, q, i, j, dt(dtype))
+    torch.cuda.synchronize()
+    blk = (M // q) * (h // q)
+    a, a1 = to_host(X), to_host(X1)
+    sl = slice((i * q + j) * blk, (i * q + j + 1) * blk)
+    assert np.array_equal(a[sl], a1[sl])
+    mask = np.ones(a.size, dtype=bool)
+    mask[sl] = False
+    assert np.all(np.isnan(a1[mask]))
+
+    dX = mat_to_dev(d_x, q, dtype)
+    G = empty(v * h, "fp32")
+    opt.embedding_bwd(dTok, dX, G, M, v, h, q, -1, -1, dt(dtype))
+    torch.cuda.synchronize()
+    got = mat_to_host(G, v, h, q)
+    want = me.embedding_grad(tokens, d_x, v)
+    assert rel_frobenius(got, want) <= TOL_F32
+    absent = np.setdiff1d(np.arange(v), tokens)
+    assert absent.size > 0 and np.all(got[absent] == 0.0)
+    G2 = empty(v * h, "fp32")
+    opt.embedding_bwd(dTok, dX, G2, M, v, h, q, -1, -1, dt(dtype))          # fixed summation order: same bits again
+    l, j = 0, q - 1                                                          # block 0 holds the frequent indices
+    G1 = empty(v * h, "fp32")
+    opt.embedding_bwd(dTok, dX, G1, M, v, h, q, l, j, dt(dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(G.view(torch.int32), G2.view(torch.int32))
+    tb = (v // q) * (h // q)
+    sl = slice((l * q + j) * tb, (l * q + j + 1) * tb)
+    assert torch.equal(G.view(torch.int32)[sl], G1.view(torch.int32)[sl])
+    rest = to_host(G1)
+    mask = np.ones(rest.size, dtype=bool)
+    mask[sl] = False
+    assert np.all(np.isnan(rest[mask]))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("b,s,v,q", [(4, 64, 512, 2), (8, 96, 1000, 4), (2, 50, 602, 2), (2, 40, 300, 1), (2, 64, 32768, 4)])
+def test_cross_entropy_forward_backward(b, s, v, q, dtype):
+    rng = np.random.default_rng(v + q)
+    M = b * s
+    _, labels = token_inputs(v + 1, b, s, v)
+    logits = _draw(rng, (M, v), dtype, 3.0)
+    loss_o, lse_o = me.cross_entropy(logits, labels)
+    dL, dLab = mat_to_dev(logits, q, dtype), _ints(labels)
+    rows = M // q
+    loss, lse, stats = empty(q * q * rows, "fp32"), empty(q * q * rows, "fp32"), empty(q * q * rows * 2, "fp32")
+    opt.cross_entropy2d(dL, dLab, loss, lse, stats, M, v, q, -1, -1, dt(dtype))
+    torch.cuda.synchronize()
+    got_loss, got_lse = to_host(loss).reshape(q, q, rows), to_host(lse).reshape(q, q, rows)
+    for j in range(q):    # every device of a grid row holds the same values
+        assert np.array_equal(got_loss[:, j], got_loss[:, 0]) and np.array_equal(got_lse[:, j], got_lse[:, 0])
+    assert rel_frobenius(got_lse[:, 0].reshape(-1), lse_o) <= TOL_F32
+    assert rel_frobenius(got_loss[:, 0].reshape(-1), loss_o) <= TOL_F32
+    scale = 1.0 / M
+    dlog = empty(M * v, dtype)
+    opt.cross_entropy2d_bwd(dL, dLab, lse, dlog, scale, M, v, q, -1, -1, dt(dtype))
+    torch.cuda.synchronize()
+    got = mat_to_host(dlog, M, v, q)
+    assert rel_frobenius(got, me.cross_entropy_grad(logits, labels, scale)) <= TOL[dtype]
+    if dtype == "fp32":
+        assert np.allclose(got.sum(axis=1), 0.0, atol=1e-6 * scale * 10)
+    # one device from resident peers: partial statistics of the others are in `stats`; same bits
+    i, j = q - 1, 0
+    loss1, lse1, dlog1 = empty(q * q * rows, "fp32"), empty(q * q * rows, "fp32"), empty(M * v, dtype)
+    opt.cross_entropy2d(dL, dLab, loss1, lse1, stats, M, v, q, i, j, dt(dtype))
+    opt.cross_entropy2d_bwd(dL, dLab, lse, dlog1, scale, M, v, q, i, j, dt(dtype))
+    torch.cuda.synchronize()
+    sl = slice((i * q + j) * rows, (i * q + j + 1) * rows)
+    assert torch.equal(loss.view(torch.int32)[sl], loss1.view(torch.int32)[sl])
+    assert torch.equal(lse.view(torch.int32)[sl], lse1.view(torch.int32)[sl])
+    blk = rows * (v // q)
+    sl = slice((i * q + j) * blk, (i * q + j + 1) * blk)
+    a, a1 = to_host(dlog), to_host(dlog1)
+    assert np.array_equal(a[sl], a1[sl])
+    mask = np.ones(a.size, dtype=bool)
+    mask[sl] = False
+    assert np.all(np.isnan(a1[mask]))
+
+
+def test_cross_entropy_closed_forms_and_range():
+    b, s, v, q = 2, 32, 256, 2
+    M = b * s
+    _, labels = token_inputs(9, b, s, v)
+    rows = M // q
+    for fill, want in ((0.0, math.log(v)), (3000.0, math.log(v))):      # uniform prediction; huge equal logits: no overflow
+        dL = mat_to_dev(np.full((M, v), fill, dtype=np.float32), q, "fp32")
+        loss, lse, stats = empty(q * q * rows, "fp32"), empty(q * q * rows, "fp32"), empty(q * q * rows * 2, "fp32")
+        opt.cross_entropy2d(dL, _ints(labels), loss, lse, stats, M, v, q, -1, -1, opt.FP32)
+        torch.cuda.synchronize()
+        assert np.allclose(to_host(loss), want, atol=1e-3 if fill else 1e-6)
+    # certain and right: loss ~ 0
+    x = np.zeros((M, v), dtype=np.float32)
+    x[np.arange(M), labels] = 60.0
+    loss, lse, stats = empty(q * q * rows, "fp32"), empty(q * q * rows, "fp32"), empty(q * q * rows * 2, "fp32")
+    opt.cross_entropy2d(mat_to_dev(x, q, "fp32"), _ints(labels), loss, lse, stats, M, v, q, -1, -1, opt.FP32)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(to_host(loss)) < 1e-5)
+
+
+def test_lm_head_and_whole_tail_against_oracle():
+    """tokens -> embedding -> lm-head with the same table (C = A B^T) -> cross entropy -> gradients back to the table:
+    d_hidden = d_logits table, d_table = d_logits^T hidden + the embedding's scatter."""
+    b, s, v, h, q = 4, 32, 512, 128, 2
+    M = b * s
+    rng = np.random.default_rng(5)
+    tokens, labels = token_inputs(6, b, s, v)
+    table = _draw(rng, (v, h), "bf16", 0.5)
+    X_o = me.embedding(tokens, table)
+    logits_o = me.lm_head(X_o, table)
+    dTok, dLab, dT = _ints(tokens), _ints(labels), mat_to_dev(table, q, "bf16")
+    X, logits = empty(M * h, "bf16"), empty(M * v, "bf16")
+    opt.embedding_fwd(dTok, dT, X, M, v, h, q, -1, -1, opt.BF16)
+    opt.summa("abt", X, dT, logits, M, h, v, q, -1, -1, opt.BF16)
+    torch.cuda.synchronize()
+    lg = mat_to_host(logits, M, v, q)
+    assert rel_frobenius(lg, logits_o) <= TOL["bf16"]
+    rows = M // q
+    loss, lse, stats = empty(q * q * rows, "fp32"), empty(q * q * rows, "fp32"), empty(q * q * rows * 2, "fp32")
+    dlog = empty(M * v, "bf16")
+    opt.cross_entropy2d(logits, dLab, loss, lse, stats, M, v, q, -1, -1, opt.BF16)
+    opt.cross_entropy2d_bwd(logits, dLab, lse, dlog, 1.0, M, v, q, -1, -1, opt.BF16)
+    torch.cuda.synchronize()
+    # stage-wise: the loss of the logits the device stored
+    loss_o, _ = me.cross_entropy(lg, labels)
+    assert rel_frobenius(to_host(loss).reshape(q, q, rows)[:, 0].reshape(-1), loss_o) <= TOL_F32
+    g_o = me.cross_entropy_grad(lg, labels, 1.0)
+    g_dev = mat_to_host(dlog, M, v, q)
+    assert rel_frobenius(g_dev, g_o) <= TOL["bf16"]
+    d_hidden, d_table_head = empty(M * h, "bf16"), empty(v * h, "fp32")
+    opt.summa("ab", dlog, dT, d_hidden, M, v, h, q, -1, -1, opt.BF16)
+    opt.summa_ex("atb", dlog, X, d_table_head, v, M, h, q, -1, -1, opt.BF16, out_fp32=True)
+    d_table_emb = empty(v * h, "fp32")
+    opt.embedding_bwd(dTok, d_hidden, d_table_emb, M, v, h, q, -1, -1, opt.BF16)
+    torch.cuda.synchronize()
+    dh = mat_to_host(d_hidden, M, h, q)
+    assert rel_frobenius(dh, g_dev.astype(np.float64) @ table.astype(np.float64)) <= TOL["bf16"]
+    assert rel_frobenius(mat_to_host(d_table_head, v, h, q), g_dev.astype(np.float64).T @ X_o) <= TOL["bf16"]
+    assert rel_frobenius(mat_to_host(d_table_emb, v, h, q), me.embedding_grad(tokens, dh, v)) <= TOL_F32
+
+
+def test_model_end_errors():
+    one = empty(64, "bf16")
+    f = empty(64, "fp32")
+    tok = _ints(np.zeros(64))
+    for args, code in [((64, 510, 128, 4), opt.ESHAPE), ((63, 512, 128, 2), opt.ESHAPE)]:
+        with pytest.raises(opt.OptimusError) as e:
+            opt.embedding_fwd(tok, one, one, *args, 0, 0, opt.BF16)
+        assert e.value.code == code
+    with pytest.raises(opt.OptimusError) as e:
+        opt.cross_entropy2d(one, tok, f, f, f, 64, 512, 2, 2, 0, opt.BF16)
+    assert e.value.code == opt.ECOORD
