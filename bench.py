@@ -248,6 +248,50 @@ def time_stack(opt, torch, harness, cfg, T, b, s, h, n, q, layers, reps):
             "bytes_checkpointed_total": int(ckpt), "bytes_all_activations_kept_total": int(kept)}
 
 
+def time_model_ends(opt, torch, b, s, h, q, i, j, v, reps, seed):
+    """Embedding, lm-head and cross entropy of ONE device at a workload's sizes (the paper fixes no vocabulary size:
+    v = 32768 here, a power of two near common sub-word vocabularies; token indices Zipf-distributed).  HBM-bound
+    kernels report algorithmic bytes / time; the lm-head is the C = A B^T product [M/q x h] x [v/q x h]^T."""
+    from workloads import token_inputs
+    M = b * s
+    rows, vb, hb = M // q, v // q, h // q
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(seed)
+
+    def rnd(nel, scale=1.0):
+        return (torch.randn(nel, generator=gen, device="cuda:0", dtype=torch.float32) * scale).to(torch.bfloat16)
+    tok_h, lab_h = token_inputs(seed, b, s, v)
+    tok, lab = torch.from_numpy(tok_h).to("cuda:0"), torch.from_numpy(lab_h).to("cuda:0")
+    table, x, d_x = rnd(v * h, 0.02), torch.empty(M * h, dtype=torch.bfloat16, device="cuda:0"), rnd(M * h)
+    d_table = torch.empty(v * h, dtype=torch.float32, device="cuda:0")
+    logits = rnd(M * v, 2.0)
+    d_logits = torch.empty(M * v, dtype=torch.bfloat16, device="cuda:0")
+    loss, lse = (torch.empty(q * q * rows, dtype=torch.float32, device="cuda:0") for _ in range(2))
+    stats = torch.empty(q * q * rows * 2, dtype=torch.float32, device="cuda:0")
+    opt.cross_entropy2d(logits, lab, loss, lse, stats, M, v, q, -1, -1, opt.BF16)   # peers' partials resident
+    out = {"v": v, "device": [i, j]}
+
+    def put(name, ms, nbytes, note):
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[name] = {"us": round(ms * 1e3, 2), "algorithmic_bytes": int(nbytes), "GBps": round(gbs, 1),
+                     "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "what": note}
+    ms = event_time_ms(lambda: opt.embedding_fwd(tok, table, x, M, v, h, q, i, j, opt.BF16), reps)
+    put("embedding_fwd", ms, 2 * rows * hb * 2 + rows * 4, f"gather {rows} rows of {hb} bf16: read + write")
+    ms = event_time_ms(lambda: opt.embedding_bwd(tok, d_x, d_table, M, v, h, q, 0, j, opt.BF16), reps)
+    put("embedding_bwd", ms, M * hb * 2 + vb * hb * 4 + M * 4,
+        f"owner (0, {j}): read all {M} token indices and the column's d_x rows that hit its {vb} table rows (at most "
+        f"{M} x {hb} bf16), write its fp32 block once")
+    ms = event_time_ms(lambda: opt.cross_entropy2d(logits, lab, loss, lse, stats, M, v, q, i, j, opt.BF16), reps)
+    put("cross_entropy2d", ms, rows * vb * 2, f"read the [{rows} x {vb}] bf16 logits block once (two kernels)")
+    ms = event_time_ms(lambda: opt.cross_entropy2d_bwd(logits, lab, lse, d_logits, 1.0 / M, M, v, q, i, j, opt.BF16), reps)
+    put("cross_entropy2d_bwd", ms, 2 * rows * vb * 2, "read logits, write d_logits")
+    ms = event_time_ms(lambda: opt.summa("abt", x, table, logits, M, h, v, q, i, j, opt.BF16), reps)
+    fl = 2 * rows * h * vb
+    out["lm_head_abt"] = {"us": round(ms * 1e3, 2), "block": [rows, h, vb], "tflops": round(fl / (ms * 1e-3) / 1e12, 1),
+                          "pct_peak": round(100 * fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 1)}
+    return out
+
+
 def pmc_probe(opt, torch, gemm, q, i, j):
     """A 256 MiB device copy (known traffic: 256 MiB read, 256 MiB written), then the given product, then the
     LayerNorm kernels at config-4 block size, each a few times; profiled with rocprofv3 --pmc FETCH_SIZE and, in a
@@ -393,6 +437,8 @@ def main():
                           "hardware": "64x Quadro RTX 5000, TACC Frontera (other machine: context, not a target)"},
     }
 
+    if not args.no_sweep:
+        out["model_ends"] = time_model_ends(opt, torch, b, s, h, q, di, dj, 32768, args.gemm_reps, 9)
     if not args.no_sweep and args.workload == "config2":
         out["stack"] = time_stack(opt, torch, harness, cfg, T, b, s, h, n, q, layers=4, reps=max(3, args.steps // 10))
     if not args.no_sweep and args.workload == "config2":

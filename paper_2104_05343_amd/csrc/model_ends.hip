@@ -3,10 +3,10 @@
 //     token indices of grid row i (every device of a row has them) and the table block (l, j) of every l is resident:
 //     out_ij[t] = table block (tok / (v/q), j), row tok % (v/q).  Pure copy: bit exact, HBM bound.
 //   * embedding gradient: d_table_lj = sum_i one_hot_il^T dX_ij, the A^T B form reduced within column j onto its owner
-//     (l, j).  Computed as the owner sees it: a workgroup owns 128 table rows x 256 columns of the block as an fp32
-//     accumulator in LDS, scans ALL token indices in order (the test "does this token fall into my rows" is uniform
-//     over the workgroup), adds the matching rows of dX and writes its piece once.  No atomics, fixed order (grid row,
-//     then position): deterministic, and rows that no token refers to are written as zeros.
+//     (l, j).  Computed as the owner sees it: a workgroup owns 32 table rows x 256 columns of the block as fp32
+//     accumulators in LDS, scans ALL token indices, adds the rows of dX whose token falls into its rows and writes
+//     its piece once.  No atomics, an order of additions fixed by the token order: deterministic, and rows that no
+//     token refers to are written as zeros.
 //   * cross entropy H = log(sum_i exp(x_i)) - x_label over a logits row that spans the q devices of a grid row: each
 //     device reduces its v/q columns to (max, sum exp(x - max)) -- the maximum is subtracted for range, which does
 //     not change the value --, the q partials are combined in the order l = 0..q-1 (the row all-reduce), and the
@@ -37,6 +37,26 @@ template <> __device__ __forceinline__ void stf<float>(float* p, float v) { *p =
 
 __device__ __forceinline__ int clamp_token(int t, int v) { return min(max(t, 0), v - 1); }
 
+// 16 bytes of a row as floats (8 bf16 or 4 fp32) and back
+template <typename T> struct V16;
+template <> struct V16<bf16_t> {
+  static constexpr int N = 8;
+  __device__ static void load(const bf16_t* p, float* f) {
+    const uint4 w = *(const uint4*)p;
+    const unsigned u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { f[2 * k] = __uint_as_float(u[k] << 16); f[2 * k + 1] = __uint_as_float(u[k] & 0xffff0000u); }
+  }
+  __device__ static void store(bf16_t* p, const float* f) {
+    *(uint4*)p = make_uint4(pack2_bf16(f[0], f[1]), pack2_bf16(f[2], f[3]), pack2_bf16(f[4], f[5]), pack2_bf16(f[6], f[7]));
+  }
+};
+template <> struct V16<float> {
+  static constexpr int N = 4;
+  __device__ static void load(const float* p, float* f) { const float4 w = *(const float4*)p; f[0] = w.x; f[1] = w.y; f[2] = w.z; f[3] = w.w; }
+  __device__ static void store(float* p, const float* f) { *(float4*)p = make_float4(f[0], f[1], f[2], f[3]); }
+};
+
 struct EndArgs {
   int rows;        // M/q: rows of a block
   int vb, hb;      // v/q, h/q
@@ -65,41 +85,100 @@ __global__ __launch_bounds__(256) void embedding_fwd_kernel(const int* __restric
   }
 }
 
-// ---- embedding backward (owner view): workgroup = EB_ROWS table rows x 256 columns of block (l, j) ----
-constexpr int EB_ROWS = 128, EB_COLS = 256, EB_CHUNK = 1024;
+// ---- embedding backward (owner view): workgroup = EB_ROWS table rows x EB_COLS columns of block (l, j) ----
+// Token indices are scanned in chunks; the positions of a chunk that fall into the workgroup's rows are compacted, in
+// order, into a list (ballot + prefix counts), which is cut into four consecutive quarters, one per wavefront.  A
+// wavefront adds its quarter's rows of dX into its OWN fp32 accumulator copy in LDS, a batch of loads in flight at a
+// time (a lane covers four adjacent columns); the four copies are added in wavefront order at the end.  The order of
+// all additions is a function of the token order alone, so the result is reproducible bit for bit.
+constexpr int EB_ROWS = 32, EB_COLS = 256, EB_CHUNK = 1024, EB_BATCH = 16;
 template <typename T>
 __global__ __launch_bounds__(256) void embedding_bwd_kernel(const int* __restrict__ tokens, const T* __restrict__ dX,
                                                             float* __restrict__ d_table, EndArgs a) {
-  __shared__ float acc[EB_ROWS * EB_COLS];
-  __shared__ int tk[EB_CHUNK];
-  const int tid = threadIdx.x;
+  __shared__ float acc[4][EB_ROWS * EB_COLS];   // one copy per wavefront
+  __shared__ int list[EB_CHUNK];                // (position in chunk) << 8 | row inside the workgroup's range
+  __shared__ int wave_count[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int dev = blockIdx.z;
   const int l = a.i0 + dev / a.nj, j = a.j0 + dev % a.nj;
   const int r0 = blockIdx.y * EB_ROWS;                  // first table row (inside block l) of this workgroup
   const int nr = min(EB_ROWS, a.vb - r0);
-  const int c = blockIdx.x * EB_COLS + tid;             // column inside the block
-  const bool col_ok = c < a.hb;
-  for (int k = tid; k < EB_ROWS * EB_COLS; k += 256) acc[k] = 0.f;
+  const int c0 = blockIdx.x * EB_COLS + 4 * lane;       // first of this lane's four columns inside the block
+  const bool vec4 = a.hb % 4 == 0 && c0 + 3 < a.hb;     // this lane's four columns exist and are 8/16-byte aligned
+  for (int k = tid; k < 4 * EB_ROWS * EB_COLS; k += 256) (&acc[0][0])[k] = 0.f;
   const int lo = l * a.vb + r0, hi = lo + nr;           // token indices that land in this workgroup's rows
-  const long long total = (long long)a.q * a.rows;      // all tokens, grid row after grid row
+  const long long total = (long long)a.q * a.rows;      // all tokens, grid row after grid row (below 2^31: host check)
   for (long long base = 0; base < total; base += EB_CHUNK) {
+    // this wavefront's quarter of the chunk: 4 rounds of 64 tokens, compacted in order
+    int mine[4], cnt = 0;
+    unsigned long long ball[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const long long t = base + wave * 256 + r * 64 + lane;
+      const int tok = t < total ? clamp_token(tokens[t], a.v) : -1;
+      const bool hit = tok >= lo && tok < hi;
+      mine[r] = hit ? (((wave * 256 + r * 64 + lane) << 8) | (tok - lo)) : -1;
+      ball[r] = __builtin_amdgcn_ballot_w64(hit);
+      cnt += __builtin_popcountll(ball[r]);
+    }
+    __syncthreads();                                    // the previous chunk's list has been consumed
+    if (lane == 0) wave_count[wave] = cnt;
     __syncthreads();
-    for (int k = tid; k < EB_CHUNK; k += 256) tk[k] = base + k < total ? clamp_token(tokens[base + k], a.v) : -1;
+    int off = 0, n = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      if (w < wave) off += wave_count[w];
+      n += wave_count[w];
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if (mine[r] >= 0) list[off + __builtin_popcountll(ball[r] & ((1ull << lane) - 1ull))] = mine[r];
+      off += __builtin_popcountll(ball[r]);
+    }
     __syncthreads();
-    const int n = (int)min((long long)EB_CHUNK, total - base);
-    for (int k = 0; k < n; ++k) {
-      const int tok = tk[k];
-      if (tok >= lo && tok < hi && col_ok) {            // uniform over the workgroup except for the column guard
-        const long long t = base + k;
-        const long long i = t / a.rows, rr = t % a.rows;
-        acc[(tok - lo) * EB_COLS + tid] += ldf<T>(dX + ((i * a.q + j) * a.rows + rr) * a.hb + c);
+    // quarter `wave` of the list, EB_BATCH rows of dX in flight.  The last batch is padded with its last entry at
+    // weight zero, so that the loop body has no branches between its loads.
+    const int q0 = (int)((long long)n * wave / 4), q1 = (int)((long long)n * (wave + 1) / 4);
+    float* my = acc[wave];
+    for (int m0 = q0; m0 < q1; m0 += EB_BATCH) {
+      float v[EB_BATCH][4];
+      int row[EB_BATCH];
+#pragma unroll
+      for (int u = 0; u < EB_BATCH; ++u) {
+        const int e = list[min(m0 + u, q1 - 1)];
+        const float wgt = m0 + u < q1 ? 1.0f : 0.0f;
+        row[u] = e & 255;
+        const unsigned t = (unsigned)base + (unsigned)(e >> 8);
+        const unsigned i = t / (unsigned)a.rows, rr = t - i * (unsigned)a.rows;
+        const T* src = dX + (((long long)i * a.q + j) * a.rows + rr) * a.hb + c0;
+        if (vec4) {
+          if (sizeof(T) == 2) {
+            const uint2 w = *(const uint2*)src;
+            v[u][0] = __uint_as_float(w.x << 16) * wgt; v[u][1] = __uint_as_float(w.x & 0xffff0000u) * wgt;
+            v[u][2] = __uint_as_float(w.y << 16) * wgt; v[u][3] = __uint_as_float(w.y & 0xffff0000u) * wgt;
+          } else {
+            const float4 w = *(const float4*)src;
+            v[u][0] = w.x * wgt; v[u][1] = w.y * wgt; v[u][2] = w.z * wgt; v[u][3] = w.w * wgt;
+          }
+        } else {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) v[u][k] = c0 + k < a.hb ? ldf<T>(src + k) * wgt : 0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < EB_BATCH; ++u) {
+        float4* p = (float4*)(my + row[u] * EB_COLS + 4 * lane);
+        float4 w = *p;
+        w.x += v[u][0]; w.y += v[u][1]; w.z += v[u][2]; w.w += v[u][3];
+        *p = w;
       }
     }
   }
   __syncthreads();
-  if (col_ok) {
-    float* dst = d_table + (((long long)l * a.q + j) * a.vb + r0) * a.hb + c;
-    for (int r = 0; r < nr; ++r) dst[(long long)r * a.hb] = acc[r * EB_COLS + tid];
+  for (int k = tid; k < nr * EB_COLS; k += 256) {
+    const int r = k / EB_COLS, c = blockIdx.x * EB_COLS + k % EB_COLS;
+    if (c < a.hb)
+      d_table[(((long long)l * a.q + j) * a.vb + r0 + r) * a.hb + c] = ((acc[0][k] + acc[1][k]) + acc[2][k]) + acc[3][k];
   }
 }
 
@@ -115,10 +194,26 @@ __global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ log
   const long long blk = (long long)i * a.q + j;
   const T* src = logits + (blk * a.rows + r) * a.vb;
   float m = -INFINITY, s = 0.f;
-  for (int c = lane; c < a.vb; c += 64) {
-    const float x = ldf<T>(src + c);
-    if (x > m) { s = s * __expf(m - x) + 1.0f; m = x; }   // exp(-inf - x) = 0 on the first element
-    else if (m > -INFINITY) s += __expf(x - m);               // (a row of -inf entries contributes nothing)
+  constexpr int VN = V16<T>::N;
+  if (a.vb % VN == 0) {   // 16-byte loads: a chunk's maximum first, then one rescale per chunk
+    for (int c = lane * VN; c < a.vb; c += 64 * VN) {
+      float f[VN];
+      V16<T>::load(src + c, f);
+      float cm = f[0];
+#pragma unroll
+      for (int k = 1; k < VN; ++k) cm = fmaxf(cm, f[k]);
+      if (cm > m) { s *= __expf(m - cm); m = cm; }            // exp(-inf - x) = 0 on the first chunk (s is 0 then)
+      if (m > -INFINITY) {
+#pragma unroll
+        for (int k = 0; k < VN; ++k) s += __expf(f[k] - m);
+      }
+    }
+  } else {
+    for (int c = lane; c < a.vb; c += 64) {
+      const float x = ldf<T>(src + c);
+      if (x > m) { s = s * __expf(m - x) + 1.0f; m = x; }
+      else if (m > -INFINITY) s += __expf(x - m);             // (a row of -inf entries contributes nothing)
+    }
   }
   const float mw = wave_max_f(m);
   s = wave_sum_f(m == -INFINITY ? 0.f : s * __expf(m - mw));
@@ -166,9 +261,20 @@ __global__ __launch_bounds__(256) void ce_bwd_kernel(const T* __restrict__ logit
   T* dst = d_logits + (blk * a.rows + r) * a.vb;
   const float L = lse[blk * a.rows + r];
   const int lab = clamp_token(labels[(long long)i * a.rows + r], a.v) - j * a.vb;   // label column inside this block, if any
-  for (int c = lane; c < a.vb; c += 64) {
-    const float qv = __expf(ldf<T>(src + c) - L);
-    stf<T>(dst + c, scale * (qv - (c == lab ? 1.0f : 0.0f)));
+  constexpr int VN = V16<T>::N;
+  if (a.vb % VN == 0) {
+    for (int c = lane * VN; c < a.vb; c += 64 * VN) {
+      float f[VN];
+      V16<T>::load(src + c, f);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) f[k] = scale * (__expf(f[k] - L) - (c + k == lab ? 1.0f : 0.0f));
+      V16<T>::store(dst + c, f);
+    }
+  } else {
+    for (int c = lane; c < a.vb; c += 64) {
+      const float qv = __expf(ldf<T>(src + c) - L);
+      stf<T>(dst + c, scale * (qv - (c == lab ? 1.0f : 0.0f)));
+    }
   }
 }
 
