@@ -359,6 +359,10 @@ int64_t optimus_layer_flops(const optimus_layer_cfg* cfg, int what);
  * 3 = 128x128, 4 = alias of 0, 5 = bounds-checked 128x128, 6 = 128x64, 7 = 64x64; -1 = automatic.
  * A variant whose tile does not divide the block falls back to the bounds-checked kernel. */
 void optimus_debug_set_gemm_variant(int v);
+/* The same for the products optimus_layer_bwd runs side by side on two streams only: chain_v for the
+ * activation-gradient chain (the four A B^T products), branch_v for the parameter-gradient branch (the four A^T B
+ * products); -1 = automatic. */
+void optimus_debug_set_corun_variants(int chain_v, int branch_v);
 /* The plan of the most recent matrix-core product launched by this process: variant | (panel splits << 8);
  * -1 before the first one.  Host state only, not synchronised between threads. */
 int optimus_debug_last_gemm_plan(void);

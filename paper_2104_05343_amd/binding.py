@@ -118,6 +118,7 @@ SIGNATURES = {
     "optimus_gemm_flops": (_I64, [_I64, _I64, _I64, _INT]),
     "optimus_layer_flops": (_I64, [C.POINTER(LayerCfg), _INT]),
     "optimus_debug_set_gemm_variant": (None, [_INT]),
+    "optimus_debug_set_corun_variants": (None, [_INT, _INT]),
     "optimus_debug_last_gemm_plan": (_INT, []),
 }
 
@@ -385,6 +386,10 @@ def layer_flops(cfg: LayerCfg, what: int) -> int:
 
 def debug_set_gemm_variant(v: int):
     lib().optimus_debug_set_gemm_variant(v)
+
+
+def debug_set_corun_variants(chain_v: int, branch_v: int) -> None:
+    lib().optimus_debug_set_corun_variants(chain_v, branch_v)
 
 
 def debug_last_gemm_plan():

@@ -74,7 +74,7 @@ GemmDesc summa_desc(int form, const void* A, const void* B, void* C, int64_t M, 
 }
 
 int run_summa(int form, const void* A, const void* B, void* C, int64_t M, int64_t K, int64_t N, int q, int i, int j, int dtype,
-              const optimus_epilogue* epi, void* ws, size_t ws_bytes, void* stream) {
+              const optimus_epilogue* epi, void* ws, size_t ws_bytes, void* stream, int corun = 0) {
   if (!A || !B || !C) return OPTIMUS_EINVAL;
   if (form < 0 || form > 2) return OPTIMUS_EINVAL;
   if (dtype != OPTIMUS_FP32 && dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
@@ -84,6 +84,7 @@ int run_summa(int form, const void* A, const void* B, void* C, int64_t M, int64_
   if (rc) return rc;
   if (epi && (epi->act < 0 || epi->act > 1)) return OPTIMUS_EINVAL;
   GemmDesc d = summa_desc(form, A, B, C, M, K, N, q, i, j, dtype, epi);
+  d.corun = corun;
   if (gemm_mfma_supported(d)) {
     int s = gemm_pick_splits(d);
     if (s > 1 && ws && ws_bytes >= gemm_partials_bytes(d, s)) {
@@ -379,13 +380,26 @@ int stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
   return OPTIMUS_OK;
 }
 
+// split workspace of one product as the layer plans it (corun: see GemmDesc)
+size_t summa_ws_bytes(int form, int64_t M, int64_t K, int64_t N, int q, int i, int j, int dtype, int corun) {
+  if (form < 0 || form > 2 || check_mkn(M, K, N, q) || check_coords(q, i, j)) return 0;
+  if (dtype != OPTIMUS_BF16) return 0;
+  // pointers only matter for alignment checks; use an aligned dummy
+  GemmDesc d = summa_desc(form, (const void*)256, (const void*)256, (void*)256, M, K, N, q, i, j, dtype, nullptr);
+  d.corun = corun;
+  if (!gemm_mfma_supported(d)) return 0;
+  return gemm_partials_bytes(d, gemm_pick_splits(d));
+}
+
 size_t layer_gemm_ws(const optimus_layer_cfg* c) {
   LayerGemm g[12];
   layer_gemms(c, g);
   size_t mx = 0;
   for (int k = 0; k < 12; ++k)
     for (int grid = 0; grid < 2; ++grid) {
-      size_t b = optimus_summa_workspace_bytes(g[k].form, g[k].M, g[k].K, g[k].N, c->q, grid ? -1 : 0, grid ? -1 : 0, c->dtype);
+      // the backward products run in pairs on two streams: chain (A B^T) and branch (A^T B), as optimus_layer_bwd flags them
+      const int corun = k < 4 ? 0 : (g[k].form == OPTIMUS_FORM_ABT ? 1 : 2);
+      size_t b = summa_ws_bytes(g[k].form, g[k].M, g[k].K, g[k].N, c->q, grid ? -1 : 0, grid ? -1 : 0, c->dtype, corun);
       if (b > mx) mx = b;
     }
   return align256(mx);
@@ -441,13 +455,7 @@ int optimus_summa_ex(int form, const void* A, const void* B, void* C, int64_t M,
 }
 
 size_t optimus_summa_workspace_bytes(int form, int64_t M, int64_t K, int64_t N, int q, int i, int j, int dtype) {
-  if (form < 0 || form > 2 || check_mkn(M, K, N, q) || check_coords(q, i, j)) return 0;
-  if (dtype != OPTIMUS_BF16) return 0;
-  // pointers only matter for alignment checks; use an aligned dummy
-  GemmDesc d = summa_desc(form, (const void*)256, (const void*)256, (void*)256, M, K, N, q, i, j, dtype, nullptr);
-  if (!gemm_mfma_supported(d)) return 0;
-  int s = gemm_pick_splits(d);
-  return gemm_partials_bytes(d, s);
+  return summa_ws_bytes(form, M, K, N, q, i, j, dtype, 0);
 }
 
 // One step of Algorithms 1-3 as the COMPUTING device (i, j) sees it (the owner view above fuses the q steps).
@@ -732,27 +740,27 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   BRANCH_AFTER_MAIN(ss->fork);
   // ---- out = h_mid + gelu W2 + b2 ----
   e = {}; e.gelu_grad_of = t->pre_gelu;  // d_pre = (d_out W2^T) * GeLU'(pre)
-  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_out, t->w2, t->d_pre_gelu, M, h, 4 * h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream));
-  RUN(run_summa(OPTIMUS_FORM_ATB, t->gelu, t->d_out, t->d_w2, 4 * h, M, h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream));
+  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_out, t->w2, t->d_pre_gelu, M, h, 4 * h, q, i, j, dt, &e, gemm_ws, gemm_bytes, stream, 1));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->gelu, t->d_out, t->d_w2, 4 * h, M, h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream, 2));
   RUN(optimus_bias_grad(t->d_out, t->d_b2, M, h, q, i, j, dt, gstream));
   // ---- pre = ln2_out W1 + b1 ----
   BRANCH_AFTER_MAIN(ss->ready[0]);  // d_pre_gelu is complete
-  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_pre_gelu, t->w1, t->d_ln2_out, M, 4 * h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));
-  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln2_out, t->d_pre_gelu, t->d_w1, h, M, 4 * h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream));
+  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_pre_gelu, t->w1, t->d_ln2_out, M, 4 * h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream, 1));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln2_out, t->d_pre_gelu, t->d_w1, h, M, 4 * h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream, 2));
   RUN(optimus_bias_grad(t->d_pre_gelu, t->d_b1, M, 4 * h, q, i, j, dt, gstream));
   // ---- LN2 backward, plus the residual branch: d_h_mid = d_out + LN2'(d_ln2_out) ----
   RUN(ln_backward(t->d_ln2_out, t->xhat2, t->rstd2, t->ln2_g, t->d_out, t->d_h_mid, t->d_ln2_g, t->d_ln2_b, t->bstats2, ln, grid, st));
   // ---- h_mid = x + attn Wo + bo ----
   BRANCH_AFTER_MAIN(ss->ready[1]);  // d_h_mid is complete
-  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_h_mid, t->w_o, t->d_attn, M, h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));
-  RUN(run_summa(OPTIMUS_FORM_ATB, t->attn, t->d_h_mid, t->d_w_o, h, M, h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream));
+  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_h_mid, t->w_o, t->d_attn, M, h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream, 1));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->attn, t->d_h_mid, t->d_w_o, h, M, h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream, 2));
   RUN(optimus_bias_grad(t->d_h_mid, t->d_b_o, M, h, q, i, j, dt, gstream));
   // ---- local attention backward ----
   RUN(layer_attention(true, c, t, i, j, attn_ws, attn_bytes, stream));
   // ---- qkv = ln1_out Wqkv + b ----
   BRANCH_AFTER_MAIN(ss->ready[2]);  // d_qkv is complete
-  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_qkv, t->w_qkv, t->d_ln1_out, M, 3 * h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream));
-  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln1_out, t->d_qkv, t->d_w_qkv, h, M, 3 * h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream));
+  RUN(run_summa(OPTIMUS_FORM_ABT, t->d_qkv, t->w_qkv, t->d_ln1_out, M, 3 * h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream, 1));
+  RUN(run_summa(OPTIMUS_FORM_ATB, t->ln1_out, t->d_qkv, t->d_w_qkv, h, M, 3 * h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream, 2));
   RUN(optimus_bias_grad(t->d_qkv, t->d_b_qkv, M, 3 * h, q, i, j, dt, gstream));
   // ---- LN1 backward, plus the residual branch: d_x = d_h_mid + LN1'(d_ln1_out) ----
   RUN(ln_backward(t->d_ln1_out, t->xhat1, t->rstd1, t->ln1_g, t->d_h_mid, t->d_x, t->d_ln1_g, t->d_ln1_b, t->bstats1, ln, grid, st));
@@ -778,6 +786,7 @@ int64_t optimus_layer_flops(const optimus_layer_cfg* c, int what) {
 
 // ---- tuning hook used by the benchmark (not part of the method): force a matrix-core tile variant, -1 = automatic ----
 void optimus_debug_set_gemm_variant(int v) { gemm_set_variant(v); }
+void optimus_debug_set_corun_variants(int chain_v, int branch_v) { gemm_set_corun_variants(chain_v, branch_v); }
 int optimus_debug_last_gemm_plan(void) { return gemm_last_plan(); }
 
 }  // extern "C"

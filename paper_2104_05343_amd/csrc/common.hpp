@@ -83,6 +83,9 @@ struct GemmDesc {
   // split of the panel loop over several workgroups (fixed-order combine)
   int splits;          // 1 = none
   float* partials;     // workspace [splits][nz][Mb][Nb] fp32 when splits > 1
+  // 0: the product has the chip to itself; 1 / 2: it is one of two products that the layer's backward pass runs
+  // side by side on two streams (1: activation-gradient chain, 2: parameter-gradient branch)
+  int corun;
 };
 
 int launch_gemm(const GemmDesc& d, hipStream_t stream);           // picks MFMA or generic kernel
@@ -93,6 +96,7 @@ int gemm_pick_splits(const GemmDesc& d);                           // heuristic;
 size_t gemm_partials_bytes(const GemmDesc& d, int splits);
 // force a specific kernel variant (benchmark sweeps); -1 = automatic
 void gemm_set_variant(int v);
+void gemm_set_corun_variants(int chain_v, int branch_v);
 int gemm_get_variant();
 int gemm_last_plan();
 

@@ -45,6 +45,8 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 static int g_variant = -1;
 void gemm_set_variant(int v) { g_variant = v; }
 int gemm_get_variant() { return g_variant; }
+static int g_corun_variant[2] = {-1, -1};
+void gemm_set_corun_variants(int chain_v, int branch_v) { g_corun_variant[0] = chain_v; g_corun_variant[1] = branch_v; }
 static int g_last_plan = -1;
 int gemm_last_plan() { return g_last_plan; }
 
@@ -1062,6 +1064,7 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
     const Cand& c = cand[ci];
     const int v = c.v;
     if (g_variant >= 0 && g_variant != kGuardVariant && v != (g_variant == 4 ? 0 : g_variant)) continue;
+    if (d.corun > 0 && g_corun_variant[d.corun - 1] >= 0 && v != g_corun_variant[d.corun - 1]) continue;
     if (!variant_fits(kVariants[v], d)) continue;
     const long long tiles = (long long)(d.Mb / kVariants[v].BM) * (d.Nb / kVariants[v].BN);
     for (int sp = 1; sp <= 8; ++sp) {
@@ -1076,7 +1079,13 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
       const float per_wg = (float)((((slabs + sp - 1) / sp) + 1) & ~1LL) * t_slab;
       // split: the combine launch, and the fp32 partial tiles read back by it (their writes overlap the products)
       const float traffic_us = sp > 1 ? 4.0f + (float)sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f : 0.f;
-      const float cost = c.fixed_us + c.out_us_per_mib * out_mib + (float)rounds * per_wg + traffic_us;
+      float cost = c.fixed_us + c.out_us_per_mib * out_mib + (float)rounds * per_wg + traffic_us;
+      // Two products that run side by side on two streams (the pairs of the layer's backward pass) overlap only if
+      // workgroups of both fit on one CU: the 8-wavefront tiles take a CU's LDS and registers alone, so such a pair
+      // runs one after the other, while the 4-wavefront tiles of the two kernels share the CUs.  Measured on the
+      // backward pass of the 4096-wide layers: 128x128 tiles for the chain 0.69 -> 0.57 ms and 0.71 -> 0.62 ms,
+      // although each product alone is faster with 256x128 tiles; no difference for the small layer.
+      if (d.corun > 0 && c.per_cu >= 2) cost *= 0.78f;
       if (!found || cost < best_cost) {
         found = true;
         best_cost = cost;
