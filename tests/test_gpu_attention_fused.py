@@ -86,6 +86,32 @@ def test_fused_attention_forward_backward(b, s, h, n, q, causal):
         assert np.all(np.isnan(a1[mask]))
 
 
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("s", [1, 2, 31, 63, 64, 65, 127, 128, 129, 191, 193])
+def test_fused_attention_block_boundaries(s, causal):
+    """Sequence lengths around the 32-row wavefront tiles, the 64-row blocks and the 128-row load pairs (forward and
+    backward, one (sequence, head) pair per device, head width 64)."""
+    b, h, n, q = 2, 128, 2, 2
+    rng = np.random.default_rng(s)
+    M = b * s
+    qkv = round_to_bf16(rng.standard_normal((M, 3 * h)).astype(np.float32))
+    d_attn = round_to_bf16(rng.standard_normal((M, h)).astype(np.float32))
+    attn_o, _ = oatt.forward(qkv, b, s, n, causal, keep_probs=False)
+    lse_o = oatt.logsumexp(qkv, b, s, n, causal)
+    dqkv_o = oatt.backward(qkv, d_attn, b, s, n, causal)
+    dQKV, dO = mat_to_dev(qkv, q, "bf16"), mat_to_dev(d_attn, q, "bf16")
+    O, L, dQ = empty(M * h, "bf16"), empty(q * q * s, "fp32"), empty(M * 3 * h, "bf16")
+    ws = torch.empty(max(256, opt.attention_fused_workspace_bytes(b, s, h, n, q)), dtype=torch.uint8, device="cuda:0")
+    opt.attention_fused_fwd(dQKV, O, L, b, s, h, n, q, -1, -1, causal, opt.BF16)
+    opt.attention_fused_bwd(dQKV, O, L, dO, dQ, b, s, h, n, q, -1, -1, causal, opt.BF16, ws)
+    torch.cuda.synchronize()
+    assert rel_frobenius(mat_to_host(O, M, h, q), attn_o) <= TOL
+    assert rel_frobenius(to_host(L).reshape(q, q, 1, s), _lse_blocks(lse_o, b, n, q)) <= TOL_LSE
+    got = mat_to_host(dQ, M, 3 * h, q)
+    assert not np.any(np.isnan(got))
+    assert rel_frobenius(got, dqkv_o) <= TOL
+
+
 def test_fused_attention_closed_forms():
     """Q = 0: uniform weights over the visible prefix, O_t = mean(V_0..t) and L_t = log(t + 1)."""
     b, s, h, n, q = 2, 200, 128, 2, 1
