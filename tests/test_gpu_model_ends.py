@@ -187,6 +187,59 @@ def test_lm_head_and_whole_tail_against_oracle():
     assert rel_frobenius(mat_to_host(d_table_emb, v, h, q), me.embedding_grad(tokens, dh, v)) <= TOL_F32
 
 
+def test_model_ends_at_benchmark_size():
+    """The sizes bench.py times (config-2 layer, v = 32768, q = 4), device mode after a grid pass: embedding exact,
+    table gradient of one owner block in full, cross entropy and its gradient on sampled rows (the operations are
+    row-wise, so the oracle recomputes exactly those rows)."""
+    b, s, h, q, v = 8, 512, 1024, 4, 32768
+    M, rows, vb, hb = b * s, b * s // q, v // q, h // q
+    rng = np.random.default_rng(2)
+    tokens, labels = token_inputs(9, b, s, v)
+    dTok, dLab = _ints(tokens), _ints(labels)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(1)
+    table = (torch.randn(v * h, generator=gen, device="cuda:0") * 0.02).to(torch.bfloat16)     # block-major [v x h]
+    d_x = torch.randn(M * h, generator=gen, device="cuda:0").to(torch.bfloat16)
+    logits = (torch.randn(M * v, generator=gen, device="cuda:0") * 2.0).to(torch.bfloat16)
+    i, j = 1, 2
+    # embedding forward, device (i, j): rows of table block (tok / vb, j)
+    X = empty(M * h, "bf16")
+    opt.embedding_fwd(dTok, table, X, M, v, h, q, i, j, opt.BF16)
+    torch.cuda.synchronize()
+    tb = to_host(table).reshape(q, q, vb, hb)
+    got = to_host(X).reshape(q, q, rows, hb)[i, j]
+    tok_i = tokens[i * rows:(i + 1) * rows]
+    assert np.array_equal(got, tb[tok_i // vb, j, tok_i % vb])
+    # table gradient, owner (0, j): the block with the frequent indices
+    G = empty(v * h, "fp32")
+    opt.embedding_bwd(dTok, d_x, G, M, v, h, q, 0, j, opt.BF16)
+    torch.cuda.synchronize()
+    dxb = to_host(d_x).reshape(q, q, rows, hb)[:, j].reshape(M, hb).astype(np.float64)       # column block j of d_x, all rows
+    want = np.zeros((vb, hb))
+    sel = tokens < vb
+    np.add.at(want, tokens[sel], dxb[sel])
+    assert rel_frobenius(to_host(G).reshape(q, q, vb, hb)[0, j], want) <= TOL_F32
+    # cross entropy: grid pass for the partial statistics, then device (i, j)
+    loss, lse, stats = empty(q * q * rows, "fp32"), empty(q * q * rows, "fp32"), empty(q * q * rows * 2, "fp32")
+    opt.cross_entropy2d(logits, dLab, loss, lse, stats, M, v, q, -1, -1, opt.BF16)
+    loss1, lse1 = empty(q * q * rows, "fp32"), empty(q * q * rows, "fp32")
+    dlog = empty(M * v, "bf16")
+    opt.cross_entropy2d(logits, dLab, loss1, lse1, stats, M, v, q, i, j, opt.BF16)
+    opt.cross_entropy2d_bwd(logits, dLab, lse1, dlog, 1.0 / M, M, v, q, i, j, opt.BF16)
+    torch.cuda.synchronize()
+    sample = np.sort(rng.choice(rows, 48, replace=False))
+    lg = logits.view(q, q, rows, vb)[i][:, torch.as_tensor(sample, device="cuda:0")]            # [q, n, vb]
+    x_rows = np.concatenate([to_host(lg[l].reshape(-1)).reshape(len(sample), vb) for l in range(q)], axis=1)   # [n, v]
+    lab_rows = labels[i * rows + sample]
+    loss_o, lse_o = me.cross_entropy(x_rows, lab_rows)
+    sl = (i * q + j) * rows + sample
+    assert rel_frobenius(to_host(loss1)[sl], loss_o) <= TOL_F32 and rel_frobenius(to_host(lse1)[sl], lse_o) <= TOL_F32
+    assert np.array_equal(to_host(loss1)[sl], to_host(loss)[sl])                                  # device mode = grid mode
+    g_o = me.cross_entropy_grad(x_rows, lab_rows, 1.0 / M)[:, j * vb:(j + 1) * vb]
+    g_dev = to_host(dlog.view(q, q, rows, vb)[i, j][torch.as_tensor(sample, device="cuda:0")].reshape(-1)).reshape(len(sample), vb)
+    assert rel_frobenius(g_dev, g_o) <= TOL["bf16"]
+
+
 def test_model_end_errors():
     one = empty(64, "bf16")
     f = empty(64, "fp32")
