@@ -112,6 +112,51 @@ def test_fused_attention_block_boundaries(s, causal):
     assert rel_frobenius(got, dqkv_o) <= TOL
 
 
+@pytest.mark.parametrize("b,s,h,n,q,dev", [(8, 1024, 4096, 32, 4, (1, 2)), (64, 512, 4096, 32, 8, (6, 3)), (8, 512, 1024, 16, 4, (3, 1))],
+                         ids=["config4", "config5", "config2"])
+def test_fused_attention_at_benchmark_sizes(b, s, h, n, q, dev):
+    """Configs 4, 5 and 2 at full size, device mode as bench.py launches it: sampled (sequence, head) pairs of the
+    device recomputed by the oracle from the device's own inputs; device mode = grid mode bit for bit."""
+    d = h // n
+    M, nb, nh = b * s, b // q, n // q
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(s + q)
+    qkv = (torch.randn(M * 3 * h, generator=gen, device="cuda:0") * 0.7).to(torch.bfloat16)      # block-major
+    d_attn = torch.randn(M * h, generator=gen, device="cuda:0").to(torch.bfloat16)
+    nmat = nb * nh
+    i, j = dev
+    O, L, dQ = empty(M * h, "bf16"), empty(q * q * nmat * s, "fp32"), empty(M * 3 * h, "bf16")
+    ws = torch.empty(opt.attention_fused_workspace_bytes(b, s, h, n, q), dtype=torch.uint8, device="cuda:0")
+    opt.attention_fused_fwd(qkv, O, L, b, s, h, n, q, i, j, True, opt.BF16)
+    opt.attention_fused_bwd(qkv, O, L, d_attn, dQ, b, s, h, n, q, i, j, True, opt.BF16, ws)
+    torch.cuda.synchronize()
+    dev_id = i * q + j
+    qb = qkv.view(q * q, nb * s, 3 * h // q)[dev_id]
+    ob, gb, dqb = (t.view(q * q, nb * s, -1)[dev_id] for t in (O, d_attn, dQ))
+    lb = L.view(q * q, nmat, s)[dev_id]
+    rng = np.random.default_rng(0)
+    for _ in range(3):
+        seq, head = int(rng.integers(nb)), int(rng.integers(nh))
+        rows = slice(seq * s, (seq + 1) * s)
+        blk = to_host(qb[rows, head * 3 * d:(head + 1) * 3 * d].reshape(-1)).reshape(s, 3 * d).astype(np.float64)
+        Qh, Kh, Vh = blk[:, :d], blk[:, d:2 * d], blk[:, 2 * d:]
+        O_o, P_o = oatt.head_forward(Qh, Kh, Vh, True)
+        assert rel_frobenius(to_host(ob[rows, head * d:(head + 1) * d].reshape(-1)).reshape(s, d), O_o) <= TOL
+        assert rel_frobenius(to_host(lb[seq * nh + head]), oatt.head_logsumexp(Qh, Kh, True)) <= TOL_LSE
+        dO = to_host(gb[rows, head * d:(head + 1) * d].reshape(-1)).reshape(s, d).astype(np.float64)
+        want = np.concatenate(oatt.head_backward(Qh, Kh, Vh, P_o, dO), axis=1)
+        got = to_host(dqb[rows, head * 3 * d:(head + 1) * 3 * d].reshape(-1)).reshape(s, 3 * d)
+        assert rel_frobenius(got, want) <= TOL
+    # grid mode writes the same bits into this device's blocks
+    O2, L2, dQ2 = empty(M * h, "bf16"), empty(q * q * nmat * s, "fp32"), empty(M * 3 * h, "bf16")
+    opt.attention_fused_fwd(qkv, O2, L2, b, s, h, n, q, -1, -1, True, opt.BF16)
+    opt.attention_fused_bwd(qkv, O2, L2, d_attn, dQ2, b, s, h, n, q, -1, -1, True, opt.BF16, ws)
+    torch.cuda.synchronize()
+    for a_, b_ in ((O, O2), (dQ, dQ2)):
+        assert torch.equal(a_.view(q * q, -1)[dev_id].view(torch.int16), b_.view(q * q, -1)[dev_id].view(torch.int16))
+    assert torch.equal(L.view(q * q, -1)[dev_id].view(torch.int32), L2.view(q * q, -1)[dev_id].view(torch.int32))
+
+
 def test_fused_attention_closed_forms():
     """Q = 0: uniform weights over the visible prefix, O_t = mean(V_0..t) and L_t = log(t + 1)."""
     b, s, h, n, q = 2, 200, 128, 2, 1
