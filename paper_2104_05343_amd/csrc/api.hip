@@ -625,7 +625,8 @@ int optimus_cross_entropy2d(const void* logits, const int32_t* labels, float* lo
   EndDesc d;
   int rc = end_desc(M, v, q, q, i, j, dtype, &d);
   if (rc) return rc;
-  if ((rc = launch_ce_stats(logits, stats, d, as_stream(stream)))) return rc;   // own partial (all partials in grid mode)
+  if (!is_grid(i, j)) return launch_ce_stats_final(logits, labels, stats, loss, lse, d, as_stream(stream));  // peers resident
+  if ((rc = launch_ce_stats(logits, stats, d, as_stream(stream)))) return rc;   // every device's partial first
   return launch_ce_finalize(logits, labels, stats, loss, lse, d, as_stream(stream));
 }
 int optimus_cross_entropy2d_bwd(const void* logits, const int32_t* labels, const float* lse, void* d_logits, float scale, int64_t M,

@@ -156,6 +156,8 @@ struct EndDesc {
 int launch_embedding_fwd(const int* tokens, const void* table, void* out, const EndDesc& d, hipStream_t stream);
 int launch_embedding_bwd(const int* tokens, const void* dX, float* d_table, const EndDesc& d, hipStream_t stream);
 int launch_ce_stats(const void* logits, float* stats, const EndDesc& d, hipStream_t stream);
+int launch_ce_stats_final(const void* logits, const int* labels, float* stats, float* loss, float* lse, const EndDesc& d,
+                          hipStream_t stream);
 int launch_ce_finalize(const void* logits, const int* labels, const float* stats, float* loss, float* lse, const EndDesc& d,
                        hipStream_t stream);
 int launch_ce_bwd(const void* logits, const int* labels, const float* lse, void* d_logits, float scale, const EndDesc& d,

@@ -183,9 +183,34 @@ __global__ __launch_bounds__(256) void embedding_bwd_kernel(const int* __restric
 }
 
 // ---- cross entropy ----
-// partial statistics of one block: (max, sum exp(x - max)) per row; one wavefront per row
+// Loss and log-sum-exp of row r of device (i, j) from the q partials of grid row i, combined in the order l = 0..q-1.
+// own_l >= 0: that partial is taken from (own_m, own_s) instead of memory (same values: it has just been computed).
 template <typename T>
-__global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ logits, float* __restrict__ stats, EndArgs a) {
+__device__ __forceinline__ void ce_combine(const T* __restrict__ logits, const int* __restrict__ labels, const float* __restrict__ stats,
+                                           float* __restrict__ loss, float* __restrict__ lse, const EndArgs& a, int i, int j,
+                                           long long r, int own_l, float own_m, float own_s) {
+  float m = -INFINITY;
+  for (int l = 0; l < a.q; ++l) m = fmaxf(m, l == own_l ? own_m : stats[(((long long)i * a.q + l) * a.rows + r) * 2]);
+  float s = 0.f;
+  for (int l = 0; l < a.q; ++l) {
+    const float* p = stats + (((long long)i * a.q + l) * a.rows + r) * 2;
+    const float ml = l == own_l ? own_m : p[0], sl = l == own_l ? own_s : p[1];
+    s += sl * __expf(ml - m);
+  }
+  const float L = m + __logf(s);
+  const int lab = clamp_token(labels[(long long)i * a.rows + r], a.v);
+  const float xl = ldf<T>(logits + ((((long long)i * a.q + lab / a.vb) * a.rows + r) * a.vb + lab % a.vb));
+  const long long o = ((long long)i * a.q + j) * a.rows + r;
+  lse[o] = L;
+  loss[o] = L - xl;
+}
+
+// partial statistics of one block: (max, sum exp(x - max)) per row; one wavefront per row.  FINAL: the peers'
+// partials are already in memory (one device recomputed from resident peers), so the row is finished here.
+template <typename T, bool FINAL>
+__global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ logits, float* __restrict__ stats,
+                                                       const int* __restrict__ labels, float* __restrict__ loss,
+                                                       float* __restrict__ lse, EndArgs a) {
   const int lane = threadIdx.x & 63;
   const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= a.rows) return;
@@ -220,6 +245,7 @@ __global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ log
   if (lane == 0) {
     stats[(blk * a.rows + r) * 2] = mw;
     stats[(blk * a.rows + r) * 2 + 1] = s;
+    if (FINAL) ce_combine<T>(logits, labels, stats, loss, lse, a, i, j, r, j, mw, s);
   }
 }
 
@@ -232,19 +258,7 @@ __global__ __launch_bounds__(256) void ce_finalize_kernel(const T* __restrict__ 
   if (r >= a.rows) return;
   const int dev = blockIdx.y;
   const int i = a.i0 + dev / a.nj, j = a.j0 + dev % a.nj;
-  float m = -INFINITY;
-  for (int l = 0; l < a.q; ++l) m = fmaxf(m, stats[(((long long)i * a.q + l) * a.rows + r) * 2]);
-  float s = 0.f;
-  for (int l = 0; l < a.q; ++l) {
-    const float* p = stats + (((long long)i * a.q + l) * a.rows + r) * 2;
-    s += p[1] * __expf(p[0] - m);
-  }
-  const float L = m + __logf(s);
-  const int lab = clamp_token(labels[(long long)i * a.rows + r], a.v);
-  const float xl = ldf<T>(logits + ((((long long)i * a.q + lab / a.vb) * a.rows + r) * a.vb + lab % a.vb));
-  const long long o = ((long long)i * a.q + j) * a.rows + r;
-  lse[o] = L;
-  loss[o] = L - xl;
+  ce_combine<T>(logits, labels, stats, loss, lse, a, i, j, r, -1, 0.f, 0.f);
 }
 
 // d_logits = scale * (exp(x - L) - [column == label]); one wavefront per row of a block
@@ -298,8 +312,17 @@ int launch_embedding_bwd(const int* tokens, const void* dX, float* d_table, cons
 int launch_ce_stats(const void* logits, float* stats, const EndDesc& d, hipStream_t st) {
   EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
   const dim3 grid((d.rows + 3) / 4, d.ni * d.nj);
-  if (d.dtype == OPTIMUS_BF16) ce_stats_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)logits, stats, a);
-  else ce_stats_kernel<float><<<grid, 256, 0, st>>>((const float*)logits, stats, a);
+  if (d.dtype == OPTIMUS_BF16) ce_stats_kernel<bf16_t, false><<<grid, 256, 0, st>>>((const bf16_t*)logits, stats, nullptr, nullptr, nullptr, a);
+  else ce_stats_kernel<float, false><<<grid, 256, 0, st>>>((const float*)logits, stats, nullptr, nullptr, nullptr, a);
+  return hip_launch_status();
+}
+// one device whose peers' partials are resident: statistics and finish in one launch
+int launch_ce_stats_final(const void* logits, const int* labels, float* stats, float* loss, float* lse, const EndDesc& d,
+                          hipStream_t st) {
+  EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
+  const dim3 grid((d.rows + 3) / 4, d.ni * d.nj);
+  if (d.dtype == OPTIMUS_BF16) ce_stats_kernel<bf16_t, true><<<grid, 256, 0, st>>>((const bf16_t*)logits, stats, labels, loss, lse, a);
+  else ce_stats_kernel<float, true><<<grid, 256, 0, st>>>((const float*)logits, stats, labels, loss, lse, a);
   return hip_launch_status();
 }
 int launch_ce_finalize(const void* logits, const int* labels, const float* stats, float* loss, float* lse, const EndDesc& d,
