@@ -207,13 +207,17 @@ __device__ __forceinline__ void ce_combine(const T* __restrict__ logits, const i
 
 // partial statistics of one block: (max, sum exp(x - max)) per row; one wavefront per row.  FINAL: the peers'
 // partials are already in memory (one device recomputed from resident peers), so the row is finished here.
-template <typename T, bool FINAL>
+// WIDE: a whole workgroup per row (its four wavefronts take interleaved 16-byte chunks and their partials are
+// combined in wavefront order through LDS): long rows need more loads in flight than one wavefront per SIMD gives.
+template <typename T, bool FINAL, bool WIDE>
 __global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ logits, float* __restrict__ stats,
                                                        const int* __restrict__ labels, float* __restrict__ loss,
                                                        float* __restrict__ lse, EndArgs a) {
-  const int lane = threadIdx.x & 63;
-  const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= a.rows) return;
+  __shared__ float part[8];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long r = WIDE ? (long long)blockIdx.x : (long long)blockIdx.x * 4 + wave;
+  if (r >= a.rows) return;   // (WIDE: the same for the whole workgroup)
+  const int first = WIDE ? wave * 64 + lane : lane, step = WIDE ? 256 : 64;
   const int dev = blockIdx.y;
   const int i = a.i0 + dev / a.nj, j = a.j0 + dev % a.nj;
   const long long blk = (long long)i * a.q + j;
@@ -221,7 +225,7 @@ __global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ log
   float m = -INFINITY, s = 0.f;
   constexpr int VN = V16<T>::N;
   if (a.vb % VN == 0) {   // 16-byte loads: a chunk's maximum first, then one rescale per chunk
-    for (int c = lane * VN; c < a.vb; c += 64 * VN) {
+    for (int c = first * VN; c < a.vb; c += step * VN) {
       float f[VN];
       V16<T>::load(src + c, f);
       float cm = f[0];
@@ -234,14 +238,22 @@ __global__ __launch_bounds__(256) void ce_stats_kernel(const T* __restrict__ log
       }
     }
   } else {
-    for (int c = lane; c < a.vb; c += 64) {
+    for (int c = first; c < a.vb; c += step) {
       const float x = ldf<T>(src + c);
       if (x > m) { s = s * __expf(m - x) + 1.0f; m = x; }
       else if (m > -INFINITY) s += __expf(x - m);             // (a row of -inf entries contributes nothing)
     }
   }
-  const float mw = wave_max_f(m);
+  float mw = wave_max_f(m);
   s = wave_sum_f(m == -INFINITY ? 0.f : s * __expf(m - mw));
+  if (WIDE) {
+    if (lane == 0) { part[wave] = mw; part[4 + wave] = s; }
+    __syncthreads();
+    if (wave != 0) return;
+    mw = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+    s = 0.f;
+    for (int w = 0; w < 4; ++w) s += part[w] == -INFINITY ? 0.f : part[4 + w] * __expf(part[w] - mw);
+  }
   if (lane == 0) {
     stats[(blk * a.rows + r) * 2] = mw;
     stats[(blk * a.rows + r) * 2 + 1] = s;
@@ -294,6 +306,23 @@ __global__ __launch_bounds__(256) void ce_bwd_kernel(const T* __restrict__ logit
 
 }  // namespace
 
+namespace {
+template <bool FINAL>
+int ce_stats_dispatch(const void* logits, float* stats, const int* labels, float* loss, float* lse, const EndDesc& d,
+                      const EndArgs& a, hipStream_t st) {
+  const bool wide = d.vb >= 2048;   // a workgroup per row from 2048 columns per block on
+  const dim3 grid(wide ? d.rows : (d.rows + 3) / 4, d.ni * d.nj);
+  if (d.dtype == OPTIMUS_BF16) {
+    if (wide) ce_stats_kernel<bf16_t, FINAL, true><<<grid, 256, 0, st>>>((const bf16_t*)logits, stats, labels, loss, lse, a);
+    else ce_stats_kernel<bf16_t, FINAL, false><<<grid, 256, 0, st>>>((const bf16_t*)logits, stats, labels, loss, lse, a);
+  } else {
+    if (wide) ce_stats_kernel<float, FINAL, true><<<grid, 256, 0, st>>>((const float*)logits, stats, labels, loss, lse, a);
+    else ce_stats_kernel<float, FINAL, false><<<grid, 256, 0, st>>>((const float*)logits, stats, labels, loss, lse, a);
+  }
+  return hip_launch_status();
+}
+}  // namespace
+
 int launch_embedding_fwd(const int* tokens, const void* table, void* out, const EndDesc& d, hipStream_t st) {
   EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
   const dim3 grid((d.rows + 3) / 4, d.ni * d.nj);
@@ -311,19 +340,13 @@ int launch_embedding_bwd(const int* tokens, const void* dX, float* d_table, cons
 }
 int launch_ce_stats(const void* logits, float* stats, const EndDesc& d, hipStream_t st) {
   EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
-  const dim3 grid((d.rows + 3) / 4, d.ni * d.nj);
-  if (d.dtype == OPTIMUS_BF16) ce_stats_kernel<bf16_t, false><<<grid, 256, 0, st>>>((const bf16_t*)logits, stats, nullptr, nullptr, nullptr, a);
-  else ce_stats_kernel<float, false><<<grid, 256, 0, st>>>((const float*)logits, stats, nullptr, nullptr, nullptr, a);
-  return hip_launch_status();
+  return ce_stats_dispatch<false>(logits, stats, nullptr, nullptr, nullptr, d, a, st);
 }
 // one device whose peers' partials are resident: statistics and finish in one launch
 int launch_ce_stats_final(const void* logits, const int* labels, float* stats, float* loss, float* lse, const EndDesc& d,
                           hipStream_t st) {
   EndArgs a = {d.rows, d.vb, d.hb, d.q, d.v, d.i0, d.ni, d.j0, d.nj};
-  const dim3 grid((d.rows + 3) / 4, d.ni * d.nj);
-  if (d.dtype == OPTIMUS_BF16) ce_stats_kernel<bf16_t, true><<<grid, 256, 0, st>>>((const bf16_t*)logits, stats, labels, loss, lse, a);
-  else ce_stats_kernel<float, true><<<grid, 256, 0, st>>>((const float*)logits, stats, labels, loss, lse, a);
-  return hip_launch_status();
+  return ce_stats_dispatch<true>(logits, stats, labels, loss, lse, d, a, st);
 }
 int launch_ce_finalize(const void* logits, const int* labels, const float* stats, float* loss, float* lse, const EndDesc& d,
                        hipStream_t st) {
