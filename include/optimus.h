@@ -8,7 +8,8 @@
  *   library neither frees nor retains it.  `stream` is a hipStream_t passed as
  *   void* (NULL = the default stream).  Calls validate their arguments on the
  *   host, enqueue kernels on `stream` and return without synchronising.
- *   `optimus_layer_cfg` / `optimus_layer_tensors` structs are HOST memory.
+ *   The structs (`optimus_layer_cfg`, `optimus_layer_tensors`, `optimus_layer_params`, `optimus_layer_grads`,
+ *   `optimus_stack_buffers`, ...) and arrays of them are HOST memory holding device pointers.
  * Grid.  The method distributes every matrix over a q x q device mesh
  *   (Section 2.4): a logical row-major matrix T[R x C] is cut evenly into q*q
  *   sub-blocks, block (r, c) belonging to device (r, c).  This library keeps
@@ -26,9 +27,13 @@
  *   bf16 storage (round-to-nearest-even on store), fp32 accumulation on the
  *   matrix cores; statistics, soft-max sums, weight and bias gradients stay
  *   fp32.
- * Errors.  Return value 0 = OK, otherwise one of the OPTIMUS_E* codes below;
- *   on any error nothing has been enqueued.  No exceptions, no global state
- *   apart from a per-process cache of device properties.
+ * Errors.  Return value 0 = OK, otherwise one of the OPTIMUS_E* codes below.
+ *   Arguments are checked before anything is enqueued: on EINVAL / ESHAPE /
+ *   ECOORD / EDTYPE / EWORKSPACE nothing has been enqueued.  OPTIMUS_EHIP (the
+ *   runtime refused a launch) can come from a later kernel of a call that
+ *   enqueues several.  No exceptions.  Process state: the tuning hooks at the
+ *   end of this file, and per device one stream with its events that
+ *   optimus_layer_bwd creates on first use (see there).
  * Determinism.  No floating-point atomics: the same call on the same inputs
  *   gives bitwise identical output.
  */
