@@ -119,17 +119,17 @@ __device__ __forceinline__ float halfwave_sum(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// ---- direct global -> LDS copy of a PAIR x D tile (rows row0 .. row0 + 127 of a [s][ld] matrix) by four wavefronts ----
+// ---- direct global -> LDS copy of a PAIR x D tile (rows row0 .. row0 + 127 of a [s][ld] matrix) by NW wavefronts ----
 __device__ __forceinline__ i32x4 make_rsrc(const bf16_t* base) {  // raw buffer, 2 GiB window (offsets used are far below)
   const unsigned long long p = (unsigned long long)base;  // wave-uniform by construction; say so to the compiler
   const int lo = __builtin_amdgcn_readfirstlane((int)(unsigned)p);
   const int hi = __builtin_amdgcn_readfirstlane((int)(unsigned)((p >> 32) & 0xffffu));
   return i32x4{lo, hi, (int)0x80000000u, 0x00020000};
 }
-template <int D>
+template <int D, int NW = NWAVES>
 struct PairLoader {
-  static constexpr int CH = D / 8, ROWS_PER_KIB = 64 / CH, PIECES = PAIR * D * 2 / 1024, PER = PIECES / NWAVES;
-  static_assert(PIECES % NWAVES == 0, "tile must divide over the wavefronts");
+  static constexpr int CH = D / 8, ROWS_PER_KIB = 64 / CH, PIECES = PAIR * D * 2 / 1024, PER = PIECES / NW;
+  static_assert(PIECES % NW == 0, "tile must divide over the wavefronts");
   unsigned off[PER];  // byte offsets of this lane's chunks for a tile that lies entirely inside the matrix
   int ld, wave, lane;
   __device__ __forceinline__ void init(int ld_, int wave_, int lane_) {
@@ -175,26 +175,28 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 }
 
 // ---------------------------------------------------------------- forward
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fused_fwd_kernel(FusedArgs a) {
-  constexpr int KS = D / 16, DT = D / 32;
+// NRG: row groups of 32 queries per workgroup (2: 64 rows, four wavefronts; 4: 128 rows, eight wavefronts -- half the
+// K/V bytes per flop and two wavefronts per SIMD, for launches with more workgroups than compute units).
+template <int D, bool CAUSAL, int NRG>
+__global__ __launch_bounds__(NRG * 128) void attn_fused_fwd_kernel(FusedArgs a) {
+  constexpr int KS = D / 16, DT = D / 32, BQ = NRG * 32;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];  // [stage][K, V][pair tile]
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int rg = wave & 1, par = wave >> 1;
+  const int rg = wave % NRG, par = wave / NRG;
   const int tile = gridDim.x - 1 - blockIdx.x;  // the tiles with the longest causal loops start first
   const int mat = blockIdx.y, dev = blockIdx.z, s = a.s;
   const int seq = mat / a.nh, head = mat % a.nh;
   const bf16_t* Qp = a.qkv + dev * a.dev_qkv + (long long)seq * s * a.ld + head * 3 * D;
   const bf16_t* Kp = Qp + D;
   const bf16_t* Vp = Qp + 2 * D;
-  const int q0 = tile * BLK + rg * 32;
+  const int q0 = tile * BQ + rg * 32;
   const int query = q0 + (lane & 31);
   const int qrow = min(query, s - 1);
   bf16x8 qf[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(Qp + (long long)qrow * a.ld + ks * 16 + g * 8);
-  const int wg_hi = min(tile * BLK + BLK, s) - 1;  // last query row of the workgroup
+  const int wg_hi = min(tile * BQ + BQ, s) - 1;  // last query row of the workgroup
   const int nkb = CAUSAL ? wg_hi / BLK + 1 : (s + BLK - 1) / BLK;
   const int n_it = (nkb + 1) / 2;
   const int wave_nkb = q0 >= s ? 0 : (CAUSAL ? min(q0 + 31, s - 1) / BLK + 1 : nkb);
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(256) void attn_fused_fwd_kernel(FusedArgs a) {
   for (int dt = 0; dt < DT; ++dt) oacc[dt] = zero16();
   float m_run = -INFINITY, l_run = 0.f;
 
-  PairLoader<D> ldr;
+  PairLoader<D, 2 * NRG> ldr;
   ldr.init(a.ld, wave, lane);
   ldr.issue(Kp, 0, s, lds[0][0]);
   ldr.issue(Vp, 0, s, lds[0][1]);
@@ -616,9 +618,17 @@ bool desc_ok(const AttnFusedDesc& d) {
 
 template <int D>
 void fwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
-  const dim3 grid((d.s + BLK - 1) / BLK, d.nb * d.nh, d.ndev), block(NWAVES * 64);
-  if (d.causal) attn_fused_fwd_kernel<D, true><<<grid, block, 0, st>>>(a);
-  else attn_fused_fwd_kernel<D, false><<<grid, block, 0, st>>>(a);
+  // 128-row workgroups once they still outnumber the compute units two to one; 64-row ones otherwise
+  const bool big = (long long)((d.s + 127) / 128) * d.nb * d.nh * d.ndev >= 512;
+  if (big) {
+    const dim3 grid((d.s + 127) / 128, d.nb * d.nh, d.ndev), block(512);
+    if (d.causal) attn_fused_fwd_kernel<D, true, 4><<<grid, block, 0, st>>>(a);
+    else attn_fused_fwd_kernel<D, false, 4><<<grid, block, 0, st>>>(a);
+  } else {
+    const dim3 grid((d.s + BLK - 1) / BLK, d.nb * d.nh, d.ndev), block(256);
+    if (d.causal) attn_fused_fwd_kernel<D, true, 2><<<grid, block, 0, st>>>(a);
+    else attn_fused_fwd_kernel<D, false, 2><<<grid, block, 0, st>>>(a);
+  }
 }
 template <int D>
 void bwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {

@@ -29,8 +29,10 @@ def _lse_blocks(L, b, n, q):
 # tiles, q = 1, config-2- and config-4-like sequence lengths, and a sequence longer than the unfused path accepts
 CASES = [(4, 64, 256, 4, 2), (2, 328, 256, 2, 2), (2, 256, 128, 2, 1), (4, 136, 256, 4, 4), (2, 100, 128, 2, 2),
          (2, 33, 256, 2, 1), (2, 512, 128, 2, 2), (2, 1024, 256, 2, 2), (1, 4360, 64, 1, 1),
-         # enough (sequence, head) pairs that the library switches from two to four wavefronts per workgroup
-         (8, 392, 512, 8, 1), (8, 520, 1024, 8, 1)]
+         # many (sequence, head) pairs, ragged s
+         (8, 392, 512, 8, 1), (8, 520, 1024, 8, 1),
+         # enough work that the forward switches to 128-row workgroups of eight wavefronts (ragged and exact s)
+         (8, 1024, 512, 8, 1), (8, 1100, 1024, 8, 1)]
 
 
 @pytest.mark.parametrize("causal", [True, False])
