@@ -327,20 +327,20 @@ __global__ __launch_bounds__(NRG * 128) void attn_fused_fwd_kernel(FusedArgs a) 
 }
 
 // ---------------------------------------------------------------- backward, dQ (and rowsum(dO * O))
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fused_bwd_dq_kernel(FusedArgs a) {
-  constexpr int KS = D / 16, DT = D / 32;
+template <int D, bool CAUSAL, int NRG>
+__global__ __launch_bounds__(NRG * 128) void attn_fused_bwd_dq_kernel(FusedArgs a) {
+  constexpr int KS = D / 16, DT = D / 32, BQ = NRG * 32;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];  // [stage][K, V][pair tile]
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int rg = wave & 1, par = wave >> 1;
+  const int rg = wave % NRG, par = wave / NRG;
   const int tile = gridDim.x - 1 - blockIdx.x;
   const int mat = blockIdx.y, dev = blockIdx.z, s = a.s;
   const int seq = mat / a.nh, head = mat % a.nh;
   const bf16_t* Qp = a.qkv + dev * a.dev_qkv + (long long)seq * s * a.ld + head * 3 * D;
   const bf16_t* Kp = Qp + D;
   const bf16_t* Vp = Qp + 2 * D;
-  const int q0 = tile * BLK + rg * 32;
+  const int q0 = tile * BQ + rg * 32;
   const int query = q0 + (lane & 31);
   const int qrow = min(query, s - 1);
   const long long orow = dev * a.dev_attn + ((long long)seq * s + qrow) * a.ldo + head * D;
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(256) void attn_fused_bwd_dq_kernel(FusedArgs a) {
   delta = halfwave_sum(delta);
   if (par == 0 && g == 0 && query < s) a.delta[vrow] = delta;
   const float lse2 = a.lse[vrow] * LOG2E;
-  const int wg_hi = min(tile * BLK + BLK, s) - 1;
+  const int wg_hi = min(tile * BQ + BQ, s) - 1;
   const int nkb = CAUSAL ? wg_hi / BLK + 1 : (s + BLK - 1) / BLK;
   const int n_it = (nkb + 1) / 2;
   const int wave_nkb = q0 >= s ? 0 : (CAUSAL ? min(q0 + 31, s - 1) / BLK + 1 : nkb);
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(256) void attn_fused_bwd_dq_kernel(FusedArgs a) {
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) dqacc[dt] = zero16();
 
-  PairLoader<D> ldr;
+  PairLoader<D, 2 * NRG> ldr;
   ldr.init(a.ld, wave, lane);
   ldr.issue(Kp, 0, s, lds[0][0]);
   ldr.issue(Vp, 0, s, lds[0][1]);
@@ -450,15 +450,15 @@ __global__ __launch_bounds__(256) void attn_fused_bwd_dq_kernel(FusedArgs a) {
 
 // ---------------------------------------------------------------- backward, dK and dV
 // A wavefront owns 32 keys and every second block of 64 queries (from the diagonal on when causal).
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
-  constexpr int KS = D / 16, DT = D / 32;
+template <int D, bool CAUSAL, int NRG>
+__global__ __launch_bounds__(NRG * 128) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
+  constexpr int KS = D / 16, DT = D / 32, BKW = NRG * 32;
   __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];  // [stage][Q, dO][pair tile]
   __shared__ __attribute__((aligned(16))) float ldsL[2][PAIR];           // lse * log2(e) of the pair's queries
   __shared__ __attribute__((aligned(16))) float ldsD[2][PAIR];           // rowsum(dO * O)
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int rg = wave & 1, par = wave >> 1;
+  const int rg = wave % NRG, par = wave / NRG;
   const int tile = blockIdx.x;  // early key tiles have the longest causal loops
   const int mat = blockIdx.y, dev = blockIdx.z, s = a.s;
   const int seq = mat / a.nh, head = mat % a.nh;
@@ -468,7 +468,7 @@ __global__ __launch_bounds__(256) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
   const bf16_t* Gp = a.d_attn + dev * a.dev_attn + (long long)seq * s * a.ldo + head * D;
   const float* Lp = a.lse + dev * a.dev_vec + (long long)mat * s;
   const float* Dp = a.delta + dev * a.dev_vec + (long long)mat * s;
-  const int k0 = tile * BLK + rg * 32;
+  const int k0 = tile * BKW + rg * 32;
   const int key = k0 + (lane & 31);
   const int krow = min(key, s - 1);
   bf16x8 kf[KS], vf[KS];
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(256) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
     vf[ks] = *(const bf16x8*)(Vp + (long long)krow * a.ld + ks * 16 + g * 8);
   }
   const int nqb = (s + BLK - 1) / BLK;
-  const int qb_lo = CAUSAL ? tile : 0;  // first block with a query >= the workgroup's first key (blocks are 64 = its rows)
+  const int qb_lo = CAUSAL ? (tile * BKW) / BLK : 0;  // first block with a query >= the workgroup's first key
   const int n_it = (nqb - qb_lo + 1) / 2;
   const bool wave_valid = k0 < s;
 
@@ -488,7 +488,7 @@ __global__ __launch_bounds__(256) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
     dkacc[dt] = zero16();
     dvacc[dt] = zero16();
   }
-  PairLoader<D> ldq, ldg;
+  PairLoader<D, 2 * NRG> ldq, ldg;
   ldq.init(a.ld, wave, lane);
   ldg.init(a.ldo, wave, lane);
   auto load_pair = [&](int it, int st) {
@@ -630,16 +630,27 @@ void fwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
     else attn_fused_fwd_kernel<D, false, 2><<<grid, block, 0, st>>>(a);
   }
 }
+template <int D, bool CAUSAL>
+void bwd_launch_c(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
+  const dim3 grid((d.s + BLK - 1) / BLK, d.nb * d.nh, d.ndev), block(NWAVES * 64);
+  // 128-row workgroups of eight wavefronts for big launches, where the kernel fits 256 registers per lane (the dK/dV
+  // kernel at head width 128 does not: it would spill a hundred registers)
+  const bool big = (long long)((d.s + 127) / 128) * d.nb * d.nh * d.ndev >= 512;
+  const dim3 grid_big((d.s + 127) / 128, d.nb * d.nh, d.ndev), block_big(512);
+  if (big) attn_fused_bwd_dq_kernel<D, CAUSAL, 4><<<grid_big, block_big, 0, st>>>(a);
+  else attn_fused_bwd_dq_kernel<D, CAUSAL, 2><<<grid, block, 0, st>>>(a);
+  if constexpr (D == 64) {
+    if (big) {
+      attn_fused_bwd_dkv_kernel<D, CAUSAL, 4><<<grid_big, block_big, 0, st>>>(a);
+      return;
+    }
+  }
+  attn_fused_bwd_dkv_kernel<D, CAUSAL, 2><<<grid, block, 0, st>>>(a);
+}
 template <int D>
 void bwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
-  const dim3 grid((d.s + BLK - 1) / BLK, d.nb * d.nh, d.ndev), block(NWAVES * 64);
-  if (d.causal) {
-    attn_fused_bwd_dq_kernel<D, true><<<grid, block, 0, st>>>(a);
-    attn_fused_bwd_dkv_kernel<D, true><<<grid, block, 0, st>>>(a);
-  } else {
-    attn_fused_bwd_dq_kernel<D, false><<<grid, block, 0, st>>>(a);
-    attn_fused_bwd_dkv_kernel<D, false><<<grid, block, 0, st>>>(a);
-  }
+  if (d.causal) bwd_launch_c<D, true>(a, d, st);
+  else bwd_launch_c<D, false>(a, d, st);
 }
 
 }  // namespace
