@@ -618,8 +618,8 @@ bool desc_ok(const AttnFusedDesc& d) {
 
 template <int D>
 void fwd_launch(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
-  // 128-row workgroups once they still outnumber the compute units two to one; 64-row ones otherwise
-  const bool big = (long long)((d.s + 127) / 128) * d.nb * d.nh * d.ndev >= 512;
+  // 128-row workgroups from one per two compute units on (measured: equal or faster than 64-row ones from there)
+  const bool big = (long long)((d.s + 127) / 128) * d.nb * d.nh * d.ndev >= 128;
   if (big) {
     const dim3 grid((d.s + 127) / 128, d.nb * d.nh, d.ndev), block(512);
     if (d.causal) attn_fused_fwd_kernel<D, true, 4><<<grid, block, 0, st>>>(a);
