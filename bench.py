@@ -309,9 +309,10 @@ def pmc_probe(opt, torch, gemm, q, i, j):
     torch.cuda.synchronize()
     rows = time_gemms(opt, torch, [gemm], q, i, j, 5, 7, rotating=False)
     bw = time_bandwidth(opt, torch, 8, 1024, 4096, 32, 4, 1, 2, 3, 11)
+    ends = time_model_ends(opt, torch, 8, 1024, 4096, 4, 1, 2, 32768, 3, 12)
     torch.cuda.synchronize()
-    print(json.dumps({"probe": "copy 268435456 B x3; product x graph replays; layernorm/attention at config-4 blocks",
-                      "gemm": rows, "bandwidth": bw}))
+    print(json.dumps({"probe": "copy 268435456 B x3; product x graph replays; layernorm/attention (both forms) and the model "
+                               "ends at config-4 blocks", "gemm": rows, "bandwidth": bw, "model_ends": ends}))
 
 
 def main():
