@@ -733,6 +733,10 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   hipStream_t gst = ss ? ss->s : st;
   void* gstream = (void*)gst;
   void* grad_ws = ss ? (char*)gemm_ws + gemm_bytes : gemm_ws;
+  // LayerNorm 2's parameter gradients need d_ln2_out only.  Small blocks: the chain is a string of short kernels and
+  // the column sums are one more serial step of it, so they go to the branch (measured: the step 5 % shorter at
+  // [1024 x 256] blocks).  Large blocks: the branch, with its transposing products, is the longer stream already.
+  const bool ln2_grads_on_branch = colsum_narrow((int)(M / q), (int)(h / q));
   optimus_epilogue e = {};
   optimus_epilogue e32 = {};
   e32.out_fp32 = 1;
@@ -750,12 +754,14 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   RUN(run_summa(OPTIMUS_FORM_ATB, t->ln2_out, t->d_pre_gelu, t->d_w1, h, M, 4 * h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream, 2));
   RUN(optimus_bias_grad(t->d_pre_gelu, t->d_b1, M, 4 * h, q, i, j, dt, gstream));
   // ---- LN2 backward, plus the residual branch: d_h_mid = d_out + LN2'(d_ln2_out) ----
-  RUN(ln_backward(t->d_ln2_out, t->xhat2, t->rstd2, t->ln2_g, t->d_out, t->d_h_mid, t->d_ln2_g, t->d_ln2_b, t->bstats2, ln, grid, st));
+  RUN(ln_backward(t->d_ln2_out, t->xhat2, t->rstd2, t->ln2_g, t->d_out, t->d_h_mid, ln2_grads_on_branch ? nullptr : t->d_ln2_g,
+                  ln2_grads_on_branch ? nullptr : t->d_ln2_b, t->bstats2, ln, grid, st));
   // ---- h_mid = x + attn Wo + bo ----
   BRANCH_AFTER_MAIN(ss->ready[1]);  // d_h_mid is complete
   RUN(run_summa(OPTIMUS_FORM_ABT, t->d_h_mid, t->w_o, t->d_attn, M, h, h, q, i, j, dt, nullptr, gemm_ws, gemm_bytes, stream, 1));
   RUN(run_summa(OPTIMUS_FORM_ATB, t->attn, t->d_h_mid, t->d_w_o, h, M, h, q, i, j, dt, &e32, grad_ws, gemm_bytes, gstream, 2));
   RUN(optimus_bias_grad(t->d_h_mid, t->d_b_o, M, h, q, i, j, dt, gstream));
+  if (ln2_grads_on_branch) RUN(launch_ln_param_grads(t->d_ln2_out, t->xhat2, t->d_ln2_g, t->d_ln2_b, ln, gst));
   // ---- local attention backward ----
   RUN(layer_attention(true, c, t, i, j, attn_ws, attn_bytes, stream));
   // ---- qkv = ln1_out Wqkv + b ----

@@ -123,6 +123,8 @@ int launch_ln_bwd_stats(const void* dY, const void* xhat, const float* gamma, fl
                         hipStream_t stream);
 int launch_ln_bwd_apply(const void* dY, const void* xhat, const float* rstd, const float* gamma, const void* dres,
                         void* dX, float* stats, const LnDesc& d, bool own_stats_ready, hipStream_t stream);
+// small blocks (narrow column strips; the kernel is latency-bound there)
+bool colsum_narrow(int rows, int cols);
 int launch_ln_param_grads(const void* dY, const void* xhat, float* dgamma_part, float* dbeta_part, const LnDesc& d,
                           hipStream_t stream);
 

@@ -285,7 +285,7 @@ __global__ __launch_bounds__(CS_THREADS) void colsum_kernel(const T* __restrict_
 }
 
 // strip width from the block shape only (never from the batch): grid mode and device mode then add in the same order
-static bool colsum_narrow(int rows, int cols) { return (long long)rows * cols <= (1LL << 20); }
+bool colsum_narrow(int rows, int cols) { return (long long)rows * cols <= (1LL << 20); }
 
 template <typename T, bool PROD>
 static void colsum_launch(dim3 batch, const T* X, const T* W, float* out, float* out2, int rows, int cols, int ld, long long sX,
@@ -314,10 +314,12 @@ int launch_ln_param_grads(const void* dY, const void* xhat, float* dgamma_part, 
                           hipStream_t stream) {
   const long long blk = (long long)d.rows * d.cols;
   int rc = OPTIMUS_OK;
-  for (int ii = 0; ii < d.ni && rc == OPTIMUS_OK; ++ii) {
-    // the nj blocks of one grid row are contiguous in block-major storage
+  // block-major storage: the nj blocks of one grid row are contiguous, and so are whole grid rows that follow each other
+  const bool whole_rows = d.nj == d.q;
+  const int launches = whole_rows ? 1 : d.ni, per_launch = whole_rows ? d.ni * d.nj : d.nj;
+  for (int ii = 0; ii < launches && rc == OPTIMUS_OK; ++ii) {
     const long long first = ((long long)(d.i0 + ii) * d.q + d.j0);
-    dim3 batch(1, (unsigned)d.nj);
+    dim3 batch(1, (unsigned)per_launch);
     if (d.dtype == OPTIMUS_BF16)
       colsum_launch<bf16_t, true>(batch, (const bf16_t*)dY + first * blk, (const bf16_t*)xhat + first * blk, dbeta_part + first * d.cols,
                                   dgamma_part + first * d.cols, d.rows, d.cols, d.cols, blk, (long long)d.cols, stream);
