@@ -187,6 +187,29 @@ def test_layer_config2_full_size():
         assert torch.equal(v.view(torch.uint8), snap[k].view(torch.uint8)), k
 
 
+@pytest.mark.parametrize("shp", [LayerShape(b=4, s=64, h=128, n=4, q=2), LayerShape(b=8, s=1024, h=2048, n=16, q=2)],
+                         ids=["small_blocks", "large_blocks"])
+def test_layer_layernorm_parameter_gradients_equal_the_standalone_call(shp):
+    """The layer runs the LayerNorm parameter gradients on either of its two streams depending on the block size
+    ([128 x 64]: the gradient branch; [4096 x 1024]: the activation chain).  Wherever they run, they are the column
+    sums of the stored dY and dY * xhat: bit-identical to optimus_layernorm2d_bwd on the same stored tensors."""
+    inp = layer_inputs(14, shp, "bf16", perturb_affine=True)
+    cfg, T, lt, ws = alloc_layer(inp, shp, True)
+    opt.layer_fwd(cfg, lt, -1, -1, ws)
+    opt.layer_bwd(cfg, lt, -1, -1, ws)
+    torch.cuda.synchronize()
+    M, h, q = shp.M, shp.h, shp.q
+    for k, dy, res in (("2", "d_ln2_out", "d_out"), ("1", "d_ln1_out", "d_h_mid")):
+        dg, db = torch.full_like(T["d_ln%s_g" % k], float("nan")), torch.full_like(T["d_ln%s_b" % k], float("nan"))
+        dx = torch.empty_like(T[dy])
+        stats = torch.empty_like(T["bstats" + k])
+        opt.layernorm2d_bwd(T[dy], T["xhat" + k], T["rstd" + k], T["ln%s_g" % k], T[res], dx, dg, db, stats, M, h, q, -1, -1, opt.BF16)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(dg), to_host(T["d_ln%s_g" % k])), k
+        assert np.array_equal(to_host(db), to_host(T["d_ln%s_b" % k])), k
+        assert np.array_equal(to_host(dx), to_host(T["d_h_mid" if k == "2" else "d_x"])), k
+
+
 def test_layer_errors():
     shp = LayerShape(b=4, s=64, h=128, n=4, q=2)
     inp = layer_inputs(1, shp, "bf16")
