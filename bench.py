@@ -297,6 +297,52 @@ def time_model_ends(opt, torch, b, s, h, q, i, j, v, reps, seed):
     return out
 
 
+def time_layer_step(opt, torch, harness, name, steps, warmup):
+    """The layer step (device mode, HIP graph replay) of another configuration, timed like the main workload's:
+    reported beside it so that one default run also carries the whole-step figures of the larger layers."""
+    from workloads import CONFIGS, layer_inputs, bf16_bits
+    cfgd = CONFIGS[name]
+    shp = cfgd["layer"]
+    b, s, h, n, q = shp.b, shp.s, shp.h, shp.n, shp.q
+    di, dj = 1 % q, 2 % q
+    inp = layer_inputs(cfgd["seed"], shp, "bf16")
+    bits = {k: bf16_bits(inp[k]) for k in ("x", "w_qkv", "w_o", "w1", "w2", "d_out")}
+    vecs = {k: inp[k] for k in ("ln1_g", "ln1_b", "b_qkv", "b_o", "ln2_g", "ln2_b", "b1", "b2")}
+    del inp
+    res = {"workload": f"{name}: one device ({di},{dj}) of a q={q} grid, layer fwd+bwd, b={b} s={s} h={h} n={n}, causal"}
+    summa_flops = sum(opt.gemm_flops(M, K, N, q) for (_, _, M, K, N) in layer_gemm_list(b, s, h))
+    T0 = None
+    for fused in (False, True):
+        if fused and (h // n) not in (64, 128):
+            break
+        cfg, T, lt, ws = harness.alloc_layer(bits, vecs, b, s, h, n, q, causal=True, fused_attention=fused, share=T0)
+        T0 = T0 or T
+        opt.layer_fwd(cfg, lt, -1, -1, ws)   # untimed grid-mode pass: every peer block resident
+        opt.layer_bwd(cfg, lt, -1, -1, ws)
+        torch.cuda.synchronize()
+
+        def step():
+            opt.layer_fwd(cfg, lt, di, dj, ws)
+            opt.layer_bwd(cfg, lt, di, dj, ws)
+        run, graphed = capture(step, 1)
+        for _ in range(warmup):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        key = "fused_attention" if fused else "unfused_attention"
+        res[key] = {"ms_per_step": round(ms, 4), "tflops": round(summa_flops / (ms * 1e-3) / 1e12, 1),
+                    "pct_of_bf16_mfma_peak": round(100 * summa_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+                    "launch": "HIP graph replay" if graphed else "eager launches"}
+        del run, lt, ws
+        if fused:
+            del T
+    return res
+
+
 def pmc_probe(opt, torch, gemm, q, i, j):
     """A 256 MiB device copy (known traffic: 256 MiB read, 256 MiB written), then the given product, then the
     LayerNorm kernels at config-4 block size, each a few times; profiled with rocprofv3 --pmc FETCH_SIZE and, in a
@@ -447,6 +493,10 @@ def main():
         out["model_ends"] = time_model_ends(opt, torch, b, s, h, q, di, dj, 32768, args.gemm_reps, 9)
     if not args.no_sweep and args.workload == "config2":
         out["stack"] = time_stack(opt, torch, harness, cfg, T, b, s, h, n, q, layers=4, reps=max(3, args.steps // 10))
+    if not args.no_sweep and args.workload == "config2":
+        # whole-step figures of the larger layers (the same measurement as `value`, fewer replays)
+        out["other_workload_steps"] = [time_layer_step(opt, torch, harness, name, max(10, args.steps // 2), args.warmup)
+                                       for name in ("config4", "config5")]
     if not args.no_sweep and args.workload == "config2":
         # the same forward products launched for the whole grid at once (i = j = -1: all q*q devices' blocks)
         fwd = [g for g in gemms if g[0] in ("qkv.ab", "mlp_up.ab", "mlp_down.ab")]
