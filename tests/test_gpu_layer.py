@@ -185,6 +185,35 @@ def test_layer_config2_full_size():
     torch.cuda.synchronize()
     for k, v in T.items():
         assert torch.equal(v.view(torch.uint8), snap[k].view(torch.uint8)), k
+    # the benchmark replays the step of device (1, 2) from a HIP graph: every replay, with eager work and
+    # synchronisations in between, must leave the grid run's bits (its blocks are poisoned before each replay)
+    outs = [k for k in T if k in FWD_OUT + BWD_OUT + FP32_MATS]
+    i, j, q = 1, 2, shp.q
+
+    def step():
+        opt.layer_fwd(cfg, lt, i, j, ws)
+        opt.layer_bwd(cfg, lt, i, j, ws)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for replay in range(3):
+        for k in outs:
+            r, c = MAT_SHAPES[k](shp.M, shp.h)
+            blk = (r // q) * (c // q)
+            T[k][(i * q + j) * blk:(i * q + j + 1) * blk] = float("nan")
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k, v in T.items():
+            assert torch.equal(v.view(torch.uint8), snap[k].view(torch.uint8)), (replay, k)
+        opt.layer_fwd(cfg, lt, 0, 3, ws)   # eager work between the replays
+        torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("shp", [LayerShape(b=4, s=64, h=128, n=4, q=2), LayerShape(b=8, s=1024, h=2048, n=16, q=2)],
