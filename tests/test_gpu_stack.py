@@ -115,6 +115,66 @@ def test_stack_against_oracle_and_layerwise_run(shp, L, fused):
     assert torch.equal(g_in.view(torch.int16), dX.view(torch.int16))
 
 
+def test_stack_graph_replays_equal_eager():
+    """The benchmark times the stack from a HIP graph (a device-to-device copy node, the recomputation and the forked
+    gradient branch of every layer).  Every replay, with eager work and synchronisations between them and the outputs
+    poisoned before each, leaves the bits of the eager run."""
+    shp, L = LayerShape(b=4, s=64, h=128, n=4, q=2), 3
+    M, h, q = shp.M, shp.h, shp.q
+    layers, x, d_out = _inputs(31, shp, L)
+    cfg = opt.LayerCfg(shp.b, shp.s, shp.h, shp.n, shp.q, 1e-5, 1, opt.BF16, 0)
+    dev_params = []
+    for inp in layers:
+        t = {k: mat_to_dev(inp[k], q, "bf16") for k in MATS}
+        t.update({k: vec_to_dev(inp[k]) for k in ostack.PARAM_NAMES if k not in MATS})
+        dev_params.append(t)
+    P = [opt.make_layer_params(t) for t in dev_params]
+    sz, raw, buf = _buffers(cfg, L)
+    X, dO = mat_to_dev(x, q, "bf16"), mat_to_dev(d_out, q, "bf16")
+    OUT, dX = empty(M * h, "bf16"), empty(M * h, "bf16")
+    G = [_alloc_grads(shp) for _ in range(L)]
+    GL = [opt.make_layer_grads(g) for g in G]
+
+    def step():
+        opt.stack_fwd(cfg, P, X, buf, OUT)
+        opt.stack_bwd(cfg, P, GL, dO, buf, dX)
+
+    def results():
+        torch.cuda.synchronize()
+        r = {"out": OUT.clone(), "d_x": dX.clone()}
+        for l in range(L):
+            r.update({f"L{l}.{k}": v.clone() for k, v in G[l].items()})
+        return r
+
+    def poison():
+        OUT.view(torch.int16).fill_(-1)
+        dX.view(torch.int16).fill_(-1)
+        for g in G:
+            for v in g.values():
+                v.fill_(float("nan"))
+        torch.cuda.synchronize()
+
+    step()
+    want = results()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for replay in range(3):
+        poison()
+        graph.replay()
+        got = results()
+        for k in want:
+            assert torch.equal(got[k].view(torch.uint8), want[k].view(torch.uint8)), (replay, k)
+        opt.stack_fwd(cfg, P, X, buf, OUT)   # eager work between the replays
+        torch.cuda.synchronize()
+
+
 def test_stack_shared_gradient_buffer_with_callback():
     """All layers write their parameter gradients into ONE buffer; the per-layer callback takes them out (here: a
     stream-ordered copy), as an optimizer that updates a layer right after its backward pass would."""
