@@ -188,7 +188,7 @@ def time_bandwidth(opt, torch, b, s, h, n, q, i, j, reps, seed):
     put("layernorm2d_bwd", ms, 5 * blk, "dx kernel (read dy, xhat; write dx) + column-sum kernel (read dy, xhat)")
     # the same kernels over all q*q blocks in one launch: how far the kernels go when a launch is not latency-bound
     ms = event_time_ms(lambda: opt.layernorm2d(X, gamma, beta, Y, xhat, rstd, stats, M, H, q, -1, -1, 1e-5, opt.BF16), reps)
-    put("layernorm2d_fwd_all_blocks", ms, 3 * blk * q * q, f"the same for all {q * q} blocks in one launch (stats kernel + apply kernel)")
+    put("layernorm2d_fwd_all_blocks", ms, 3 * blk * q * q, f"the same for all {q * q} blocks in one launch (the partial row statistics meet inside the launch)")
     ms = event_time_ms(lambda: opt.layernorm2d_bwd(dY, xhat, rstd, gamma, None, dX, None, None, bstats, M, H, q, -1, -1, opt.BF16), reps)
     put("layernorm2d_bwd_dx_all_blocks", ms, 3 * blk * q * q, f"dx for all {q * q} blocks in one launch (no parameter gradients)")
     # attention: scores fp32 scratch -> probabilities bf16; bytes counted for the two softmax-like passes only

@@ -290,17 +290,18 @@ int ln_desc(int64_t M, int64_t H, int q, int i, int j, int dtype, float eps, LnD
 
 int ln_forward(const void* X, const float* gamma, const float* beta, void* Y, void* xhat, float* rstd, float* stats,
                const LnDesc& d, bool grid, hipStream_t st) {
-  if (grid) {
+  if (grid && !ln_rowgroup_ok(d)) {
     int rc = launch_ln_stats(X, stats, d, st);
     if (rc) return rc;
     return launch_ln_apply(X, gamma, beta, Y, xhat, rstd, stats, d, true, st);
   }
+  // one device: its own partial, the peers' from `stats`; whole grid: every row's partials meet inside the launch
   return launch_ln_apply(X, gamma, beta, Y, xhat, rstd, stats, d, false, st);
 }
 int ln_backward(const void* dY, const void* xhat, const float* rstd, const float* gamma, const void* dres, void* dX,
                 float* dgamma_part, float* dbeta_part, float* stats, const LnDesc& d, bool grid, hipStream_t st) {
   int rc;
-  if (grid) {
+  if (grid && !ln_rowgroup_ok(d)) {
     if ((rc = launch_ln_bwd_stats(dY, xhat, gamma, stats, d, st))) return rc;
     rc = launch_ln_bwd_apply(dY, xhat, rstd, gamma, dres, dX, stats, d, true, st);
   } else {

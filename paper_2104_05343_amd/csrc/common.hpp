@@ -116,6 +116,9 @@ struct LnDesc {
   int dtype;
   float eps;
 };
+// true if launch_ln_apply / launch_ln_bwd_apply with own_ready = false compute and exchange the partials of a whole
+// grid row inside one launch (then no separate statistics launch is needed before them)
+bool ln_rowgroup_ok(const LnDesc& d);
 int launch_ln_stats(const void* X, float* stats, const LnDesc& d, hipStream_t stream);
 int launch_ln_apply(const void* X, const float* gamma, const float* beta, void* Y, void* xhat, float* rstd,
                     float* stats, const LnDesc& d, bool own_stats_ready, hipStream_t stream);

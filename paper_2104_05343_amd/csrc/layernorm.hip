@@ -50,8 +50,13 @@ struct LnArgs {
 
 // MODE 0: forward stats only.  MODE 1: forward apply (own partial computed here unless own_ready).
 // MODE 2: backward stats only. MODE 3: backward apply.
-template <typename T, int MODE>
-__global__ __launch_bounds__(256) void ln_kernel(const T* __restrict__ X, const T* __restrict__ X2, const float* __restrict__ gamma,
+// RG ("row group", MODE 1 and 3, whole grid rows only): a workgroup holds the q wavefronts that own the q segments of
+// the same logical row (times a few rows), each computes its partial, the partials meet in LDS, and every
+// wavefront adds them in the order l = 0..q-1: the same numbers in the same order as the two-kernel form
+// (statistics kernel, then apply with own_ready), in one pass over the input.  The partials are still written
+// to `stats`, which device-mode calls of the peers read.
+template <typename T, int MODE, bool RG = false>
+__global__ __launch_bounds__(RG ? 1024 : 256) void ln_kernel(const T* __restrict__ X, const T* __restrict__ X2, const float* __restrict__ gamma,
                                                  const float* __restrict__ beta, const float* __restrict__ rstd_in,
                                                  const T* __restrict__ dres, T* __restrict__ Y, T* __restrict__ xhat_out,
                                                  float* __restrict__ rstd_out, float* __restrict__ stats, LnArgs a, int own_ready) {
@@ -59,8 +64,10 @@ __global__ __launch_bounds__(256) void ln_kernel(const T* __restrict__ X, const 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int dev = blockIdx.y;
-  const int di = a.i0 + dev / a.nj, dj = a.j0 + dev % a.nj;
-  const int row = blockIdx.x * 4 + wave;
+  // RG: wavefront = (row of the workgroup, segment dj); the host launches whole workgroups only (no partial last one)
+  const int di = RG ? a.i0 + dev : a.i0 + dev / a.nj;
+  const int dj = RG ? wave % a.q : a.j0 + dev % a.nj;
+  const int row = RG ? blockIdx.x * ((int)(blockDim.x >> 6) / a.q) + wave / a.q : blockIdx.x * 4 + wave;
   if (row >= a.rows) return;
   const long long blk = (long long)a.rows * a.cols;
   const long long base = ((long long)di * a.q + dj) * blk + (long long)row * a.cols;
@@ -108,11 +115,19 @@ __global__ __launch_bounds__(256) void ln_kernel(const T* __restrict__ X, const 
 
   // add the q partials of this grid row in fixed order (own partial from registers when computed here)
   float t0 = 0.f, t1 = 0.f;
-  for (int l = 0; l < a.q; ++l) {
-    float p0, p1;
-    if (l == dj && need_own) { p0 = own0; p1 = own1; }
-    else { p0 = st_row[l * st_dev]; p1 = st_row[l * st_dev + 1]; }
-    t0 += p0; t1 += p1;
+  if constexpr (RG) {
+    __shared__ float part[16][2];
+    if (lane == 0) { part[wave][0] = own0; part[wave][1] = own1; }
+    __syncthreads();
+    const int w0 = wave - dj;  // first wavefront of this row
+    for (int l = 0; l < a.q; ++l) { t0 += part[w0 + l][0]; t1 += part[w0 + l][1]; }
+  } else {
+    for (int l = 0; l < a.q; ++l) {
+      float p0, p1;
+      if (l == dj && need_own) { p0 = own0; p1 = own1; }
+      else { p0 = st_row[l * st_dev]; p1 = st_row[l * st_dev + 1]; }
+      t0 += p0; t1 += p1;
+    }
   }
   const float invH = 1.0f / (float)a.H;
   if (MODE == 1) {
@@ -183,12 +198,30 @@ static LnArgs make_args(const LnDesc& d, bool ptr_ok, int elem_bytes) {
 }
 static bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+// rows of one workgroup of the row-group form: q wavefronts per row, four wavefronts or more per workgroup
+static int ln_rowgroup_rows(const LnDesc& d) {
+  int r = d.q >= 4 ? 1 : 4 / d.q;
+  while (r > 1 && d.rows % r) r >>= 1;
+  return r;
+}
+// the call covers whole grid rows (every segment of a logical row), and q wavefronts fit a workgroup
+bool ln_rowgroup_ok(const LnDesc& d) { return d.j0 == 0 && d.nj == d.q && d.q >= 1 && d.q <= 16; }
+
 template <typename T, int MODE>
 static int run(const void* X, const void* X2, const float* gamma, const float* beta, const float* rstd_in, const void* dres,
                void* Y, void* xhat, float* rstd_out, float* stats, const LnDesc& d, bool own_ready, hipStream_t stream) {
   bool ok = al16(X) && (!X2 || al16(X2)) && (!dres || al16(dres)) && (!Y || al16(Y)) && (!xhat || al16(xhat)) &&
             (!gamma || al16(gamma)) && (!beta || al16(beta));
   LnArgs a = make_args(d, ok, (int)sizeof(T));
+  if constexpr (MODE == 1 || MODE == 3) {
+    if (!own_ready && ln_rowgroup_ok(d)) {
+      const int rpw = ln_rowgroup_rows(d);
+      dim3 grid((unsigned)(d.rows / rpw), (unsigned)d.ni);
+      hipLaunchKernelGGL((ln_kernel<T, MODE, true>), grid, dim3(64 * d.q * rpw), 0, stream, (const T*)X, (const T*)X2, gamma, beta,
+                         rstd_in, (const T*)dres, (T*)Y, (T*)xhat, rstd_out, stats, a, 0);
+      return hip_launch_status();
+    }
+  }
   dim3 grid((unsigned)((d.rows + 3) / 4), (unsigned)(d.ni * d.nj));
   hipLaunchKernelGGL((ln_kernel<T, MODE>), grid, dim3(256), 0, stream, (const T*)X, (const T*)X2, gamma, beta, rstd_in,
                      (const T*)dres, (T*)Y, (T*)xhat, rstd_out, stats, a, own_ready ? 1 : 0);
