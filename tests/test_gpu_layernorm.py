@@ -25,8 +25,11 @@ def _inputs(seed, M, H, dtype):
     return x, gamma, beta, dy, dres
 
 
-# (M, H, q): vector path, ragged columns (scalar path), wide rows (re-read path), q = 1
-CASES = [(64, 512, 2), (36, 100, 2), (24, 8192 * 2, 2), (16, 96, 1), (48, 768, 4), (10, 4096, 1)]
+# (M, H, q): vector path, ragged columns (scalar path), wide rows (re-read path), q = 1; workgroups of 1, 2 and 4
+# rows per grid row (odd row counts), q = 3 and 8 wavefronts per row, and q = 32 (more wavefronts than a workgroup
+# holds: statistics kernel first, then the apply kernel)
+CASES = [(64, 512, 2), (36, 100, 2), (24, 8192 * 2, 2), (16, 96, 1), (48, 768, 4), (10, 4096, 1),
+         (18, 128, 2), (96, 384, 3), (40, 512, 8), (64, 1024, 32)]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
