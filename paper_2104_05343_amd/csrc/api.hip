@@ -56,7 +56,7 @@ GemmDesc summa_desc(int form, const void* A, const void* B, void* C, int64_t M, 
   d.act = epi ? epi->act : 0;
   d.sBias0 = Nb;
   if (is_grid(i, j)) {
-    d.nz1 = q; d.nz0 = q;
+    d.nz1 = q; d.nz0 = q; d.plan_for_batch = 1;
     d.A = A; d.B = B; d.C = C;
     d.bias = bias; d.pre_act = pre; d.gelu_grad_of = gg; d.residual = res;
   } else {

@@ -86,6 +86,10 @@ struct GemmDesc {
   // 0: the product has the chip to itself; 1 / 2: it is one of two products that the layer's backward pass runs
   // side by side on two streams (1: activation-gradient chain, 2: parameter-gradient branch)
   int corun;
+  // 1: the tile shape may be chosen for all nz0 * nz1 blocks of the launch (whole-grid launches of a product);
+  // 0: from one block's shape only (the batched products of attention: the planner's cost model is calibrated on
+  // dense products and mispredicts their diagonal-trimmed, short-k shapes)
+  int plan_for_batch;
 };
 
 int launch_gemm(const GemmDesc& d, hipStream_t stream);           // picks MFMA or generic kernel

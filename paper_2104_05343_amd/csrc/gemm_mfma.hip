@@ -1060,15 +1060,23 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
   const float out_mib = (float)d.Mb * (float)d.Nb * 2.0f / 1048576.0f;
   float best_cost = 0.f;
   bool found = false;
+  // Two passes.  The panel split changes the order in which a result is added up, so it is chosen from ONE block's
+  // shape (pass 0).  The tile shape does not (every element walks the same slabs in the same order whatever tile it
+  // lies in: the variants give identical bits, which the tests check), so a launch that covers several blocks
+  // (the whole grid, the matrices of a batch of heads) then picks its tile for the workgroups it really has (pass 1).
+  const long long batch = d.plan_for_batch ? (long long)(d.nz0 > 0 ? d.nz0 : 1) * (d.nz1 > 0 ? d.nz1 : 1) : 1;
+  for (int pass = 0; pass < (batch > 1 ? 2 : 1); ++pass) {
+  const int fixed_sp = pass == 0 ? 0 : best.splits;
+  if (pass == 1) found = false;
   for (int ci = 0; ci < 6; ++ci) {
     const Cand& c = cand[ci];
     const int v = c.v;
     if (g_variant >= 0 && g_variant != kGuardVariant && v != (g_variant == 4 ? 0 : g_variant)) continue;
     if (d.corun > 0 && g_corun_variant[d.corun - 1] >= 0 && v != g_corun_variant[d.corun - 1]) continue;
     if (!variant_fits(kVariants[v], d)) continue;
-    const long long tiles = (long long)(d.Mb / kVariants[v].BM) * (d.Nb / kVariants[v].BN);
-    for (int sp = 1; sp <= 8; ++sp) {
-      if (sp > 1 && (!splittable || slabs / sp < 8)) break;
+    const long long tiles = (long long)(d.Mb / kVariants[v].BM) * (d.Nb / kVariants[v].BN) * (pass == 0 ? 1 : batch);
+    for (int sp = fixed_sp ? fixed_sp : 1; sp <= (fixed_sp ? fixed_sp : 8); ++sp) {
+      if (!fixed_sp && sp > 1 && (!splittable || slabs / sp < 8)) break;
       const long long wgs = tiles * sp;
       const long long cap = 256LL * c.per_cu;
       const long long rounds = (wgs + cap - 1) / cap;
@@ -1079,7 +1087,7 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
       const float per_wg = (float)((((slabs + sp - 1) / sp) + 1) & ~1LL) * t_slab;
       // split: the combine launch, and the fp32 partial tiles read back by it (their writes overlap the products)
       const float traffic_us = sp > 1 ? 4.0f + (float)sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f : 0.f;
-      float cost = c.fixed_us + c.out_us_per_mib * out_mib + (float)rounds * per_wg + traffic_us;
+      float cost = c.fixed_us + c.out_us_per_mib * out_mib * (pass == 0 ? 1.0f : (float)batch) + (float)rounds * per_wg + traffic_us;
       // Two products that run side by side on two streams (the pairs of the layer's backward pass) overlap only if
       // workgroups of both fit on one CU: the 8-wavefront tiles take a CU's LDS and registers alone, so such a pair
       // runs one after the other, while the 4-wavefront tiles of the two kernels share the CUs.  Measured on the
@@ -1092,6 +1100,7 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
         best = {v, sp};
       }
     }
+  }
   }
   return best;
 }

@@ -141,6 +141,47 @@ def test_every_tile_variant(form, variant):
     _check_blocks(dC, want, M, N, q, TOL["bf16"])
 
 
+@pytest.mark.parametrize("mb,kp,nb,with_ws", [(512, 256, 768, False), (256, 2048, 256, True)], ids=["wide", "long_k_split"])
+@pytest.mark.parametrize("form", FORMS)
+def test_tile_variants_give_identical_bits_and_grid_equals_device(form, mb, kp, nb, with_ws):
+    """The planner picks the panel split from one block's shape, but the tile shape for the workgroups a launch really
+    has (a whole-grid launch has q*q blocks).  That keeps grid mode = device mode bit for bit because an element walks
+    the same slabs in the same order whatever tile it lies in: every fast tile variant gives the same bits, and so do
+    the whole-grid launch and the q*q single-device launches (which choose different tiles)."""
+    q = 2
+    M, K, N = mb * q, kp * q, nb * q
+    A, B = gemm_inputs(57, form, M, K, N, "bf16", "n1", "n1")
+    ws = None
+    if with_ws:   # the planned panel split needs its workspace: the larger of the two modes' requests
+        nbytes = max(opt.summa_workspace_bytes(form, M, K, N, q, -1, -1, opt.BF16), opt.summa_workspace_bytes(form, M, K, N, q, 0, 1, opt.BF16))
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
+    ref = None
+    plans = set()
+    if not with_ws:   # (a forced variant plans its own split: compare the variants without one)
+        try:
+            for variant in (0, 1, 2, 3, 6, 7):
+                opt.debug_set_gemm_variant(variant)
+                dC = _run(form, A, B, M, K, N, q, "bf16")
+                plans.add(opt.binding.debug_last_gemm_plan()[0])
+                ref = dC if ref is None else ref
+                assert torch.equal(dC.view(torch.int16), ref.view(torch.int16)), variant
+        finally:
+            opt.debug_set_gemm_variant(-1)
+        assert len(plans) == 6          # six different tile shapes were really used
+    grid = _run(form, A, B, M, K, N, q, "bf16", ws=ws)
+    grid_plan = opt.binding.debug_last_gemm_plan()
+    ref = grid if ref is None else ref
+    dev = empty(M * N, "bf16")
+    dev_plans = set()
+    for i in range(q):
+        for j in range(q):
+            _run(form, A, B, M, K, N, q, "bf16", i, j, ws=ws, out=dev)
+            dev_plans.add(opt.binding.debug_last_gemm_plan())
+    assert torch.equal(grid.view(torch.int16), dev.view(torch.int16)) and torch.equal(grid.view(torch.int16), ref.view(torch.int16))
+    print("grid plan", grid_plan, "device plans", dev_plans)
+    assert all(p[1] == grid_plan[1] for p in dev_plans)   # the same panel split in both modes
+
+
 def test_closed_forms_and_identities():
     q, n = 2, 256
     I = np.eye(n, dtype=np.float32)
