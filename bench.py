@@ -240,7 +240,7 @@ def time_stack(opt, torch, harness, cfg, T, b, s, h, n, q, layers, reps):
     fwd_ms = event_time_ms(lambda: opt.stack_fwd(cfg, P, T["x"], buf, out_t), reps)
     bwd_ms = event_time_ms(lambda: opt.stack_bwd(cfg, P, G, T["d_out"], buf, dx_t), reps)
     lt = opt.make_layer_tensors(T)
-    ws = torch.empty(opt.layer_workspace_bytes(cfg), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(opt.layer_workspace_bytes_grid(cfg), dtype=torch.uint8, device="cuda:0")   # the stack's own size
     lf_ms = event_time_ms(lambda: opt.layer_fwd(cfg, lt, -1, -1, ws), reps)
     lb_ms = event_time_ms(lambda: opt.layer_bwd(cfg, lt, -1, -1, ws), reps)
     kept = layers * (sz.forward + M * h * 2) + sz.backward + sz.conjunction + sz.workspace + sz.param_grad
@@ -493,6 +493,11 @@ def main():
         out["model_ends"] = time_model_ends(opt, torch, b, s, h, q, di, dj, 32768, args.gemm_reps, 9)
     if not args.no_sweep and args.workload == "config2":
         out["stack"] = time_stack(opt, torch, harness, cfg, T, b, s, h, n, q, layers=4, reps=max(3, args.steps // 10))
+        if (h // n) in (64, 128):
+            cfg_f, T_f, _, _ = harness.alloc_layer(bits, vecs, b, s, h, n, q, causal=True, fused_attention=True, share=T)
+            out["stack_fused_attention"] = time_stack(opt, torch, harness, cfg_f, T_f, b, s, h, n, q, layers=4,
+                                                      reps=max(3, args.steps // 10))
+            del T_f
     if not args.no_sweep and args.workload == "config2":
         # whole-step figures of the larger layers (the same measurement as `value`, fewer replays)
         out["other_workload_steps"] = [time_layer_step(opt, torch, harness, name, max(10, args.steps // 2), args.warmup)

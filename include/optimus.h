@@ -184,7 +184,9 @@ int optimus_layernorm2d_bwd(const void* dY, const void* xhat, const float* rstd,
  * the diagonal are exact zeros when causal); attn: block-major [b*s x h].
  * Backward: dV = P^T dO, dP = dO V^T, dS = P*(dP - rowsum(dP*P)),
  * dQ = dS K / sqrt(d), dK = dS^T Q / sqrt(d); d_qkv has qkv's layout.
- * ws must hold optimus_attention_workspace_bytes(...) bytes. bf16 only.
+ * ws must hold optimus_attention_workspace_bytes(...) bytes (scratch for one
+ * device's scores); a whole-grid call (i = j = -1) takes g devices per launch
+ * when ws holds g times that (same bits, fewer and larger launches). bf16 only.
  * Requires q | b, q | n, n | h, d % 8 == 0, s % 8 == 0. */
 int optimus_attention_fwd(const void* qkv, void* probs, void* attn, int b, int s, int h, int n, int q,
                           int i, int j, int causal, int dtype, void* ws, size_t ws_bytes, void* stream);
@@ -281,6 +283,11 @@ typedef struct {
  * optimus_layer_bwd must not be called from several host threads at once
  * for the same device.) */
 size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg);
+/* The size to give whole-grid calls (i = j = -1) that should run fast: the minimum above plus attention scratch
+ * for more devices, so that the unfused attention of several devices is one batch per launch instead of one device
+ * after the other (as many as stay inside the 256 MB Infinity Cache, at least one).  optimus_layer_fwd / _bwd use
+ * whatever `ws_bytes` holds beyond the products' regions for this; the results do not depend on it, bit for bit. */
+size_t optimus_layer_workspace_bytes_grid(const optimus_layer_cfg* cfg);
 int optimus_layer_fwd(const optimus_layer_cfg* cfg, const optimus_layer_tensors* t, int i, int j,
                       void* ws, size_t ws_bytes, void* stream);
 int optimus_layer_bwd(const optimus_layer_cfg* cfg, const optimus_layer_tensors* t, int i, int j,

@@ -113,6 +113,7 @@ SIGNATURES = {
     "optimus_stack_bwd": (_INT, [C.POINTER(LayerCfg), _INT, C.POINTER(LayerParams), C.POINTER(LayerGrads), _P,
                                  C.POINTER(StackBuffers), _P, LAYER_DONE_FN, _P, _P]),
     "optimus_layer_workspace_bytes": (_SZ, [C.POINTER(LayerCfg)]),
+    "optimus_layer_workspace_bytes_grid": (_SZ, [C.POINTER(LayerCfg)]),
     "optimus_layer_fwd": (_INT, [C.POINTER(LayerCfg), C.POINTER(LayerTensors), _INT, _INT, _P, _SZ, _P]),
     "optimus_layer_bwd": (_INT, [C.POINTER(LayerCfg), C.POINTER(LayerTensors), _INT, _INT, _P, _SZ, _P]),
     "optimus_gemm_flops": (_I64, [_I64, _I64, _I64, _INT]),
@@ -284,6 +285,10 @@ def attention_fused_bwd(qkv, attn, lse, d_attn, d_qkv, b, s, h, n, q, i, j, caus
 
 def layer_workspace_bytes(cfg: LayerCfg) -> int:
     return lib().optimus_layer_workspace_bytes(C.byref(cfg))
+
+
+def layer_workspace_bytes_grid(cfg: LayerCfg) -> int:
+    return lib().optimus_layer_workspace_bytes_grid(C.byref(cfg))
 
 
 def make_layer_tensors(tensors: dict) -> LayerTensors:

@@ -207,20 +207,27 @@ int run_attention(bool bwd, const void* qkv, const void* probs_in, void* probs_o
   if (rc) return rc;
   if ((rc = check_coords(q, i, j))) return rc;
   if (!ws || ws_bytes < attn_ws_bytes(a)) return OPTIMUS_EWORKSPACE;
-  const int i0 = is_grid(i, j) ? 0 : i, i1 = is_grid(i, j) ? q : i + 1;
-  const int j0 = is_grid(i, j) ? 0 : j, j1 = is_grid(i, j) ? q : j + 1;
-  for (int di = i0; di < i1; ++di)
-    for (int dj = j0; dj < j1; ++dj) {
-      const long long dev = (long long)di * q + dj;
-      const bf16_t* qb = (const bf16_t*)qkv + dev * a.blk_qkv;
-      if (!bwd)
-        rc = attention_fwd_device(qb, (bf16_t*)probs_out + dev * a.blk_probs, (bf16_t*)out + dev * a.blk_attn, a, causal, ws,
-                                  as_stream(stream));
-      else
-        rc = attention_bwd_device(qb, (const bf16_t*)probs_in + dev * a.blk_probs, (const bf16_t*)d_attn + dev * a.blk_attn,
-                                  (bf16_t*)out + dev * a.blk_qkv, a, causal, ws, as_stream(stream));
-      if (rc) return rc;
-    }
+  // Whole grid: the blocks of consecutive devices follow each other in every tensor, and inside a block the
+  // sequences do too, so g devices are one batch of g * (b/q) sequences with the same strides.  As many devices per
+  // launch as the workspace holds scratch for (one device's worth is the minimum: then device after device).
+  const long long first = is_grid(i, j) ? 0 : (long long)i * q + j;
+  const long long ndev = is_grid(i, j) ? (long long)q * q : 1;
+  long long group = (long long)(ws_bytes / attn_ws_bytes(a));
+  if (group > ndev) group = ndev;
+  if (group > 0x7fffffffLL / (a.nmat > 0 ? a.nmat : 1)) group = 0x7fffffffLL / a.nmat;   // batch counts are ints
+  for (long long dev = first; dev < first + ndev; dev += group) {
+    const long long g = dev + group <= first + ndev ? group : first + ndev - dev;
+    AttnDims ag = a;
+    ag.nb = (int)(a.nb * g); ag.nmat = a.nmat * g; ag.blk_probs = a.blk_probs * g;
+    const bf16_t* qb = (const bf16_t*)qkv + dev * a.blk_qkv;
+    if (!bwd)
+      rc = attention_fwd_device(qb, (bf16_t*)probs_out + dev * a.blk_probs, (bf16_t*)out + dev * a.blk_attn, ag, causal, ws,
+                                as_stream(stream));
+    else
+      rc = attention_bwd_device(qb, (const bf16_t*)probs_in + dev * a.blk_probs, (const bf16_t*)d_attn + dev * a.blk_attn,
+                                (bf16_t*)out + dev * a.blk_qkv, ag, causal, ws, as_stream(stream));
+    if (rc) return rc;
+  }
   return OPTIMUS_OK;
 }
 
@@ -646,6 +653,19 @@ size_t optimus_layer_workspace_bytes(const optimus_layer_cfg* cfg) {
   return layer_attn_ws(cfg, a) + 2 * layer_gemm_ws(cfg);
 }
 
+size_t optimus_layer_workspace_bytes_grid(const optimus_layer_cfg* cfg) {
+  const size_t base = optimus_layer_workspace_bytes(cfg);
+  AttnDims a;
+  if (base == 0 || cfg->fused_attention || layer_check(cfg, 0, 0, &a)) return base;
+  // scratch for as many devices' attention per launch as stay inside the 256 MB Infinity Cache (at least one)
+  const size_t one = attn_ws_bytes(a);
+  size_t g = ((size_t)256 << 20) / one;
+  const size_t all = (size_t)cfg->q * cfg->q;
+  if (g > all) g = all;
+  if (g < 1) g = 1;
+  return base + (g - 1) * one;
+}
+
 }  // extern "C"
 
 // The forward pass; with skip_out the last product (out = h_mid + gelu W2 + b2) is left out: no gradient needs it, so a
@@ -667,10 +687,11 @@ int optimus::layer_forward(const optimus_layer_cfg* c, const optimus_layer_tenso
   const int64_t M = (int64_t)c->b * c->s, h = c->h;
   const bool grid = is_grid(i, j);
   hipStream_t st = as_stream(stream);
-  void* attn_ws = ws;
-  const size_t attn_bytes = layer_attn_ws(c, a);
-  void* gemm_ws = (char*)ws + attn_bytes;
+  // workspace: [products, chain][products, branch][attention: everything that is left]
+  void* gemm_ws = ws;
   const size_t gemm_bytes = layer_gemm_ws(c);
+  void* attn_ws = (char*)ws + 2 * gemm_bytes;
+  const size_t attn_bytes = ws_bytes - 2 * gemm_bytes;
   LnDesc ln;
   if ((rc = ln_desc(M, h, q, i, j, dt, c->eps, &ln))) return rc;
   // a1 = LN1(x)
@@ -723,10 +744,11 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   const int64_t M = (int64_t)c->b * c->s, h = c->h;
   const bool grid = is_grid(i, j);
   hipStream_t st = as_stream(stream);
-  void* attn_ws = ws;
-  const size_t attn_bytes = layer_attn_ws(c, a);
-  void* gemm_ws = (char*)ws + attn_bytes;
+  // workspace: [products, chain][products, branch][attention: everything that is left]
+  void* gemm_ws = ws;
   const size_t gemm_bytes = layer_gemm_ws(c);
+  void* attn_ws = (char*)ws + 2 * gemm_bytes;
+  const size_t attn_bytes = ws_bytes - 2 * gemm_bytes;
   LnDesc ln;
   if ((rc = ln_desc(M, h, q, i, j, dt, c->eps, &ln))) return rc;
   // gradient branch: its own stream and its own split workspace (see SideStream)

@@ -107,7 +107,7 @@ int optimus_stack_sizes_of(const optimus_layer_cfg* cfg, int n_layers, optimus_s
   if (rc) return rc;
   if (!out) return OPTIMUS_EINVAL;
   if (n_layers < 1 || n_layers > 65536) return OPTIMUS_ESHAPE;
-  out->workspace = optimus_layer_workspace_bytes(cfg);
+  out->workspace = optimus_layer_workspace_bytes_grid(cfg);   // the stack runs the whole grid
   out->forward = carve_forward(cfg, d, nullptr, nullptr);
   out->backward = carve_backward(d, nullptr, nullptr);
   out->param_grad = carve_grads(d, nullptr, nullptr);
@@ -136,7 +136,7 @@ int optimus_stack_fwd(const optimus_layer_cfg* cfg, int n_layers, const optimus_
     if (!params_ok(params[l])) return OPTIMUS_EINVAL;
   char* ck = (char*)buf->checkpoint;
   if (hipMemcpyAsync(ck, x, d.act, hipMemcpyDeviceToDevice, (hipStream_t)stream) != hipSuccess) return OPTIMUS_EHIP;
-  const size_t ws_bytes = optimus_layer_workspace_bytes(cfg);
+  const size_t ws_bytes = optimus_layer_workspace_bytes_grid(cfg);
   for (int l = 0; l < n_layers; ++l) {
     optimus_layer_tensors t = {};
     carve_forward(cfg, d, buf->forward, &t);
@@ -160,7 +160,7 @@ int optimus_stack_bwd(const optimus_layer_cfg* cfg, int n_layers, const optimus_
     return OPTIMUS_EINVAL;
   for (int l = 0; l < n_layers; ++l)
     if (!params_ok(params[l]) || !grads_ok(grads[l])) return OPTIMUS_EINVAL;
-  const size_t ws_bytes = optimus_layer_workspace_bytes(cfg);
+  const size_t ws_bytes = optimus_layer_workspace_bytes_grid(cfg);
   const size_t slot = (d.act + 255) & ~(size_t)255;
   const char* ck = (const char*)buf->checkpoint;
   const void* g_in = d_out;

@@ -72,11 +72,17 @@ def test_stack_sizes_host_only():
     act = 8 * 512 * 1024 * 2
     sz = opt.stack_sizes(cfg, 24)
     assert sz.checkpoint == 24 * act and sz.conjunction == 2 * act
-    assert sz.workspace == opt.layer_workspace_bytes(cfg)
+    # the stack runs the whole grid: its workspace is the layer's whole-grid size = the minimum plus attention scratch
+    # for 15 more devices (8 matrices of 512 x 512, fp32 scores + bf16 gradient each; all 16 fit in 256 MiB)
+    one = 8 * 512 * 512 * (4 + 2)
+    assert sz.workspace == opt.layer_workspace_bytes_grid(cfg) == opt.layer_workspace_bytes(cfg) + 15 * one
+    big = opt.LayerCfg(8, 1024, 4096, 32, 4, 1e-5, 1, opt.BF16)   # 16 matrices of 1024 x 1024 per device: two devices fit
+    assert opt.layer_workspace_bytes_grid(big) == opt.layer_workspace_bytes(big) + 16 * 1024 * 1024 * 6
     assert sz.forward >= 12 * act + 16 * 2 * 4 * 512 * 512 * 2        # 12 activation-sized units + probabilities
     assert sz.backward >= 11 * act and sz.param_grad >= 12 * 1024 * 1024 * 4
     fused = opt.LayerCfg(8, 512, 1024, 16, 4, 1e-5, 1, opt.BF16, 1)
     assert opt.stack_sizes(fused, 24).forward < sz.forward
+    assert opt.layer_workspace_bytes_grid(fused) == opt.layer_workspace_bytes(fused)   # no score scratch to batch
     for bad_cfg, L in ((opt.LayerCfg(3, 64, 128, 4, 2, 1e-5, 1, opt.BF16), 2), (cfg, 0)):
         with pytest.raises(opt.OptimusError) as e:
             opt.stack_sizes(bad_cfg, L)

@@ -88,6 +88,30 @@ def test_attention_forward_backward(b, s, h, n, q, causal):
     assert np.all(np.isnan(a1[mask]))
 
 
+@pytest.mark.parametrize("b,s,h,n,q,devices", [(4, 136, 128, 8, 4, 16), (4, 136, 128, 8, 4, 5), (2, 328, 256, 2, 2, 3)])
+def test_whole_grid_in_batches_of_devices_same_bits(b, s, h, n, q, devices):
+    """With scratch for g devices a whole-grid call takes g devices per launch (g = all of them, or a count that
+    leaves a shorter last group): forward and backward give the bits of the device-after-device run."""
+    rng = np.random.default_rng(s + devices)
+    M = b * s
+    qkv = round_to_bf16(rng.standard_normal((M, 3 * h)).astype(np.float32))
+    d_attn = round_to_bf16(rng.standard_normal((M, h)).astype(np.float32))
+    dQKV, dO = mat_to_dev(qkv, q, "bf16"), mat_to_dev(d_attn, q, "bf16")
+    nmat = (b // q) * (n // q)
+    one = opt.attention_workspace_bytes(b, s, h, n, q)
+    res = []
+    for g in (1, devices):
+        ws = torch.empty(g * one, dtype=torch.uint8, device="cuda:0")
+        P, O, dQ = empty(q * q * nmat * s * s, "bf16"), empty(M * h, "bf16"), empty(M * 3 * h, "bf16")
+        opt.attention_fwd(dQKV, P, O, b, s, h, n, q, -1, -1, True, opt.BF16, ws)
+        opt.attention_bwd(dQKV, P, dO, dQ, b, s, h, n, q, -1, -1, True, opt.BF16, ws)
+        torch.cuda.synchronize()
+        res.append((P, O, dQ))
+    for x, y in zip(res[0], res[1]):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+    assert not torch.isnan(res[1][2].float()).any()
+
+
 def test_attention_closed_forms():
     """Q = 0 gives uniform weights over the visible prefix: O_t = mean(V_0..t); constant V gives O = V."""
     b, s, h, n, q = 2, 128, 64, 2, 1
