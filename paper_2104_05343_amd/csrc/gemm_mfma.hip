@@ -1092,8 +1092,9 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
       // workgroups of both fit on one CU: the 8-wavefront tiles take a CU's LDS and registers alone, so such a pair
       // runs one after the other, while the 4-wavefront tiles of the two kernels share the CUs.  Measured on the
       // backward pass of the 4096-wide layers: 128x128 tiles for the chain 0.69 -> 0.57 ms and 0.71 -> 0.62 ms,
-      // although each product alone is faster with 256x128 tiles; no difference for the small layer.
-      if (d.corun > 0 && c.per_cu >= 2) cost *= 0.78f;
+      // although each product alone is faster with 256x128 tiles; no difference for the small layer.  A whole-grid
+      // launch (pass 1) fills the chip by itself, and there the larger tiles win (4-layer stack backward 3.17 -> 3.06 ms).
+      if (d.corun > 0 && c.per_cu >= 2 && pass == 0) cost *= 0.78f;
       if (!found || cost < best_cost) {
         found = true;
         best_cost = cost;
