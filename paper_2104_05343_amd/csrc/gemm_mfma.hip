@@ -1031,8 +1031,9 @@ static bool variant_fits(const Variant& v, const GemmDesc& d) {
   return 512 * ld < (1LL << 30) && 2 * (long long)d.Kp * ld < (1LL << 30);
 }
 
-// Tile shape and panel split for one product.  The choice looks at ONE device's block only (never at the batch
-// count), so that grid mode and device mode add the same slabs in the same order and give identical bits.
+// Tile shape and panel split for one product.  The split is chosen from ONE device's block only (never from the
+// batch count), so that grid mode and device mode add the same slabs in the same order and give identical bits; the
+// tile shape changes no bit and may be chosen for the whole launch (GemmDesc::plan_for_batch, see make_plan).
 // Cost model (microseconds, calibrated on MI355X): fixed launch/prologue/epilogue cost, plus the slabs one
 // workgroup walks times the measured time per slab of the variant, times the rounds needed to place all
 // workgroups; a split adds the combine launch and the fp32 partial tiles written once and read once.
