@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="config2", choices=["config2", "config4", "config5"])
     ap.add_argument("--device-coords", default="1,2", help="device (i,j) whose share is timed")
     ap.add_argument("--gemm-reps", type=int, default=50)
@@ -74,6 +74,32 @@ def capture(fn, reps):
             for _ in range(reps):
                 fn()
         return eager, False
+
+
+LAUNCH_GRAPH = "HIP graph replay, 10 steps per graph"
+STEPS_PER_GRAPH = 10   # a replay costs about 9 us on top of its kernels: amortised as a multi-layer model would
+
+
+def time_steps(step, steps, warmup):
+    """W untimed and exactly K timed calls of step(), replayed from HIP graphs of STEPS_PER_GRAPH steps each (the
+    remainder from a one-step graph), between two synchronisations.  Returns (ms per step, graphed?)."""
+    import torch
+    run1, graphed = capture(step, 1)
+    runN = capture(step, STEPS_PER_GRAPH)[0] if graphed and steps >= STEPS_PER_GRAPH else None
+
+    def go(k):
+        if runN is not None:
+            for _ in range(k // STEPS_PER_GRAPH):
+                runN()
+            k %= STEPS_PER_GRAPH
+        for _ in range(k):
+            run1()
+    go(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    go(steps)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps, graphed
 
 
 def event_time_ms(fn, reps, warm=1):
@@ -324,20 +350,12 @@ def time_layer_step(opt, torch, harness, name, steps, warmup):
         def step():
             opt.layer_fwd(cfg, lt, di, dj, ws)
             opt.layer_bwd(cfg, lt, di, dj, ws)
-        run, graphed = capture(step, 1)
-        for _ in range(warmup):
-            run()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            run()
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
+        ms, graphed = time_steps(step, steps, warmup)
         key = "fused_attention" if fused else "unfused_attention"
         res[key] = {"ms_per_step": round(ms, 4), "tflops": round(summa_flops / (ms * 1e-3) / 1e12, 1),
                     "pct_of_bf16_mfma_peak": round(100 * summa_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
-                    "launch": "HIP graph replay" if graphed else "eager launches"}
-        del run, lt, ws
+                    "launch": LAUNCH_GRAPH if graphed else "eager launches"}
+        del lt, ws
         if fused:
             del T
     return res
@@ -399,18 +417,9 @@ def main():
         opt.layer_fwd(cfg, lt, di, dj, ws)
         opt.layer_bwd(cfg, lt, di, dj, ws)
 
-    # the step is launch-bound when issued from Python (about 45 small kernels): replay it from a HIP graph,
-    # as a training loop would; W warm-up replays, then exactly K timed replays between two synchronisations
-    run_step, graphed = capture(step, 1)
-    for _ in range(args.warmup):
-        run_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # the step is launch-bound when issued from Python (37 small kernels, two streams): replay it from a HIP graph,
+    # as a training loop would; W warm-up steps, then exactly K timed steps between two synchronisations
+    ms_per_step, graphed = time_steps(step, args.steps, args.warmup)
 
     # the same step with the attention that keeps no [s x s] tensor (cfg.fused_attention = 1), reported beside it
     fused_step = None
@@ -423,18 +432,11 @@ def main():
         def step_f():
             opt.layer_fwd(cfg_f, lt_f, di, dj, ws_f)
             opt.layer_bwd(cfg_f, lt_f, di, dj, ws_f)
-        run_f, graphed_f = capture(step_f, 1)
-        for _ in range(args.warmup):
-            run_f()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            run_f()
-        torch.cuda.synchronize()
-        fused_step = {"ms_per_step": round((time.perf_counter() - t0) * 1e3 / args.steps, 4),
-                      "launch": "HIP graph replay" if graphed_f else "eager launches",
+        ms_f, graphed_f = time_steps(step_f, args.steps, args.warmup)
+        fused_step = {"ms_per_step": round(ms_f, 4),
+                      "launch": LAUNCH_GRAPH if graphed_f else "eager launches",
                       "what": "same layer step with cfg.fused_attention = 1 (no probs tensor; lse saved)"}
-        del T_f, lt_f, ws_f, run_f
+        del T_f, lt_f, ws_f
 
     gemms = layer_gemm_list(b, s, h)
     summa_flops = sum(opt.gemm_flops(M, K, N, q) for (_, _, M, K, N) in gemms)
@@ -475,7 +477,7 @@ def main():
         "config": {"workload": f"{args.workload}: one device ({di},{dj}) of a q={q} grid, layer fwd+bwd, b={b} s={s} h={h} n={n}, causal",
                    "q": q, "device": [di, dj], "b": b, "s": s, "h": h, "heads": n,
                    "step": "optimus_layer_fwd + optimus_layer_bwd (device mode, peers resident)",
-                   "launch": "HIP graph replay" if graphed else "eager launches"},
+                   "launch": LAUNCH_GRAPH if graphed else "eager launches"},
         "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
         "roofline": roofline,
         "step_detail": {"summa_flops_per_step": summa_flops, "layer_flops_per_step_table1": layer_flops,
