@@ -216,8 +216,9 @@ def test_layer_config2_full_size():
         torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("shp", [LayerShape(b=4, s=64, h=128, n=4, q=2), LayerShape(b=8, s=1024, h=2048, n=16, q=2)],
-                         ids=["small_blocks", "large_blocks"])
+@pytest.mark.parametrize("shp", [LayerShape(b=4, s=64, h=128, n=4, q=2), LayerShape(b=8, s=1024, h=2048, n=16, q=2),
+                                 LayerShape(b=8, s=512, h=1024, n=16, q=4)],
+                         ids=["small_blocks", "large_blocks", "config2_panel_split"])
 def test_layer_layernorm_parameter_gradients_equal_the_standalone_call(shp):
     """The layer runs the LayerNorm parameter gradients on either of its two streams depending on the block size
     ([128 x 64]: the gradient branch; [4096 x 1024]: the activation chain).  Wherever they run, they are the column
@@ -237,6 +238,26 @@ def test_layer_layernorm_parameter_gradients_equal_the_standalone_call(shp):
         assert np.array_equal(to_host(dg), to_host(T["d_ln%s_g" % k])), k
         assert np.array_equal(to_host(db), to_host(T["d_ln%s_b" % k])), k
         assert np.array_equal(to_host(dx), to_host(T["d_h_mid" if k == "2" else "d_x"])), k
+    # The dY the two LayerNorm backward kernels read is the layer's own product (planned as one of two products that
+    # run side by side, panel-split at config 2): it has the bits of the standalone product on the same stored
+    # operands, and a single device's backward pass reproduces the grid run's bits.
+    for dy, a_name, w_name, K in (("d_ln2_out", "d_pre_gelu", "w1", 4 * h), ("d_ln1_out", "d_qkv", "w_qkv", 3 * h)):
+        nbytes = max(opt.summa_workspace_bytes("abt", M, K, h, q, -1, -1, opt.BF16), opt.summa_workspace_bytes("abt", M, K, h, q, 0, 0, opt.BF16))
+        ws2 = torch.empty(max(256, nbytes), dtype=torch.uint8, device="cuda:0")
+        Cm = torch.empty_like(T[dy])
+        opt.summa("abt", T[a_name], T[w_name], Cm, M, K, h, q, -1, -1, opt.BF16, ws=ws2)
+        torch.cuda.synchronize()
+        print(dy, "standalone plan (variant, splits):", opt.binding.debug_last_gemm_plan())
+        assert torch.equal(Cm.view(torch.int16), T[dy].view(torch.int16)), dy
+    snap = {k_: v.clone() for k_, v in T.items()}
+    i, j = q - 1, 0
+    for k_ in ("d_ln2_out", "d_ln1_out", "d_h_mid", "d_x"):
+        blk = (M // q) * (h // q)
+        T[k_][(i * q + j) * blk:(i * q + j + 1) * blk] = float("nan")
+    opt.layer_bwd(cfg, lt, i, j, ws)
+    torch.cuda.synchronize()
+    for k_, v in T.items():
+        assert torch.equal(v.view(torch.uint8), snap[k_].view(torch.uint8)), k_
 
 
 def test_layer_errors():
