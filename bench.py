@@ -337,12 +337,13 @@ def time_layer_step(opt, torch, harness, name, steps, warmup):
     del inp
     res = {"workload": f"{name}: one device ({di},{dj}) of a q={q} grid, layer fwd+bwd, b={b} s={s} h={h} n={n}, causal"}
     summa_flops = sum(opt.gemm_flops(M, K, N, q) for (_, _, M, K, N) in layer_gemm_list(b, s, h))
-    T0 = None
+    T0 = cfg0 = None
     for fused in (False, True):
         if fused and (h // n) not in (64, 128):
             break
         cfg, T, lt, ws = harness.alloc_layer(bits, vecs, b, s, h, n, q, causal=True, fused_attention=fused, share=T0)
         T0 = T0 or T
+        cfg0 = cfg0 or cfg
         opt.layer_fwd(cfg, lt, -1, -1, ws)   # untimed grid-mode pass: every peer block resident
         opt.layer_bwd(cfg, lt, -1, -1, ws)
         torch.cuda.synchronize()
@@ -358,6 +359,13 @@ def time_layer_step(opt, torch, harness, name, steps, warmup):
         del lt, ws
         if fused:
             del T
+    if name == "config4":   # the checkpointed stack at a size where the products dominate (whole grid on the one GPU)
+        st = time_stack(opt, torch, harness, cfg0, T0, b, s, h, n, q, layers=2, reps=3)
+        # per layer and device: forward, recomputation without the last product (a third of the forward flops), backward
+        # (twice the forward): 11/3 forward passes = 11/9 of the step's product flops
+        fl = 2 * q * q * summa_flops * 11 // 9
+        st["summa_tflops_fwd_bwd_recompute"] = round(fl / ((st["fwd_ms"] + st["bwd_with_recompute_ms"]) * 1e-3) / 1e12, 1)
+        res["stack_2_layers"] = st
     return res
 
 
