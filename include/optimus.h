@@ -375,7 +375,8 @@ void optimus_debug_set_gemm_variant(int v);
  * activation-gradient chain (the four A B^T products), branch_v for the parameter-gradient branch (the four A^T B
  * products); -1 = automatic. */
 void optimus_debug_set_corun_variants(int chain_v, int branch_v);
-/* The plan of the most recent matrix-core product launched by this process: variant | (panel splits << 8);
+/* The plan of the most recent matrix-core product launched by this process: variant | (panel splits << 8) |
+ * (1 << 16 if the split is emulated inside each workgroup);
  * -1 before the first one.  Host state only, not synchronised between threads. */
 int optimus_debug_last_gemm_plan(void);
 

@@ -398,6 +398,6 @@ def debug_set_corun_variants(chain_v: int, branch_v: int) -> None:
 
 
 def debug_last_gemm_plan():
-    """(variant, panel splits) of the most recent matrix-core product."""
+    """(variant, panel splits, 1 if the split is emulated inside each workgroup) of the most recent matrix-core product."""
     p = lib().optimus_debug_last_gemm_plan()
-    return (p & 0xFF, p >> 8) if p >= 0 else None
+    return (p & 0xFF, (p >> 8) & 0xFF, p >> 16) if p >= 0 else None

@@ -67,6 +67,9 @@ struct KArgs {
   int skip_upper, k_hi_diag, k_lo_diag;
   int splits;
   float* partials;
+  // > 1 (with splits == 1): one workgroup walks all slabs but adds them up as `seq_splits` panel-split workgroups and
+  // their fixed-order combine would -- a fresh accumulator per range, the ranges' sums added in range order
+  int seq_splits;
   long long nz;  // total batch count
   EpiArgs epi;
 };
@@ -420,9 +423,10 @@ struct Occ {
 // PLAIN (FAST only) = the epilogue is a bare store of the accumulator (alpha 1, no bias / activation / residual):
 // a short, fully unrolled store sequence instead of the general epilogue, whose straight-line code costs
 // microseconds per tile.
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST, bool PLAIN>
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST, bool PLAIN, bool SEQ = false>
 __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gemm_mfma_kernel(const KArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
+  static_assert(!SEQ || (FAST && !PLAIN), "the range-wise accumulation exists on the fast path with the full epilogue");
   using T = Tile<BM, BN, WM, WN>;
   constexpr int THREADS = T::THREADS, NW = T::NW;
   constexpr int TM = T::TM, TN = T::TN, MI = T::MI, NI = T::NI;
@@ -495,6 +499,21 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
+  // SEQ: `tot` holds the sum of the finished ranges, `acc` the running range (see KArgs::seq_splits); ranges are cut
+  // exactly as the panel split cuts them
+  f32x16 tot[SEQ ? MI : 1][SEQ ? NI : 1];
+  int seq_per = 0, seq_next = 0;
+  if constexpr (SEQ) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tot[mi][ni][e] = 0.f;
+    const int total = t_hi - t_lo;
+    seq_per = (((total + a.seq_splits - 1) / a.seq_splits) + 1) & ~1;
+    seq_next = seq_per;
+  }
 
   const bf16_t* Atile = Az + (AKC ? (long long)m0 * a.lda : (long long)m0);
   const bf16_t* Btile = Bz + (BKC ? (long long)n0 * a.ldb : (long long)n0);
@@ -670,6 +689,21 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
     OPTIMUS_HALF(fa0, fb0, ((S) + 1) & 3, 0, fa1, fb1, true, S, 0, (G_ODD + 1) / 2, ((ST) || pend));              \
     ++i;                                                                                                          \
   } while (0)
+      // SEQ: a range ends in front of slab i (ranges are even, so only in front of even steps)
+#define OPTIMUS_RANGE_END()                                                        \
+  do {                                                                             \
+    if constexpr (SEQ) {                                                           \
+      if (i == seq_next) {                                                         \
+        _Pragma("unroll") for (int mi_ = 0; mi_ < MI; ++mi_)                       \
+          _Pragma("unroll") for (int ni_ = 0; ni_ < NI; ++ni_)                     \
+            _Pragma("unroll") for (int e_ = 0; e_ < 16; ++e_) {                    \
+              tot[mi_][ni_][e_] += acc[mi_][ni_][e_];                              \
+              acc[mi_][ni_][e_] = 0.f;                                             \
+            }                                                                      \
+        seq_next += seq_per;                                                       \
+      }                                                                            \
+    }                                                                              \
+  } while (0)
       // prologue: whole groups at once
       OPTIMUS_ISSUE_KC(0);
       OPTIMUS_ISSUE_KS(0);
@@ -686,22 +720,28 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
       load_frags<BM, BN, WM, WN, AKC, BKC>(fa0, fb0, ldsA, ldsB, 0, 0, wm, wn, lane);
       int i = 0;
       while (i + 4 <= nslab) {
+        OPTIMUS_RANGE_END();
         OPTIMUS_STEP_EVEN(0, 0);
         OPTIMUS_STEP_ODD(1, 0);
+        OPTIMUS_RANGE_END();
         OPTIMUS_STEP_EVEN(2, 0);
         OPTIMUS_STEP_ODD(3, 0);
         while (i + 8 <= nslab) {  // i >= 4 here
+          OPTIMUS_RANGE_END();
           OPTIMUS_STEP_EVEN(0, 1);
           OPTIMUS_STEP_ODD(1, 1);
+          OPTIMUS_RANGE_END();
           OPTIMUS_STEP_EVEN(2, 1);
           OPTIMUS_STEP_ODD(3, 1);
           pend = true;  // the last steady step opened a group
         }
       }
       if (i < nslab) {  // one pair left
+        OPTIMUS_RANGE_END();
         OPTIMUS_STEP_EVEN(0, 0);
         OPTIMUS_STEP_ODD(1, 0);
       }
+#undef OPTIMUS_RANGE_END
 #undef OPTIMUS_STEP_EVEN
 #undef OPTIMUS_STEP_ODD
 #undef OPTIMUS_HALF
@@ -742,6 +782,14 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
     }
   }
 
+  if constexpr (SEQ) {  // the last range joins the sum; the epilogue below works on `acc`
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[mi][ni][e] = tot[mi][ni][e] + acc[mi][ni][e];
+  }
   // ---- epilogue: lane holds row (lane%32), columns 8*g + 4*(lane/32) + 0..3 of each 32x32 tile ----
   if (a.splits > 1) {
     // raw fp32 partial tile; the combine kernel adds the splits in order and applies the epilogue
@@ -992,6 +1040,14 @@ constexpr int kGuardVariant = 5;
 template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST>
 static int launch_one(const KArgs& ka, long long nwg, hipStream_t stream) {
   const EpiArgs& e = ka.epi;
+  if constexpr (FAST && BM * BN < 256 * 256) {  // (the 256x256 tile has no registers for a second accumulator)
+    if (ka.seq_splits > 1) {
+      hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, AKC, BKC, true, false, true>), dim3((unsigned)nwg), dim3(WM * WN * 64), 0,
+                         stream, ka);
+      return hip_launch_status();
+    }
+  }
+  if (ka.seq_splits > 1) return OPTIMUS_EINVAL;
   const bool plain = FAST && ka.splits == 1 && e.alpha == 1.0f && !e.bias && !e.pre_act && !e.act && !e.gelu_grad_of && !e.residual;
   if (plain) {
     if constexpr (FAST)
@@ -1040,10 +1096,11 @@ static bool variant_fits(const Variant& v, const GemmDesc& d) {
 struct Plan {
   int variant;
   int splits;
+  int seq;  // 1: the split is emulated inside each workgroup (KArgs::seq_splits): same bits, no partial tiles, no combine
 };
 
 static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
-  Plan best = {kGuardVariant, 1};
+  Plan best = {kGuardVariant, 1, 0};
   if (!vec_ok || g_variant == kGuardVariant) return best;  // the fast kernels only have the vector epilogue
   // per candidate: variant id, workgroups resident per CU, fixed cost (launch, prologue, epilogue: us and us per MiB
   // of output), and the time per slab of one workgroup: alone on the chip (t_lone), with every CU holding one
@@ -1087,7 +1144,8 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
       const float t_slab = c.t_lone + (c.t_full - c.t_lone) * busy * busy + c.t_more * (float)(resident - 1);
       const float per_wg = (float)((((slabs + sp - 1) / sp) + 1) & ~1LL) * t_slab;
       // split: the combine launch, and the fp32 partial tiles read back by it (their writes overlap the products)
-      const float traffic_us = sp > 1 ? 4.0f + (float)sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f : 0.f;
+      const float traffic_us =
+          sp > 1 ? 4.0f + (float)sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f * (pass == 0 ? 1.0f : (float)batch) : 0.f;
       float cost = c.fixed_us + c.out_us_per_mib * out_mib * (pass == 0 ? 1.0f : (float)batch) + (float)rounds * per_wg + traffic_us;
       // Two products that run side by side on two streams (the pairs of the layer's backward pass) overlap only if
       // workgroups of both fit on one CU: the 8-wavefront tiles take a CU's LDS and registers alone, so such a pair
@@ -1099,7 +1157,21 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
       if (!found || cost < best_cost) {
         found = true;
         best_cost = cost;
-        best = {v, sp};
+        best = {v, sp, 0};
+      }
+      // A launch with many blocks has workgroups enough without the split: one workgroup then walks all the slabs of
+      // its tile and adds them up range by range as the split workgroups and their combine would (identical bits).
+      if (pass == 1 && sp > 1 && kVariants[v].BM * kVariants[v].BN < 256 * 256) {
+        const long long rounds1 = (tiles + cap - 1) / cap;
+        const long long in1 = tiles < cap ? tiles : cap;
+        const int res1 = (int)((in1 + 255) / 256);
+        const float busy1 = in1 >= 256 ? 1.0f : (float)in1 / 256.0f;
+        const float t1 = c.t_lone + (c.t_full - c.t_lone) * busy1 * busy1 + c.t_more * (float)(res1 - 1);
+        const float cost1 = c.fixed_us + c.out_us_per_mib * out_mib * (float)batch + (float)rounds1 * (float)slabs * t1;
+        if (cost1 < best_cost) {
+          best_cost = cost1;
+          best = {v, sp, 1};
+        }
       }
     }
   }
@@ -1129,7 +1201,7 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
   // d.splits > 1 means the caller provided the workspace that the planned split asked for
   const Plan plan = make_plan(d, vec_ok, d.splits > 1 && d.partials != nullptr);
   const int vi = plan.variant;
-  g_last_plan = plan.variant | (plan.splits << 8);
+  g_last_plan = plan.variant | (plan.splits << 8) | (plan.seq << 16);
   const Variant& v = kVariants[vi];
   KArgs ka;
   ka.A = (const bf16_t*)d.A;
@@ -1149,7 +1221,8 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
     ka.group = g;
   }
   ka.skip_upper = d.skip_upper; ka.k_hi_diag = d.k_hi_diag; ka.k_lo_diag = d.k_lo_diag;
-  ka.splits = plan.splits;
+  ka.splits = plan.seq ? 1 : plan.splits;
+  ka.seq_splits = plan.seq ? plan.splits : 1;
   ka.partials = d.partials;
   ka.nz = (long long)d.nz0 * d.nz1;
   EpiArgs& e = ka.epi;

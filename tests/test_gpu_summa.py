@@ -141,14 +141,16 @@ def test_every_tile_variant(form, variant):
     _check_blocks(dC, want, M, N, q, TOL["bf16"])
 
 
-@pytest.mark.parametrize("mb,kp,nb,with_ws", [(512, 256, 768, False), (256, 2048, 256, True)], ids=["wide", "long_k_split"])
+@pytest.mark.parametrize("q,mb,kp,nb,with_ws", [(2, 512, 256, 768, False), (2, 256, 2048, 256, True), (4, 1024, 1024, 256, True)],
+                         ids=["wide", "long_k_split", "config2_mlp_down"])
 @pytest.mark.parametrize("form", FORMS)
-def test_tile_variants_give_identical_bits_and_grid_equals_device(form, mb, kp, nb, with_ws):
+def test_tile_variants_give_identical_bits_and_grid_equals_device(form, q, mb, kp, nb, with_ws):
     """The planner picks the panel split from one block's shape, but the tile shape for the workgroups a launch really
     has (a whole-grid launch has q*q blocks).  That keeps grid mode = device mode bit for bit because an element walks
     the same slabs in the same order whatever tile it lies in: every fast tile variant gives the same bits, and so do
-    the whole-grid launch and the q*q single-device launches (which choose different tiles)."""
-    q = 2
+    the whole-grid launch and the q*q single-device launches (which choose different tiles).  Where the whole-grid
+    launch has workgroups enough without the panel split it emulates it inside each workgroup (one accumulator per
+    range of slabs, the ranges' sums added in range order): third element of the plan, same bits again."""
     M, K, N = mb * q, kp * q, nb * q
     A, B = gemm_inputs(57, form, M, K, N, "bf16", "n1", "n1")
     ws = None
@@ -180,6 +182,9 @@ def test_tile_variants_give_identical_bits_and_grid_equals_device(form, mb, kp, 
     assert torch.equal(grid.view(torch.int16), dev.view(torch.int16)) and torch.equal(grid.view(torch.int16), ref.view(torch.int16))
     print("grid plan", grid_plan, "device plans", dev_plans)
     assert all(p[1] == grid_plan[1] for p in dev_plans)   # the same panel split in both modes
+    assert all(p[2] == 0 for p in dev_plans)              # one device: the real split
+    if q == 4 and form == "ab":
+        assert grid_plan[1] > 1 and grid_plan[2] == 1     # 16 blocks of [1024 x 4096 x 256]: emulated in the workgroups
 
 
 def test_closed_forms_and_identities():
