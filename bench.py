@@ -359,6 +359,14 @@ def time_layer_step(opt, torch, harness, name, steps, warmup):
         del lt, ws
         if fused:
             del T
+    if name == "config4":   # whole-grid launches of the forward products: the kernel on 16 devices' blocks at once
+        fwd = [g for g in layer_gemm_list(b, s, h) if g[0] in ("qkv.ab", "mlp_up.ab", "mlp_down.ab", "mlp_down.abt", "mlp_up.atb")]
+        rows = time_gemms(opt, torch, fwd, q, -1, -1, 6, 78, rotating=False)
+        for r in rows:   # time_gemms counts one device's flops: the grid launch does q*q times as much
+            r["tflops"] = round(r["tflops"] * q * q, 1)
+            r["pct_peak"] = round(100 * r["tflops"] / PEAK_BF16_TFLOPS, 1)
+            r["devices"] = q * q
+        res["grid_launch"] = rows
     if name == "config4":   # the checkpointed stack at a size where the products dominate (whole grid on the one GPU)
         st = time_stack(opt, torch, harness, cfg0, T0, b, s, h, n, q, layers=2, reps=3)
         # per layer and device: forward, recomputation without the last product (a third of the forward flops), backward
