@@ -166,7 +166,7 @@ def test_layer_device_mode_writes_only_its_blocks():
 
 
 def test_layer_config2_full_size():
-    """BASELINE config 2 (b=8, s=512, h=1024, 16 heads, q=4) at full size: grid run vs the oracle,
+    """Benchmark configuration 2 (b=8, s=512, h=1024, 16 heads, q=4) at full size: grid run vs the oracle,
     then the timed launch configuration (one device, resident peers) reproduces its blocks bit for bit."""
     shp = CONFIGS["config2"]["layer"]
     inp = layer_inputs(CONFIGS["config2"]["seed"], shp, "bf16")

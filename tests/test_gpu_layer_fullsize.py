@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of BASELINE configs 4 and 5, in the launch configuration the benchmark times.
+"""GPU parity at the full sizes of benchmark configurations 4 and 5, in the launch configuration the benchmark times.
 
 A whole-layer fp64 oracle at these sizes is 10-40 TFLOP of host work, so every stage is checked on SAMPLED
 outputs instead: for each stage of the forward and backward path (Section 3.2 of the paper: 2D LayerNorm, the

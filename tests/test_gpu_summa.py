@@ -299,7 +299,7 @@ FULL = [(name, g) for name in ("config2", "config3", "config4", "config5") for g
 
 @pytest.mark.parametrize("name,g", FULL, ids=[f"{n}-{g.name}" for n, g in FULL])
 def test_full_size_one_device_sampled(name, g):
-    """BASELINE sizes, one device's share in the launch configuration the benchmark times (explicit (i, j),
+    """Benchmark sizes, one device's share in the launch configuration the benchmark times (explicit (i, j),
     workspace given).  The oracle recomputes sampled output rows of the device's block one by one in fp64."""
     q = g.q
     i, j = q - 1, 1
