@@ -20,14 +20,28 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# Bytes that crossed the L2 -> fabric boundary per launch of the dominant product, from two rocprofv3 --pmc runs
+# Bytes that crossed the L2 -> fabric boundary per launch of the dominant product come from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE) of `bench.py [--workload W] --pmc-probe`, each scaled by what the counter reads for a
-# 256 MiB copy in the same run (fetch x 2.0, write x 1.0).  Hardware counters cannot be read from inside this
-# script; the values are those of the profiled runs of this same command and are None for anything not profiled.
-MEASURED_TRAFFIC_BYTES = {
-    ("config2", "mlp_up.ab"): {"variant": "64x64", "fetch_KiB": 6229.7 * 2.0, "write_KiB": 2048.0},
-    ("config4", "mlp_up.ab"): {"variant": "256x128", "fetch_KiB": 65643.0 * 2.0, "write_KiB": 16384.0},
-}
+# 256 MiB copy in the same run.  Hardware counters cannot be read from inside this script: the summary tool
+# (python -m paper_2104_05343_amd.profile_summary pmc ...) writes them to this file together with the tile plan and
+# the commit they were measured at, and they are reported only while the planner still picks that tile.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "dominant_product_traffic.json")
+
+
+def measured_traffic(workload, product, plan):
+    """(bytes per launch or None, note) for the dominant product from the tracked counter summary."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f).get(workload, {}).get(product)
+    except (OSError, ValueError):
+        rec = None
+    if rec is None:
+        return None, "no counter summary for this workload under profiles/"
+    if rec.get("plan") != plan:
+        return None, f"counter summary was taken with tile plan {rec.get('plan')}, the planner now picks {plan}: re-profile"
+    return int(rec["fetch_bytes"] + rec["write_bytes"]), f"rocprofv3 FETCH_SIZE/WRITE_SIZE scaled by a 256 MiB copy, measured at commit {rec.get('commit')}"
+
+
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
@@ -35,9 +49,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="config2", choices=["config2", "config4", "config5"])
+    ap.add_argument("--workload", default="config4", choices=["config2", "config4", "config5"])
     ap.add_argument("--device-coords", default="1,2", help="device (i,j) whose share is timed")
     ap.add_argument("--gemm-reps", type=int, default=50)
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-config GEMM table")
@@ -154,10 +168,12 @@ def time_gemms(opt, torch, gemms, q, i, j, reps, seed, rotating=True):
         ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
         A, B, C = sets[0]
         ms = event_time_ms(lambda: opt.summa(form, A, B, C, M, K, N, q, i, j, opt.BF16, ws=ws), reps)
+        plan = opt.debug_last_gemm_plan()
         fl = opt.gemm_flops(M, K, N, q)
         tf = fl / (ms * 1e-3) / 1e12
         row = {"name": name, "form": form, "block": [M // q, K, N // q], "panel": K // q, "us": round(ms * 1e3, 2),
-               "tflops": round(tf, 1), "pct_peak": round(100 * tf / PEAK_BF16_TFLOPS, 1), "split_ws_bytes": int(nbytes)}
+               "tflops": round(tf, 1), "pct_peak": round(100 * tf / PEAK_BF16_TFLOPS, 1), "split_ws_bytes": int(nbytes),
+               "plan": list(plan) if plan else None}
         if rotating:
             dev_ws = 2 * ((M // q) * K + K * (N // q) + (M // q) * (N // q))   # bytes one device touches per launch
             nsets = max(2, min(64, -(-ROTATE_BYTES // dev_ws)))
@@ -173,6 +189,8 @@ def time_gemms(opt, torch, gemms, q, i, j, reps, seed, rotating=True):
             ms_r = event_time_ms(launch, rr)
             row["us_rotating"] = round(ms_r * 1e3, 2)
             row["rotating_sets"] = nsets
+            row["tflops_rotating"] = round(fl / (ms_r * 1e-3) / 1e12, 1)
+            row["pct_peak_rotating"] = round(100 * fl / (ms_r * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 1)
         rows.append(row)
         del A, B, C, ws, sets
     return rows
@@ -217,8 +235,22 @@ def time_bandwidth(opt, torch, b, s, h, n, q, i, j, reps, seed):
     put("layernorm2d_fwd_all_blocks", ms, 3 * blk * q * q, f"the same for all {q * q} blocks in one launch (the partial row statistics meet inside the launch)")
     ms = event_time_ms(lambda: opt.layernorm2d_bwd(dY, xhat, rstd, gamma, None, dX, None, None, bstats, M, H, q, -1, -1, opt.BF16), reps)
     put("layernorm2d_bwd_dx_all_blocks", ms, 3 * blk * q * q, f"dx for all {q * q} blocks in one launch (no parameter gradients)")
-    # attention: scores fp32 scratch -> probabilities bf16; bytes counted for the two softmax-like passes only
+    # the row soft-max kernels of local attention alone, one device's score matrices: fp32 scores in, bf16 out
     nmat = (b // q) * (n // q)
+    sc = torch.randn(nmat * s * s, generator=gen, device="cuda:0", dtype=torch.float32) * 1.6
+    pr = torch.empty(nmat * s * s, dtype=torch.bfloat16, device="cuda:0")
+    ds = torch.empty(nmat * s * s, dtype=torch.bfloat16, device="cuda:0")
+    tri = nmat * s * (s + 1) // 2      # entries on and below the diagonal: all a causal row reads
+    ms = event_time_ms(lambda: opt.softmax_rows(sc, pr, nmat, s, True), reps)
+    put("softmax_fwd", ms, tri * 4 + nmat * s * s * 2,
+        f"causal, {nmat} matrices [{s} x {s}]: read fp32 scores on and below the diagonal, write every bf16 probability")
+    out["softmax_fwd"]["block"] = [nmat, s, s]
+    ms = event_time_ms(lambda: opt.softmax_rows_bwd(sc, pr, ds, nmat, s, True), reps)
+    put("softmax_bwd", ms, tri * (4 + 2) + nmat * s * s * 2,
+        "causal: read fp32 dP and bf16 P on and below the diagonal, write every bf16 dS")
+    out["softmax_bwd"]["block"] = [nmat, s, s]
+    del sc, pr, ds
+    # attention: scores fp32 scratch -> probabilities bf16
     qkv = rnd(M * 3 * H, 0.5)
     d_attn = rnd(M * H)
     probs = torch.zeros(q * q * nmat * s * s, dtype=torch.bfloat16, device="cuda:0")
@@ -359,21 +391,26 @@ def time_layer_step(opt, torch, harness, name, steps, warmup):
         del lt, ws
         if fused:
             del T
-    if name == "config4":   # whole-grid launches of the forward products: the kernel on 16 devices' blocks at once
-        fwd = [g for g in layer_gemm_list(b, s, h) if g[0] in ("qkv.ab", "mlp_up.ab", "mlp_down.ab", "mlp_down.abt", "mlp_up.atb")]
-        rows = time_gemms(opt, torch, fwd, q, -1, -1, 6, 78, rotating=False)
-        for r in rows:   # time_gemms counts one device's flops: the grid launch does q*q times as much
-            r["tflops"] = round(r["tflops"] * q * q, 1)
-            r["pct_peak"] = round(100 * r["tflops"] / PEAK_BF16_TFLOPS, 1)
-            r["devices"] = q * q
-        res["grid_launch"] = rows
-    if name == "config4":   # the checkpointed stack at a size where the products dominate (whole grid on the one GPU)
-        st = time_stack(opt, torch, harness, cfg0, T0, b, s, h, n, q, layers=2, reps=3)
-        # per layer and device: forward, recomputation without the last product (a third of the forward flops), backward
-        # (twice the forward): 11/3 forward passes = 11/9 of the step's product flops
-        fl = 2 * q * q * summa_flops * 11 // 9
-        st["summa_tflops_fwd_bwd_recompute"] = round(fl / ((st["fwd_ms"] + st["bwd_with_recompute_ms"]) * 1e-3) / 1e12, 1)
-        res["stack_2_layers"] = st
+    return res
+
+
+def config4_extras(opt, torch, harness, cfg, T, b, s, h, n, q, summa_flops):
+    """Whole-grid launches of five products (the kernel on all 16 devices' blocks at once) and a two-layer
+    checkpointed stack at configuration 4's size (whole grid on the one GPU)."""
+    res = {}
+    fwd = [g for g in layer_gemm_list(b, s, h) if g[0] in ("qkv.ab", "mlp_up.ab", "mlp_down.ab", "mlp_down.abt", "mlp_up.atb")]
+    rows = time_gemms(opt, torch, fwd, q, -1, -1, 6, 78, rotating=False)
+    for r in rows:   # time_gemms counts one device's flops: the grid launch does q*q times as much
+        r["tflops"] = round(r["tflops"] * q * q, 1)
+        r["pct_peak"] = round(100 * r["tflops"] / PEAK_BF16_TFLOPS, 1)
+        r["devices"] = q * q
+    res["grid_launch"] = rows
+    st = time_stack(opt, torch, harness, cfg, T, b, s, h, n, q, layers=2, reps=3)
+    # per layer and device: forward, recomputation without the last product (a third of the forward flops), backward
+    # (twice the forward): 11/3 forward passes = 11/9 of the step's product flops
+    fl = 2 * q * q * summa_flops * 11 // 9
+    st["summa_tflops_fwd_bwd_recompute"] = round(fl / ((st["fwd_ms"] + st["bwd_with_recompute_ms"]) * 1e-3) / 1e12, 1)
+    res["stack_2_layers"] = st
     return res
 
 
@@ -463,20 +500,22 @@ def main():
     fwd_ms = event_time_ms(lambda: opt.layer_fwd(cfg, lt, di, dj, ws), max(5, args.steps // 2))
     bwd_ms = event_time_ms(lambda: opt.layer_bwd(cfg, lt, di, dj, ws), max(5, args.steps // 2))
     gemm_rows = time_gemms(opt, torch, gemms, q, di, dj, args.gemm_reps, cfgd["seed"])
-    # dominant kernel = the product with the most flops (first of equals): the same rule picks it in --pmc-probe
+    # dominant kernel = the product with the most flops (first of equals): the same rule picks it in --pmc-probe.
+    # Its rate is taken from the launches that cycle through independent buffer sets (the device's panels of all
+    # sets exceed the 256 MB Infinity Cache: what a product sees inside a step, whose tensors pass through once);
+    # the warm figure (same buffers every launch) is given beside it.
     dom = max(gemm_rows, key=lambda r: r["block"][0] * r["block"][1] * r["block"][2])
     dom_flops = 2 * dom["block"][0] * dom["block"][1] * dom["block"][2]
-    roofline = {"bound": "mfma", "kernel": f"gemm_mfma_kernel ({dom['name']}, block {dom['block']})",
-                "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "flops_per_launch": dom_flops,
-                "avg_us": dom["us"], "traffic": None}
-    mt = MEASURED_TRAFFIC_BYTES.get((args.workload, dom["name"]))
-    if mt is not None:
-        roofline["traffic"] = int((mt["fetch_KiB"] + mt["write_KiB"]) * 1024)
-        roofline["traffic_unit"] = "bytes per launch (L2 fabric reads + writes; rocprofv3 FETCH_SIZE/WRITE_SIZE, scaled by a copy)"
-        roofline["algorithmic_bytes"] = 2 * (dom["block"][0] * dom["block"][1] + dom["block"][1] * dom["block"][2]
-                                             + dom["block"][0] * dom["block"][2])
-    sum_us = sum(r["us"] for r in gemm_rows)
+    alg_bytes = 2 * (dom["block"][0] * dom["block"][1] + dom["block"][1] * dom["block"][2] + dom["block"][0] * dom["block"][2])
+    traffic, traffic_note = measured_traffic(args.workload, dom["name"], dom["plan"])
+    roofline = {"bound": "mfma", "kernel": f"gemm_mfma_kernel ({dom['name']}, block {dom['block']}, tile plan {dom['plan']})",
+                "achieved": dom["tflops_rotating"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(dom["tflops_rotating"] / PEAK_BF16_TFLOPS, 4), "flops_per_launch": dom_flops,
+                "avg_us": dom["us_rotating"], "cache": f"rotating over {dom['rotating_sets']} buffer sets (> 256 MB Infinity Cache)",
+                "avg_us_warm": dom["us"], "frac_warm": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4),
+                "traffic": traffic, "traffic_unit": "bytes per launch crossing the L2 <-> fabric boundary", "traffic_source": traffic_note,
+                "algorithmic_bytes": alg_bytes}
+    sum_us = sum(r["us_rotating"] for r in gemm_rows)
     gemm_only_tflops = summa_flops / (sum_us * 1e-6) / 1e12
 
     # bandwidth-bound kernels: at this workload's block sizes and at config 4's (4 MiB blocks)
@@ -498,7 +537,7 @@ def main():
         "roofline": roofline,
         "step_detail": {"summa_flops_per_step": summa_flops, "layer_flops_per_step_table1": layer_flops,
                         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
-                        "sum_of_12_gemm_kernels_us": round(sum_us, 1), "gemm_only_tflops": round(gemm_only_tflops, 1),
+                        "sum_of_12_gemm_kernels_us_rotating": round(sum_us, 1), "gemm_only_tflops": round(gemm_only_tflops, 1),
                         "gemm_only_pct_peak": round(100 * gemm_only_tflops / PEAK_BF16_TFLOPS, 1)},
         "step_fused_attention": fused_step,
         "gemms": gemm_rows,
@@ -509,6 +548,8 @@ def main():
 
     if not args.no_sweep:
         out["model_ends"] = time_model_ends(opt, torch, b, s, h, q, di, dj, 32768, args.gemm_reps, 9)
+    if not args.no_sweep and args.workload == "config4":
+        out.update(config4_extras(opt, torch, harness, cfg, T, b, s, h, n, q, summa_flops))
     if not args.no_sweep and args.workload == "config2":
         out["stack"] = time_stack(opt, torch, harness, cfg, T, b, s, h, n, q, layers=4, reps=max(3, args.steps // 10))
         if (h // n) in (64, 128):
@@ -516,11 +557,6 @@ def main():
             out["stack_fused_attention"] = time_stack(opt, torch, harness, cfg_f, T_f, b, s, h, n, q, layers=4,
                                                       reps=max(3, args.steps // 10))
             del T_f
-    if not args.no_sweep and args.workload == "config2":
-        # whole-step figures of the larger layers (the same measurement as `value`, fewer replays)
-        out["other_workload_steps"] = [time_layer_step(opt, torch, harness, name, max(10, args.steps // 2), args.warmup)
-                                       for name in ("config4", "config5")]
-    if not args.no_sweep and args.workload == "config2":
         # the same forward products launched for the whole grid at once (i = j = -1: all q*q devices' blocks)
         fwd = [g for g in gemms if g[0] in ("qkv.ab", "mlp_up.ab", "mlp_down.ab")]
         grid_rows = time_gemms(opt, torch, fwd, q, -1, -1, max(10, args.gemm_reps // 2), 77, rotating=False)
@@ -529,6 +565,10 @@ def main():
             r["pct_peak"] = round(100 * r["tflops"] / PEAK_BF16_TFLOPS, 1)
             r["devices"] = q * q
         out["grid_launch"] = grid_rows
+    if not args.no_sweep:
+        # whole-step figures of the other layer configurations (the same measurement as `value`, fewer replays)
+        out["other_workload_steps"] = [time_layer_step(opt, torch, harness, name, max(10, args.steps // 2), args.warmup)
+                                       for name in ("config2", "config4", "config5") if name != args.workload]
 
     if not args.no_sweep:
         from workloads import gemm_cases
@@ -538,11 +578,13 @@ def main():
             qq = gemm_cases(name)[0].q
             rows = time_gemms(opt, torch, cases, qq, qq - 1, 1, max(10, args.gemm_reps // 2), 1000 + qq)
             tot_fl = sum(2 * r["block"][0] * r["block"][1] * r["block"][2] for r in rows)
-            tot_us = sum(r["us"] for r in rows)
-            per[name] = {"q": qq, "aggregate_tflops": round(tot_fl / (tot_us * 1e-6) / 1e12, 1),
+            tot_us = sum(r["us_rotating"] for r in rows)
+            per[name] = {"q": qq, "timing": "rotating buffer sets (aggregate, best, worst); 'us'/'pct_peak' of a row = warm",
+                         "aggregate_tflops": round(tot_fl / (tot_us * 1e-6) / 1e12, 1),
                          "aggregate_pct_peak": round(100 * tot_fl / (tot_us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 1),
-                         "best_pct_peak": max(r["pct_peak"] for r in rows), "worst_pct_peak": min(r["pct_peak"] for r in rows),
-                         "gemms": rows}
+                         "best_pct_peak": max(r["pct_peak_rotating"] for r in rows),
+                         "worst_pct_peak": min(r["pct_peak_rotating"] for r in rows),
+                         "split_ws_bytes_max": max(r["split_ws_bytes"] for r in rows), "gemms": rows}
         out["per_config"] = per
 
     if not args.no_cpu:
@@ -561,10 +603,15 @@ def main():
                 flops_once = 3 * 2 * 12 * b * s * h * h      # SUMMA-product flops of the full logical layer, fwd + bwd
                 sample = "oracle.layer forward+backward (fp64) of the whole logical config2 layer = all 16 devices' work"
             else:
-                rowsN = min(b * s, 2048)
-                osumma.matmul_ab(inp["x"][:rowsN], inp["w1"])
-                flops_once = 2 * rowsN * h * 4 * h
-                sample = f"oracle.summa.matmul_ab (fp64) on {rowsN} rows of the h->4h product"
+                # one sequence of the workload through the whole layer, forward and backward (every operation of the
+                # layer acts on rows or on whole sequences independently, so this is 1/b of the logical layer's work)
+                one = dict(inp)
+                one["x"], one["d_out"] = inp["x"][:s], inp["d_out"][:s]
+                fwd_o = olayer.forward(one, 1, s, n, causal=True, keep_probs=False)
+                olayer.backward(one, fwd_o, 1, s, n, causal=True)
+                flops_once = 3 * 2 * 12 * s * h * h
+                sample = (f"oracle.layer forward+backward (fp64) of ONE sequence ({s} rows) of the logical {args.workload} "
+                          f"layer = 1/{b} of all {q * q} devices' work")
             reps_cpu += 1
             if time.perf_counter() - c0 >= 10.0 or reps_cpu >= 200:
                 break

@@ -195,6 +195,17 @@ int optimus_attention_bwd(const void* qkv, const void* probs, const void* d_attn
                           size_t ws_bytes, void* stream);
 size_t optimus_attention_workspace_bytes(int b, int s, int h, int n, int q);
 
+/* ---- the row soft-max of attention by itself ("Nonlinear" of Section 2.1; local per device, Section 3.2.1) ----
+ * The two bandwidth-bound kernels between the attention products, exported so that they can be measured and
+ * tested alone.  scores / d_probs: nmat matrices [s x s] fp32, contiguous; probs / d_scores: the same shape in
+ * bf16.  Forward: P = softmax over each row of S (with causal != 0 only columns <= row take part and the entries
+ * above the diagonal are written as exact zeros).  Backward: dS = P * (dP - rowsum(dP * P)) row by row (entries
+ * of dP above the diagonal are not read when causal).  Device memory; requires s % 4 == 0, 4 <= s <= 4096,
+ * nmat >= 1, nmat * s < 2^31 (OPTIMUS_ESHAPE otherwise); null pointers: OPTIMUS_EINVAL. */
+int optimus_softmax_rows(const float* scores, void* probs, int64_t nmat, int s, int causal, void* stream);
+int optimus_softmax_rows_bwd(const float* d_probs, const void* probs, void* d_scores, int64_t nmat, int s,
+                             int causal, void* stream);
+
 /* ---- the same attention without the [s x s] tensors (the operator fusion proposed in Section 6) ----
  * Same qkv / attn / d_qkv layouts and the same mathematics as above, but neither scores nor probabilities are
  * ever written to memory, so sequence length is no longer bounded by the [b/q, n/q, s, s] tensor.  The forward

@@ -19,6 +19,14 @@ def softmax_rows(S):
     return e / e.sum(axis=1, keepdims=True)
 
 
+def softmax_rows_backward(P, dP):
+    """Gradient of the row soft-max: with P = softmax_rows(S) and dP the gradient with respect to P,
+    dS = P * (dP - rowsum(dP * P))."""
+    P = np.asarray(P, dtype=np.float64)
+    dP = np.asarray(dP, dtype=np.float64)
+    return P * (dP - (dP * P).sum(axis=1, keepdims=True))
+
+
 def head_forward(Q, K, V, causal=True):
     """One (sequence, head). Returns O [s,d] and P [s,s]."""
     Q = np.asarray(Q, dtype=np.float64)
@@ -47,13 +55,11 @@ def head_logsumexp(Q, K, causal=True):
     return m + np.log(np.exp(S - m[:, None]).sum(axis=1))
 
 
-def head_backward(Q, K, V, P, dO, store=None):
+def head_backward(Q, K, V, P, dO):
     """Gradients for one (sequence, head).
 
     dV = P^T dO; dP = dO V^T; dS = P * (dP - rowsum(dP * P));
     dQ = dS K / sqrt(d); dK = dS^T Q / sqrt(d).
-    ``store`` (optional) is applied to dS, the one intermediate of this step that the
-    device keeps in its storage precision before the last two products.
     """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
@@ -63,9 +69,7 @@ def head_backward(Q, K, V, P, dO, store=None):
     d = Q.shape[1]
     dV = P.T @ dO
     dP = dO @ V.T
-    dS = P * (dP - (dP * P).sum(axis=1, keepdims=True))
-    if store is not None:
-        dS = store("d_scores", dS)
+    dS = softmax_rows_backward(P, dP)
     dQ = dS @ K / np.sqrt(d)
     dK = dS.T @ Q / np.sqrt(d)
     return dQ, dK, dV
@@ -80,10 +84,8 @@ def split_qkv(qkv, b, s, n, seq, head):
     return (qkv[rows, c0:c0 + d], qkv[rows, c0 + d:c0 + 2 * d], qkv[rows, c0 + 2 * d:c0 + 3 * d])
 
 
-def forward(qkv, b, s, n, causal=True, keep_probs=True, store=None):
-    """qkv [b*s, 3h] -> attn [b*s, h] (heads concatenated) and probs [b, n, s, s].
-    With ``store``, P is passed through it before the P V product (the device multiplies the
-    probabilities it saved)."""
+def forward(qkv, b, s, n, causal=True, keep_probs=True):
+    """qkv [b*s, 3h] -> attn [b*s, h] (heads concatenated) and probs [b, n, s, s]."""
     qkv = np.asarray(qkv, dtype=np.float64)
     h = qkv.shape[1] // 3
     d = h // n
@@ -93,9 +95,6 @@ def forward(qkv, b, s, n, causal=True, keep_probs=True, store=None):
         for head in range(n):
             Q, K, V = split_qkv(qkv, b, s, n, seq, head)
             O, P = head_forward(Q, K, V, causal)
-            if store is not None:
-                P = store("probs", P)
-                O = P @ np.asarray(V, dtype=np.float64)
             out[seq * s:(seq + 1) * s, head * d:(head + 1) * d] = O
             if keep_probs:
                 probs[seq, head] = P
@@ -113,7 +112,7 @@ def logsumexp(qkv, b, s, n, causal=True):
     return out
 
 
-def backward(qkv, d_attn, b, s, n, causal=True, probs=None, store=None):
+def backward(qkv, d_attn, b, s, n, causal=True, probs=None):
     """d_attn [b*s, h] -> d_qkv [b*s, 3h].  Probabilities are recomputed in fp64 unless the saved
     ones ([b, n, s, s]) are passed in."""
     qkv = np.asarray(qkv, dtype=np.float64)
@@ -126,7 +125,7 @@ def backward(qkv, d_attn, b, s, n, causal=True, probs=None, store=None):
             Q, K, V = split_qkv(qkv, b, s, n, seq, head)
             P = probs[seq, head] if probs is not None else head_forward(Q, K, V, causal)[1]
             dO = d_attn[seq * s:(seq + 1) * s, head * d:(head + 1) * d]
-            dQ, dK, dV = head_backward(Q, K, V, P, dO, store)
+            dQ, dK, dV = head_backward(Q, K, V, P, dO)
             rows = slice(seq * s, (seq + 1) * s)
             c0 = head * 3 * d
             d_qkv[rows, c0:c0 + d] = dQ

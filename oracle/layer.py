@@ -12,13 +12,9 @@ GeLU is the exact form x * Phi(x).  No dropout.  Backward uses the saved
 forward tensors (no recomputation): every linear follows Eq. 1
 (dX = dY W^T, dW = X^T dY, db = column sums of dY).
 
-Storage precision.  By default every intermediate stays in fp64.  The device keeps its
-activations and activation gradients in bf16 (round-to-nearest-even on store) and later
-stages read those stored values; ``storage="bf16"`` reproduces exactly that specification
-here — the arithmetic of every stage is still fp64, only the tensors the device stores in
-bf16 are rounded when they are produced.  The exact mode says how far bf16 storage as a
-whole drifts from real arithmetic; the storage-aware mode isolates the arithmetic of each
-stage (what "bf16 inputs, fp32 accumulation" bounds).
+Every intermediate stays in fp64: nothing is rounded anywhere.
+
+Test infrastructure only.
 """
 import math
 
@@ -45,75 +41,45 @@ def _f(t):
     return np.asarray(t, dtype=np.float64)
 
 
-# tensors the device holds in bf16 (weight/bias/affine gradients and LayerNorm statistics are fp32)
-BF16_STORED = ("ln1_out", "xhat1", "qkv", "probs", "attn", "h_mid", "ln2_out", "xhat2", "pre_gelu", "gelu", "out",
-               "d_pre_gelu", "d_ln2_out", "d_h_mid", "d_attn", "d_scores", "d_qkv", "d_ln1_out", "d_x")
-
-
-def _make_store(storage):
-    if storage is None:
-        return None
-    if storage != "bf16":
-        raise ValueError(storage)
-    from workloads import round_to_bf16   # the same rounding the input generator applies
-
-    def store(name, x):
-        if name in BF16_STORED:
-            return round_to_bf16(np.asarray(x, dtype=np.float32)).astype(np.float64)
-        if name in ("rstd1", "rstd2"):
-            return np.asarray(x, dtype=np.float32).astype(np.float64)
-        return x
-    return store
-
-
-def forward(inp, b, s, n, causal=True, eps=_ln.EPS_DEFAULT, keep_probs=True, storage=None):
+def forward(inp, b, s, n, causal=True, eps=_ln.EPS_DEFAULT, keep_probs=True):
     """inp: dict of logical tensors (see workloads.layer_inputs). Returns dict of every stage."""
-    st = _make_store(storage)
-    S = (lambda name, v: v) if st is None else st
     x = _f(inp["x"])
     t = {}
-    y, xhat, rstd = _ln.forward(x, inp["ln1_g"], inp["ln1_b"], eps)
-    t["ln1_out"], t["xhat1"], t["rstd1"] = S("ln1_out", y), S("xhat1", xhat), S("rstd1", rstd)
-    t["qkv"] = S("qkv", t["ln1_out"] @ _f(inp["w_qkv"]) + _f(inp["b_qkv"])[None, :])
-    attn, t["probs"] = _att.forward(t["qkv"], b, s, n, causal, keep_probs or st is not None, st)
-    t["attn"] = S("attn", attn)
-    t["h_mid"] = S("h_mid", x + t["attn"] @ _f(inp["w_o"]) + _f(inp["b_o"])[None, :])
-    y, xhat, rstd = _ln.forward(t["h_mid"], inp["ln2_g"], inp["ln2_b"], eps)
-    t["ln2_out"], t["xhat2"], t["rstd2"] = S("ln2_out", y), S("xhat2", xhat), S("rstd2", rstd)
-    pre = t["ln2_out"] @ _f(inp["w1"]) + _f(inp["b1"])[None, :]
-    t["pre_gelu"] = S("pre_gelu", pre)
-    t["gelu"] = S("gelu", gelu(pre))        # the activation is applied to the unrounded accumulator
-    t["out"] = S("out", t["h_mid"] + t["gelu"] @ _f(inp["w2"]) + _f(inp["b2"])[None, :])
+    t["ln1_out"], t["xhat1"], t["rstd1"] = _ln.forward(x, inp["ln1_g"], inp["ln1_b"], eps)
+    t["qkv"] = t["ln1_out"] @ _f(inp["w_qkv"]) + _f(inp["b_qkv"])[None, :]
+    t["attn"], t["probs"] = _att.forward(t["qkv"], b, s, n, causal, keep_probs)
+    t["h_mid"] = x + t["attn"] @ _f(inp["w_o"]) + _f(inp["b_o"])[None, :]
+    t["ln2_out"], t["xhat2"], t["rstd2"] = _ln.forward(t["h_mid"], inp["ln2_g"], inp["ln2_b"], eps)
+    t["pre_gelu"] = t["ln2_out"] @ _f(inp["w1"]) + _f(inp["b1"])[None, :]
+    t["gelu"] = gelu(t["pre_gelu"])
+    t["out"] = t["h_mid"] + t["gelu"] @ _f(inp["w2"]) + _f(inp["b2"])[None, :]
     return t
 
 
-def backward(inp, fwd, b, s, n, causal=True, storage=None):
+def backward(inp, fwd, b, s, n, causal=True):
     """Gradients of <d_out, out> w.r.t. x and every parameter, plus intermediate gradients."""
-    st = _make_store(storage)
-    S = (lambda name, v: v) if st is None else st
     d_out = _f(inp["d_out"])
     g = {}
     # out = h_mid + gelu @ w2 + b2
     g["d_gelu"] = d_out @ _f(inp["w2"]).T
     g["d_w2"] = fwd["gelu"].T @ d_out
     g["d_b2"] = d_out.sum(axis=0)
-    g["d_pre_gelu"] = S("d_pre_gelu", g["d_gelu"] * gelu_grad(fwd["pre_gelu"]))
+    g["d_pre_gelu"] = g["d_gelu"] * gelu_grad(fwd["pre_gelu"])
     # pre_gelu = ln2_out @ w1 + b1
-    g["d_ln2_out"] = S("d_ln2_out", g["d_pre_gelu"] @ _f(inp["w1"]).T)
+    g["d_ln2_out"] = g["d_pre_gelu"] @ _f(inp["w1"]).T
     g["d_w1"] = fwd["ln2_out"].T @ g["d_pre_gelu"]
     g["d_b1"] = g["d_pre_gelu"].sum(axis=0)
     dx2, g["d_ln2_g"], g["d_ln2_b"] = _ln.backward(g["d_ln2_out"], fwd["xhat2"], fwd["rstd2"], inp["ln2_g"])
-    g["d_h_mid"] = S("d_h_mid", d_out + dx2)
+    g["d_h_mid"] = d_out + dx2
     # h_mid = x + attn @ w_o + b_o
-    g["d_attn"] = S("d_attn", g["d_h_mid"] @ _f(inp["w_o"]).T)
+    g["d_attn"] = g["d_h_mid"] @ _f(inp["w_o"]).T
     g["d_w_o"] = fwd["attn"].T @ g["d_h_mid"]
     g["d_b_o"] = g["d_h_mid"].sum(axis=0)
-    probs = fwd.get("probs") if st is not None else None   # the device uses the probabilities it saved
-    g["d_qkv"] = S("d_qkv", _att.backward(fwd["qkv"], g["d_attn"], b, s, n, causal, probs, st))
+    g["d_qkv"] = _att.backward(fwd["qkv"], g["d_attn"], b, s, n, causal)
     # qkv = ln1_out @ w_qkv + b_qkv
-    g["d_ln1_out"] = S("d_ln1_out", g["d_qkv"] @ _f(inp["w_qkv"]).T)
+    g["d_ln1_out"] = g["d_qkv"] @ _f(inp["w_qkv"]).T
     g["d_w_qkv"] = fwd["ln1_out"].T @ g["d_qkv"]
     g["d_b_qkv"] = g["d_qkv"].sum(axis=0)
     dx1, g["d_ln1_g"], g["d_ln1_b"] = _ln.backward(g["d_ln1_out"], fwd["xhat1"], fwd["rstd1"], inp["ln1_g"])
-    g["d_x"] = S("d_x", g["d_h_mid"] + dx1)
+    g["d_x"] = g["d_h_mid"] + dx1
     return g

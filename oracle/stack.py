@@ -19,30 +19,30 @@ PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b
 GRAD_NAMES = tuple("d_" + k for k in PARAM_NAMES)
 
 
-def forward(params, x, b, s, n, causal=True, storage=None, counter=None):
+def forward(params, x, b, s, n, causal=True, counter=None):
     """params: list of L dicts with PARAM_NAMES; x [b*s, h].
     Returns (out, checkpoints) with checkpoints[l] = input of layer l."""
     cur = np.asarray(x, dtype=np.float64)
     checkpoints = []
     for p in params:
         checkpoints.append(cur)
-        f = _layer.forward(dict(p, x=cur), b, s, n, causal=causal, keep_probs=False, storage=storage)
+        f = _layer.forward(dict(p, x=cur), b, s, n, causal=causal, keep_probs=False)
         if counter is not None:
             counter["forward_passes"] = counter.get("forward_passes", 0) + 1
         cur = f["out"]
     return cur, checkpoints
 
 
-def backward(params, checkpoints, d_out, b, s, n, causal=True, storage=None, counter=None):
+def backward(params, checkpoints, d_out, b, s, n, causal=True, counter=None):
     """Returns (d_x, grads) with grads[l] = dict of GRAD_NAMES for layer l."""
     g_out = np.asarray(d_out, dtype=np.float64)
     grads = [None] * len(params)
     for l in range(len(params) - 1, -1, -1):
         inp = dict(params[l], x=checkpoints[l], d_out=g_out)
-        f = _layer.forward(inp, b, s, n, causal=causal, keep_probs=storage is not None, storage=storage)   # the recomputation
+        f = _layer.forward(inp, b, s, n, causal=causal, keep_probs=False)   # the recomputation
         if counter is not None:
             counter["forward_passes"] = counter.get("forward_passes", 0) + 1
-        g = _layer.backward(inp, f, b, s, n, causal=causal, storage=storage)
+        g = _layer.backward(inp, f, b, s, n, causal=causal)
         grads[l] = {k: g[k] for k in GRAD_NAMES}
         g_out = g["d_x"]
     return g_out, grads

@@ -99,6 +99,8 @@ SIGNATURES = {
     "optimus_attention_fwd": (_INT, [_P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
     "optimus_attention_bwd": (_INT, [_P, _P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
     "optimus_attention_workspace_bytes": (_SZ, [_INT, _INT, _INT, _INT, _INT]),
+    "optimus_softmax_rows": (_INT, [_P, _P, _I64, _INT, _INT, _P]),
+    "optimus_softmax_rows_bwd": (_INT, [_P, _P, _P, _I64, _INT, _INT, _P]),
     "optimus_attention_fused_fwd": (_INT, [_P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P]),
     "optimus_attention_fused_bwd": (_INT, [_P, _P, _P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
     "optimus_attention_fused_workspace_bytes": (_SZ, [_INT, _INT, _INT, _INT, _INT]),
@@ -266,6 +268,15 @@ def attention_bwd(qkv, probs, d_attn, d_qkv, b, s, h, n, q, i, j, causal, dtype,
     p, nb = _ws(ws)
     _check(lib().optimus_attention_bwd(_ptr(qkv), _ptr(probs), _ptr(d_attn), _ptr(d_qkv), b, s, h, n, q, i, j, int(causal), dtype,
                                        p, nb, _stream(stream)), "optimus_attention_bwd")
+
+
+def softmax_rows(scores, probs, nmat, s, causal, stream=None):
+    _check(lib().optimus_softmax_rows(_ptr(scores), _ptr(probs), nmat, s, int(causal), _stream(stream)), "optimus_softmax_rows")
+
+
+def softmax_rows_bwd(d_probs, probs, d_scores, nmat, s, causal, stream=None):
+    _check(lib().optimus_softmax_rows_bwd(_ptr(d_probs), _ptr(probs), _ptr(d_scores), nmat, s, int(causal), _stream(stream)),
+           "optimus_softmax_rows_bwd")
 
 
 def attention_fused_workspace_bytes(b, s, h, n, q) -> int:

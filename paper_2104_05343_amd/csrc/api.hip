@@ -570,6 +570,18 @@ int optimus_attention_bwd(const void* qkv, const void* probs, const void* d_attn
   return run_attention(true, qkv, probs, nullptr, d_attn, d_qkv, b, s, h, n, q, i, j, causal ? 1 : 0, dtype, ws, ws_bytes, stream);
 }
 
+int optimus_softmax_rows(const float* scores, void* probs, int64_t nmat, int s, int causal, void* stream) {
+  if (!scores || !probs) return OPTIMUS_EINVAL;
+  if (nmat < 1 || s < 4 || s % 4 || s > 4096 || nmat * s > 0x7fffffffLL) return OPTIMUS_ESHAPE;
+  return launch_softmax_fwd(scores, probs, (int)nmat, s, causal ? 1 : 0, as_stream(stream));
+}
+int optimus_softmax_rows_bwd(const float* d_probs, const void* probs, void* d_scores, int64_t nmat, int s, int causal,
+                             void* stream) {
+  if (!d_probs || !probs || !d_scores) return OPTIMUS_EINVAL;
+  if (nmat < 1 || s < 4 || s % 4 || s > 4096 || nmat * s > 0x7fffffffLL) return OPTIMUS_ESHAPE;
+  return launch_softmax_bwd(d_probs, probs, d_scores, (int)nmat, s, causal ? 1 : 0, as_stream(stream));
+}
+
 size_t optimus_attention_fused_workspace_bytes(int b, int s, int h, int n, int q) {
   AttnDims a;
   if (attn_fused_dims(b, s, h, n, q, &a)) return 0;
@@ -763,8 +775,13 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   optimus_epilogue e = {};
   optimus_epilogue e32 = {};
   e32.out_fp32 = 1;
-#define RUN(...) if ((rc = (__VA_ARGS__))) return rc
-#define BRANCH_AFTER_MAIN(EV) if (ss) RUN(stream_after(gst, st, EV))
+  // After the fork the branch stream depends on the caller's stream; whatever happens afterwards, the caller's stream
+  // must be joined with it again before this call returns (a stream capture that is left forked cannot be ended).
+  // So the first failing step only switches the remaining steps off, and the join below still runs.
+  rc = OPTIMUS_OK;
+  bool forked = false;
+#define RUN(...) do { if (rc == OPTIMUS_OK) rc = (__VA_ARGS__); } while (0)
+#define BRANCH_AFTER_MAIN(EV) do { if (ss && rc == OPTIMUS_OK) { rc = stream_after(gst, st, EV); forked = forked || rc == OPTIMUS_OK; } } while (0)
   BRANCH_AFTER_MAIN(ss->fork);
   // ---- out = h_mid + gelu W2 + b2 ----
   e = {}; e.gelu_grad_of = t->pre_gelu;  // d_pre = (d_out W2^T) * GeLU'(pre)
@@ -795,10 +812,13 @@ int optimus_layer_bwd(const optimus_layer_cfg* c, const optimus_layer_tensors* t
   // ---- LN1 backward, plus the residual branch: d_x = d_h_mid + LN1'(d_ln1_out) ----
   RUN(ln_backward(t->d_ln1_out, t->xhat1, t->rstd1, t->ln1_g, t->d_h_mid, t->d_x, t->d_ln1_g, t->d_ln1_b, t->bstats1, ln, grid, st));
   // the caller's stream owns every result again
-  if (ss) RUN(stream_after(st, gst, ss->join));
+  if (ss && forked) {
+    const int jr = stream_after(st, gst, ss->join);
+    if (rc == OPTIMUS_OK) rc = jr;
+  }
 #undef BRANCH_AFTER_MAIN
 #undef RUN
-  return OPTIMUS_OK;
+  return rc;
 }
 
 int64_t optimus_gemm_flops(int64_t M, int64_t K, int64_t N, int q) {

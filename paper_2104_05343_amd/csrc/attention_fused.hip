@@ -153,7 +153,7 @@ struct PairLoader {
 #pragma unroll
       for (int it = 0; it < PER; ++it) {
         const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)(wave * PER + it) * 1024u);
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off[it]), "s"(rsrc), "s"(m0v) : "memory");
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(off[it]), "s"(rsrc), "s"(m0v) : "memory", "m0");
       }
     } else {  // the tile reaches past the last row: clamp (wave-uniform branch, taken for the last pair only)
       const int base_row = max(0, s - PAIR);
@@ -162,7 +162,7 @@ struct PairLoader {
       for (int it = 0; it < PER; ++it) {
         const unsigned o = offset_of(it, row0, s - 1, base_row);
         const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)(wave * PER + it) * 1024u);
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(o), "s"(rsrc), "s"(m0v) : "memory");
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(o), "s"(rsrc), "s"(m0v) : "memory", "m0");
       }
     }
   }

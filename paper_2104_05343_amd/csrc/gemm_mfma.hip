@@ -141,7 +141,7 @@ __device__ __forceinline__ void direct_issue(i32x4 rsrc, unsigned soff, const un
   for (int it = 0; it < PER; ++it) {
     const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)(wave * PER + it) * 1024u);
     asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds" ::"v"(off[it]), "s"(rsrc), "s"(soff), "s"(m0v)
-                 : "memory");
+                 : "memory", "m0");
   }
 }
 
@@ -150,7 +150,7 @@ __device__ __forceinline__ void direct_issue_one(i32x4 rsrc, unsigned soff, unsi
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)lds_unit;
   const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)c * 1024u);
   asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds" ::"v"(off), "s"(rsrc), "s"(soff), "s"(m0v)
-               : "memory");
+               : "memory", "m0");
 }
 
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt left at their maxima), gfx9 encoding.  The builtin rather than inline

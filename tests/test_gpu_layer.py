@@ -8,44 +8,32 @@ from oracle import layer as olayer
 from oracle.metrics import rel_frobenius
 from workloads import LayerShape, layer_inputs, CONFIGS
 from gpu_util import to_host
-from layer_util import (alloc_layer, fetch, oracle_vec_partials, FWD_OUT, BWD_OUT, FP32_MATS, VEC_PART, MAT_SHAPES)
+from layer_util import (alloc_layer, fetch, compare_all, TOL, FWD_OUT, BWD_OUT, FP32_MATS, MAT_SHAPES)
 
 pytestmark = pytest.mark.gpu
-# Per-stage tolerance for bf16 inputs with fp32 accumulation: asserted against the storage-aware oracle, whose
-# every stage reads exactly the bf16 values the device stored (stage arithmetic in fp64).
-TOL = 5e-3
-# Against the exact oracle (no rounding anywhere) the chain of up to ~13 bf16-stored tensors between the inputs
-# and the deepest gradients accumulates: each storage rounding alone is ~1.6e-3 relative, and roundings that
-# feed the soft-max logits are amplified.  This bound is three per-stage tolerances; errors are printed.
-TOL_EXACT_CHAIN = 1.5e-2
+# Every comparison below is against the exact oracle (fp64, nothing rounded anywhere).  Bounds per tensor:
+# layer_util.bound -- 5e-3, and the stated wider bound for the gradients behind the soft-max logits.
 
 
-def _oracles(inp, shp, causal, keep_probs=True):
-    """(exact fp64 oracle, storage-aware oracle) as (fwd, bwd) pairs."""
+def _oracle(inp, shp, causal, keep_probs=True):
     fe = olayer.forward(inp, shp.b, shp.s, shp.n, causal=causal, keep_probs=keep_probs)
     be = olayer.backward(inp, fe, shp.b, shp.s, shp.n, causal=causal)
-    fs = olayer.forward(inp, shp.b, shp.s, shp.n, causal=causal, storage="bf16")
-    bs = olayer.backward(inp, fs, shp.b, shp.s, shp.n, causal=causal, storage="bf16")
-    return (fe, be), (fs, bs)
+    return fe, be
 
 
-def _compare_all(T, shp, inp, fwd_o, bwd_o, tol=TOL):
-    worst = {}
-    for name in FWD_OUT:
-        worst[name] = rel_frobenius(fetch(T, name, shp), fwd_o[name])
-    for name in BWD_OUT + FP32_MATS:
-        worst[name] = rel_frobenius(fetch(T, name, shp), bwd_o[name])
-    q, rows = shp.q, shp.M // shp.q
-    for k in ("1", "2"):
-        r = to_host(T["rstd" + k]).reshape(q, q, rows)
-        want = fwd_o["rstd" + k].reshape(q, 1, rows).repeat(q, axis=1)
-        worst["rstd" + k] = rel_frobenius(r, want)
-    for name in VEC_PART:
-        got = to_host(T[name]).reshape(q, q, -1)
-        worst[name] = rel_frobenius(got, oracle_vec_partials(name, bwd_o, fwd_o, inp, shp))
-    bad = {k: v for k, v in worst.items() if not (v <= tol)}
-    assert not bad, f"over tolerance {tol}: {bad}\nall: {worst}"
-    return worst
+def _scale_weights(inp, shp):
+    """Weights larger than the benchmark recipe's N(0, 0.02^2), which at these small h would leave the attention
+    and MLP branches without signal: scaled so that a projection of an N(0,1) row has standard deviation 0.9
+    whatever h (soft-max logits of standard deviation about 0.8; the full-size tests cover the benchmark
+    layers' own scale, 1.6)."""
+    from workloads import round_to_bf16
+    f = 4.0 * (128.0 / shp.h) ** 0.5
+    for k in ("w_qkv", "w_o", "w1", "w2"):
+        inp[k] = round_to_bf16(inp[k] * f)
+
+
+def _fmt(w):
+    return {k: f"{v:.2e}" for k, v in w.items()}
 
 
 # several tiles + ragged sizes (h/q = 72 is not a tile multiple), q = 1 (no partition), q = 2, 4
@@ -57,21 +45,14 @@ SMALL = [LayerShape(b=4, s=64, h=128, n=4, q=2), LayerShape(b=2, s=136, h=144, n
 @pytest.mark.parametrize("causal", [True, False])
 def test_layer_grid_and_device_mode(shp, causal):
     inp = layer_inputs(11, shp, "bf16", perturb_affine=True)
-    # weights a little larger than the benchmark recipe so that every branch carries signal
-    for k in ("w_qkv", "w_o", "w1", "w2"):
-        from workloads import round_to_bf16
-        inp[k] = round_to_bf16(inp[k] * 4.0)
-    (fe, be), (fs, bs) = _oracles(inp, shp, causal)
+    _scale_weights(inp, shp)
+    fe, be = _oracle(inp, shp, causal)
     cfg, T, lt, ws = alloc_layer(inp, shp, causal)
     opt.layer_fwd(cfg, lt, -1, -1, ws)
     opt.layer_bwd(cfg, lt, -1, -1, ws)
     torch.cuda.synchronize()
-    w_s = _compare_all(T, shp, inp, fs, bs, TOL)
-    w_e = _compare_all(T, shp, inp, fe, be, TOL_EXACT_CHAIN)
-    print("max err vs storage-aware oracle %.2e, vs exact oracle %.2e" % (max(w_s.values()), max(w_e.values())))
-    # the short chains stay inside the per-stage tolerance even against the exact oracle
-    for k in ("ln1_out", "xhat1", "qkv", "h_mid", "ln2_out", "xhat2", "pre_gelu", "gelu", "out", "d_pre_gelu", "d_w2", "d_b2"):
-        assert w_e[k] <= TOL, (k, w_e[k])
+    w_e = compare_all(T, shp, inp, fe, be)
+    print("vs exact oracle:", _fmt(w_e))
 
     # device mode: recompute one device's blocks from the resident peers; bits must not change anywhere
     snap = {k: v.clone() for k, v in T.items()}
@@ -96,20 +77,15 @@ def test_layer_with_fused_attention(shp, causal):
     from oracle import attention as oatt
     from workloads import round_to_bf16
     inp = layer_inputs(13, shp, "bf16", perturb_affine=True)
-    for k in ("w_qkv", "w_o", "w1", "w2"):
-        inp[k] = round_to_bf16(inp[k] * 4.0)
-    (fe, be), (fs, bs) = _oracles(inp, shp, causal)
+    _scale_weights(inp, shp)
+    fe, be = _oracle(inp, shp, causal)
     cfg, T, lt, ws = alloc_layer(inp, shp, causal, fused=True)
     assert "probs" not in T and cfg.fused_attention == 1
     opt.layer_fwd(cfg, lt, -1, -1, ws)
     opt.layer_bwd(cfg, lt, -1, -1, ws)
     torch.cuda.synchronize()
-    # whole chain against the exact oracle (the storage-aware oracle models the stored probabilities of the other
-    # attention path, so it is used only up to the attention's input here)
-    w_e = _compare_all(T, shp, inp, fe, be, TOL_EXACT_CHAIN)
-    print("fused: max err vs exact oracle %.2e" % max(w_e.values()))
-    for k in ("ln1_out", "xhat1", "qkv"):
-        assert rel_frobenius(fetch(T, k, shp), fs[k]) <= TOL, k
+    w_e = compare_all(T, shp, inp, fe, be)
+    print("fused, vs exact oracle:", _fmt(w_e))
     # the attention stage by itself, from the values the device stored for its inputs, to the per-stage tolerance
     qkv_dev = fetch(T, "qkv", shp)
     attn_o, _ = oatt.forward(qkv_dev, shp.b, shp.s, shp.n, causal, keep_probs=False)
@@ -170,15 +146,13 @@ def test_layer_config2_full_size():
     then the timed launch configuration (one device, resident peers) reproduces its blocks bit for bit."""
     shp = CONFIGS["config2"]["layer"]
     inp = layer_inputs(CONFIGS["config2"]["seed"], shp, "bf16")
-    (fe, be), (fs, bs) = _oracles(inp, shp, True, keep_probs=False)
+    fe, be = _oracle(inp, shp, True, keep_probs=False)
     cfg, T, lt, ws = alloc_layer(inp, shp, True)
     opt.layer_fwd(cfg, lt, -1, -1, ws)
     opt.layer_bwd(cfg, lt, -1, -1, ws)
     torch.cuda.synchronize()
-    w_s = _compare_all(T, shp, inp, fs, bs, TOL)
-    w_e = _compare_all(T, shp, inp, fe, be, TOL_EXACT_CHAIN)
-    print("config2 full size, vs storage-aware oracle:", {k: f"{v:.2e}" for k, v in w_s.items()})
-    print("config2 full size, vs exact oracle:", {k: f"{v:.2e}" for k, v in w_e.items()})
+    w_e = compare_all(T, shp, inp, fe, be)
+    print("config2 full size, vs exact oracle:", _fmt(w_e))
     snap = {k: v.clone() for k, v in T.items()}
     opt.layer_fwd(cfg, lt, 3, 1, ws)
     opt.layer_bwd(cfg, lt, 3, 1, ws)

@@ -72,13 +72,14 @@ def test_forward_backward_grid(M, H, q, dtype):
     assert rel_frobenius(mat_to_host(DX, M, H, q), dx_o + dres) <= tol
     g_part, b_part = to_host(dgp).reshape(q, q, cols), to_host(dbp).reshape(q, q, cols)
     # summing the partials over the grid rows is the reduce to row 0
-    assert rel_frobenius(g_part.sum(axis=0).reshape(-1), dg_o) <= 1e-4
-    assert rel_frobenius(b_part.sum(axis=0).reshape(-1), db_o) <= 1e-4
+    ptol = 1e-5 if dtype == "fp32" else 1e-4      # fp32 path: 1e-5; bf16 inputs summed in fp32
+    assert rel_frobenius(g_part.sum(axis=0).reshape(-1), dg_o) <= ptol
+    assert rel_frobenius(b_part.sum(axis=0).reshape(-1), db_o) <= ptol
     for i in range(q):
         for j in range(q):
             rs, cs = slice(i * rows, (i + 1) * rows), slice(j * cols, (j + 1) * cols)
             want = (dy[rs, cs].astype(np.float64) * xh_in[rs, cs]).sum(axis=0)
-            assert rel_frobenius(g_part[i, j], want) <= 1e-4
+            assert rel_frobenius(g_part[i, j], want) <= ptol
     # without the residual-branch gradient
     DX2 = empty(M * H, dtype)
     opt.layernorm2d_bwd(dDY, dXH, to_dev(rstd_in, "fp32"), dG, None, DX2, None, None, bst, M, H, q, -1, -1, dt(dtype))

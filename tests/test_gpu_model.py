@@ -10,6 +10,7 @@ from oracle import layernorm as oln, model_ends as me, stack as ostack
 from oracle.metrics import rel_frobenius
 from workloads import LayerShape, layer_inputs, round_to_bf16, token_inputs
 from gpu_util import mat_to_dev, mat_to_host, to_host, vec_to_dev, empty
+from layer_util import TOL_BEHIND_LOGITS
 
 pytestmark = pytest.mark.gpu
 MATS = ("w_qkv", "w_o", "w1", "w2")
@@ -104,8 +105,8 @@ def test_tokens_to_loss_and_back(fused):
         err[f"L{l}.d_w_qkv"] = rel_frobenius(mat_to_host(grads[l]["d_w_qkv"], h, 3 * h, q), grads_o[l]["d_w_qkv"])
     print("tokens -> loss -> table gradient, relative errors against the exact oracle chain:", {k: f"{e:.1e}" for k, e in err.items()})
     assert err["x0"] == 0.0
-    # Exact-oracle chain bound: 3 * 5e-3 per layer (tests of the layer and of the stack); this chain is the L layers plus
-    # the two ends, i.e. L + 1 such units on the way out and back.
-    tol = 3 * 5e-3 * (L + 1)
+    # Exact-oracle chain bound: as for the stack (tests of the stack), with the two model ends counted as one more
+    # layer: TOL_BEHIND_LOGITS * sqrt(2 (L + 1)).
+    tol = TOL_BEHIND_LOGITS * float(np.sqrt(2 * (L + 1)))
     assert all(e <= tol for e in err.values()), err
     assert err["mean_loss"] <= 5e-3

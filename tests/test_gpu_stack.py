@@ -9,10 +9,9 @@ from oracle import stack as ostack
 from oracle.metrics import rel_frobenius
 from workloads import LayerShape, layer_inputs, round_to_bf16
 from gpu_util import mat_to_dev, mat_to_host, to_host, vec_to_dev, empty
-from layer_util import alloc_layer, MAT_SHAPES
+from layer_util import alloc_layer, MAT_SHAPES, TOL_BEHIND_LOGITS
 
 pytestmark = pytest.mark.gpu
-TOL = 5e-3            # per stage, bf16 inputs with fp32 accumulation (against the storage-aware oracle)
 MATS = ("w_qkv", "w_o", "w1", "w2")
 VEC_MULT = {"d_b_qkv": 3, "d_b_o": 1, "d_b1": 4, "d_b2": 1, "d_ln1_g": 1, "d_ln1_b": 1, "d_ln2_g": 1, "d_ln2_b": 1}
 
@@ -51,14 +50,14 @@ def test_stack_against_oracle_and_layerwise_run(shp, L, fused):
     M, h, q = shp.M, shp.h, shp.q
     layers, x, d_out = _inputs(21, shp, L)
     params_o = [{k: inp[k] for k in ostack.PARAM_NAMES} for inp in layers]
-    storage = None if fused else "bf16"     # the storage-aware oracle models the stored probabilities of the unfused path
-    out_o, ck_o = ostack.forward(params_o, x, shp.b, shp.s, shp.n, True, storage)
-    dx_o, grads_o = ostack.backward(params_o, ck_o, d_out, shp.b, shp.s, shp.n, True, storage)
-    # One layer is held to TOL per stage against the storage-aware oracle and to 3 * TOL along its chain against the
-    # exact one (tests of the layer).  A stack is L such chains end to end (the deepest gradient has passed through
-    # all of them twice), so its bound is L times the layer's; the sharper statement is the bit-for-bit comparison
-    # with the layer-by-layer run below, whose every layer is covered by the layer tests.
-    tol = (TOL if not fused else 3 * TOL) * L
+    out_o, ck_o = ostack.forward(params_o, x, shp.b, shp.s, shp.n, True)
+    dx_o, grads_o = ostack.backward(params_o, ck_o, d_out, shp.b, shp.s, shp.n, True)
+    # Against the exact oracle (nothing rounded).  One layer's deepest gradients are held to TOL_BEHIND_LOGITS (tests
+    # of the layer); in a stack the input gradient and the first layer's parameter gradients have passed through all
+    # L layers forward and back, each adding its own independent rounding error, so the bound grows with the
+    # number of layer passes behind a tensor: TOL_BEHIND_LOGITS * sqrt(2 L).  The sharper statement is the bit-for-bit
+    # comparison with the layer-by-layer run below, whose every layer is covered by the layer tests.
+    tol = TOL_BEHIND_LOGITS * float(np.sqrt(2 * L))
 
     cfg = opt.LayerCfg(shp.b, shp.s, shp.h, shp.n, shp.q, 1e-5, 1, opt.BF16, 1 if fused else 0)
     dev_params = []
@@ -88,7 +87,7 @@ def test_stack_against_oracle_and_layerwise_run(shp, L, fused):
             worst[f"L{l}.{k}"] = rel_frobenius(got, grads_o[l][k])
     bad = {k: v for k, v in worst.items() if not (v <= tol)}
     assert not bad, f"over tolerance {tol}: {bad}\nall: {worst}"
-    print("stack worst error %.2e" % max(worst.values()))
+    print("stack worst error %.2e (bound %.2e)" % (max(worst.values()), tol), {k: f"{v:.1e}" for k, v in worst.items()})
 
     # the same layers one by one, every tensor kept, no recomputation: the stack must reproduce these bits
     cur = X

@@ -314,12 +314,12 @@ def test_full_size_one_device_sampled(name, g):
     blk = to_host(dC[(i * q + j) * mb * nb:(i * q + j + 1) * mb * nb]).reshape(mb, nb)
     rows = np.unique(np.concatenate([[0, mb - 1], np.random.default_rng(1).integers(0, mb, 30)]))
     cols = slice(j * nb, (j + 1) * nb)
-    Bsub = (B[cols, :].T if g.form == "abt" else B[:, cols]).astype(np.float64)   # [K, nb]
-    for r in rows:
-        R = i * mb + r
-        a_row = (A[:, R] if g.form == "atb" else A[R, :]).astype(np.float64)
-        want = a_row @ Bsub
-        assert rel_frobenius(blk[r], want) <= TOL["bf16"], (name, g.name, r)
+    R = i * mb + rows
+    a_rows = A[:, R] if g.form == "atb" else A[R, :]              # the operand slices the sampled output rows depend on
+    b_cols = B[cols, :] if g.form == "abt" else B[:, cols]
+    want = summa.product(g.form, a_rows, b_cols)                 # [len(rows), nb]
+    for k, r in enumerate(rows):
+        assert rel_frobenius(blk[r], want[k]) <= TOL["bf16"], (name, g.name, r)
     # nothing outside block (i, j) was touched
     full = dC.view(torch.int16)
     assert int(torch.count_nonzero(full[:(i * q + j) * mb * nb])) == 0

@@ -130,3 +130,20 @@ def test_backward_row_term_equals_output_form():
             P2 = np.exp(S - att.head_logsumexp(Q, K, causal)[:, None])
         for a_, b_ in zip(att.head_backward(Q, K, V, P, dO), att.head_backward(Q, K, V, P2, dO)):
             assert np.allclose(a_, b_, atol=1e-13)
+
+
+def test_softmax_rows_backward_finite_differences():
+    """dS = P * (dP - rowsum(dP * P)) is the gradient of <R, softmax_rows(S)> (central differences in fp64)."""
+    rng = np.random.default_rng(5)
+    S = rng.standard_normal((5, 7))
+    R = rng.standard_normal((5, 7))
+    got = att.softmax_rows_backward(att.softmax_rows(S), R)
+    eps = 1e-6
+    for (r, c) in [(0, 0), (2, 3), (4, 6), (1, 5)]:
+        Sp, Sm = S.copy(), S.copy()
+        Sp[r, c] += eps
+        Sm[r, c] -= eps
+        fd = (np.sum(R * att.softmax_rows(Sp)) - np.sum(R * att.softmax_rows(Sm))) / (2 * eps)
+        assert abs(fd - got[r, c]) < 1e-8
+    # each row of dS sums to zero (a soft-max row is invariant to adding a constant to its logits)
+    assert np.allclose(got.sum(axis=1), 0.0, atol=1e-14)
