@@ -222,6 +222,21 @@ int optimus_attention_fused_bwd(const void* qkv, const void* attn, const float* 
                                 int dtype, void* ws, size_t ws_bytes, void* stream);
 size_t optimus_attention_fused_workspace_bytes(int b, int s, int h, int n, int q);
 
+/* ---- optimus_attention_fused_bwd for callers that cannot allocate ----
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the same operation,
+ * arguments, layouts and results (bit for bit) as optimus_attention_fused_bwd, without the ws argument.  The one
+ * scratch buffer of that call (one fp32 per query row of every (sequence, head) matrix of the launch) lives in a
+ * static device array of OPTIMUS_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process
+ * ends; the call allocates and frees nothing.  A launch that needs more -- (i = j = -1 ? q*q : 1) * (b/q) * (n/q)
+ * * s * 4 bytes -- is rejected with OPTIMUS_EWORKSPACE before anything is enqueued.  All calls on one GPU share
+ * the array (it keeps the last call's contents; every call overwrites what it reads, nothing needs clearing):
+ * two calls that overlap on one GPU (different streams, several host threads) race on it.  The array's address
+ * is looked up on the first call made with a device current; make that first call outside stream capture. */
+#define OPTIMUS_STATIC_SCRATCH_BYTES (4u << 20)
+int optimus_attention_fused_bwd_static(const void* qkv, const void* attn, const float* lse, const void* d_attn,
+                                       void* d_qkv, int b, int s, int h, int n, int q, int i, int j,
+                                       int causal, int dtype, void* stream);
+
 /* ---- one transformer layer on device (i, j) (Section 3.2; Eq. 1) ----
  * Wiring: a1 = LN1(x); qkv = a1 Wqkv + b; attn = local attention;
  * h_mid = x + attn Wo + b; a2 = LN2(h_mid); pre = a2 W1 + b; g = GeLU(pre);

@@ -17,6 +17,7 @@ OK, EINVAL, ESHAPE, ECOORD, EDTYPE, EWORKSPACE, EHIP = range(7)
 FP32, BF16 = 0, 1
 FORM_AB, FORM_ABT, FORM_ATB = 0, 1, 2
 ALL = -1
+STATIC_SCRATCH_BYTES = 4 << 20   # OPTIMUS_STATIC_SCRATCH_BYTES: the most scratch optimus_attention_fused_bwd_static can serve
 FORMS = {"ab": FORM_AB, "abt": FORM_ABT, "atb": FORM_ATB}
 
 
@@ -104,6 +105,7 @@ SIGNATURES = {
     "optimus_attention_fused_fwd": (_INT, [_P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P]),
     "optimus_attention_fused_bwd": (_INT, [_P, _P, _P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P, _SZ, _P]),
     "optimus_attention_fused_workspace_bytes": (_SZ, [_INT, _INT, _INT, _INT, _INT]),
+    "optimus_attention_fused_bwd_static": (_INT, [_P, _P, _P, _P, _P, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _INT, _P]),
     "optimus_embedding_fwd": (_INT, [_P, _P, _P, _I64, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
     "optimus_embedding_bwd": (_INT, [_P, _P, _P, _I64, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
     "optimus_cross_entropy2d_stats": (_INT, [_P, _P, _I64, _I64, _INT, _INT, _INT, _INT, _P]),
@@ -268,6 +270,11 @@ def attention_bwd(qkv, probs, d_attn, d_qkv, b, s, h, n, q, i, j, causal, dtype,
     p, nb = _ws(ws)
     _check(lib().optimus_attention_bwd(_ptr(qkv), _ptr(probs), _ptr(d_attn), _ptr(d_qkv), b, s, h, n, q, i, j, int(causal), dtype,
                                        p, nb, _stream(stream)), "optimus_attention_bwd")
+
+
+def attention_fused_bwd_static(qkv, attn, lse, d_attn, d_qkv, b, s, h, n, q, i, j, causal, dtype, stream=None):
+    _check(lib().optimus_attention_fused_bwd_static(_ptr(qkv), _ptr(attn), _ptr(lse), _ptr(d_attn), _ptr(d_qkv), b, s, h, n, q, i, j,
+                                                    int(causal), dtype, _stream(stream)), "optimus_attention_fused_bwd_static")
 
 
 def softmax_rows(scores, probs, nmat, s, causal, stream=None):

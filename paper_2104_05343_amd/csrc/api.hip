@@ -3,9 +3,17 @@
 // enqueues nothing on error.
 #include <math.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 using namespace optimus;
+
+// Scratch of the entry point that allocates nothing (optimus_attention_fused_bwd_static): one array per GPU the library
+// runs on, held until the process ends.  In host code the array's NAME is only a handle for hipGetSymbolAddress, never
+// a device address: every use goes through static_scratch(), which looks the address up once per device.
+constexpr size_t kStaticScratchBytes = OPTIMUS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -388,6 +396,23 @@ int stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
   return OPTIMUS_OK;
 }
 
+// Device address of `scratch` on the current device (each GPU holds its own copy at its own address): looked up on
+// the first call made with that device current, kept afterwards.
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return OPTIMUS_EHIP; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return OPTIMUS_EHIP; }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return OPTIMUS_OK;
+}
+
 // split workspace of one product as the layer plans it (corun: see GemmDesc)
 size_t summa_ws_bytes(int form, int64_t M, int64_t K, int64_t N, int q, int i, int j, int dtype, int corun) {
   if (form < 0 || form > 2 || check_mkn(M, K, N, q) || check_coords(q, i, j)) return 0;
@@ -597,6 +622,25 @@ int optimus_attention_fused_bwd(const void* qkv, const void* attn, const float* 
   if (!qkv || !attn || !lse || !d_attn || !d_qkv) return OPTIMUS_EINVAL;
   return run_attention_fused(true, qkv, const_cast<void*>(attn), const_cast<float*>(lse), d_attn, d_qkv, b, s, h, n, q, i, j,
                              causal ? 1 : 0, dtype, ws, ws_bytes, stream);
+}
+
+int optimus_attention_fused_bwd_static(const void* qkv, const void* attn, const float* lse, const void* d_attn, void* d_qkv, int b,
+                                       int s, int h, int n, int q, int i, int j, int causal, int dtype, void* stream) {
+  if (!qkv || !attn || !lse || !d_attn || !d_qkv) return OPTIMUS_EINVAL;
+  if (dtype != OPTIMUS_BF16) return OPTIMUS_EDTYPE;
+  AttnDims a;
+  int rc = attn_fused_dims(b, s, h, n, q, &a);
+  if (rc) return rc;
+  if ((rc = check_coords(q, i, j))) return rc;
+  // one fp32 per query row of every matrix of the launch (one device's, or the whole grid's)
+  const size_t need = (size_t)(is_grid(i, j) ? q * q : 1) * (size_t)a.nmat * (size_t)s * sizeof(float);
+  if (need > kStaticScratchBytes) return OPTIMUS_EWORKSPACE;
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  // the kernels index the scratch by the launch's own device count, so `need` bytes are all they touch; the size
+  // check of the shared code path is against the whole-grid size, which the array is not required to hold
+  return run_attention_fused(true, qkv, const_cast<void*>(attn), const_cast<float*>(lse), d_attn, d_qkv, b, s, h, n, q, i, j,
+                             causal ? 1 : 0, dtype, ws, attn_fused_ws_bytes(a, q), stream);
 }
 
 size_t layer_attn_ws(const optimus_layer_cfg* c, const AttnDims& a) {
