@@ -94,11 +94,10 @@ int run_summa(int form, const void* A, const void* B, void* C, int64_t M, int64_
   GemmDesc d = summa_desc(form, A, B, C, M, K, N, q, i, j, dtype, epi);
   d.corun = corun;
   if (gemm_mfma_supported(d)) {
-    int s = gemm_pick_splits(d);
-    if (s > 1 && ws && ws_bytes >= gemm_partials_bytes(d, s)) {
-      d.splits = s;
-      d.partials = (float*)ws;
-    }
+    // a planned panel split writes its partial tiles to the workspace if it is there and large enough; otherwise the
+    // same split is emulated inside the workgroups: the bits of a result do not depend on the workspace
+    const size_t need = gemm_plan_bytes(d);
+    if (need > 0 && ws && ws_bytes >= need) d.partials = (float*)ws;
   }
   return launch_gemm(d, as_stream(stream));
 }
@@ -421,7 +420,7 @@ size_t summa_ws_bytes(int form, int64_t M, int64_t K, int64_t N, int q, int i, i
   GemmDesc d = summa_desc(form, (const void*)256, (const void*)256, (void*)256, M, K, N, q, i, j, dtype, nullptr);
   d.corun = corun;
   if (!gemm_mfma_supported(d)) return 0;
-  return gemm_partials_bytes(d, gemm_pick_splits(d));
+  return gemm_plan_bytes(d);
 }
 
 size_t layer_gemm_ws(const optimus_layer_cfg* c) {

@@ -31,6 +31,8 @@
 // The two MFMA operands are swapped (D^T = B^T A^T) so that every lane ends up with four
 // consecutive columns of one output row; results leave through wavefront-private LDS chunks as
 // whole rows of the tile (see ChunkBf16).
+#include <type_traits>
+
 #include "common.hpp"
 #include "epilogue.hpp"
 
@@ -43,15 +45,24 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 static int g_variant = -1;
-void gemm_set_variant(int v) { g_variant = v; }
+static int g_loop = 2;   // k-loop of the fast path where both exist (see gemm_mfma_kernel); 1 or 2
+void gemm_set_variant(int v) {
+  // v >= 1000: the older k-loop with variant v - 1000 (1000 + 255 = automatic tile); otherwise the default k-loop
+  if (v >= 1000) { g_loop = 1; v -= 1000; if (v == 255) v = -1; } else g_loop = 2;
+  g_variant = v;
+}
 int gemm_get_variant() { return g_variant; }
 static int g_corun_variant[2] = {-1, -1};
 void gemm_set_corun_variants(int chain_v, int branch_v) { g_corun_variant[0] = chain_v; g_corun_variant[1] = branch_v; }
 static int g_last_plan = -1;
 int gemm_last_plan() { return g_last_plan; }
 
+
 constexpr int BK = 32;
 constexpr int NSTAGE = 4;
+#ifndef OPTIMUS_LAB_DBG
+#define OPTIMUS_LAB_DBG 0
+#endif
 
 struct KArgs {
   const bf16_t* A;
@@ -423,15 +434,27 @@ struct Occ {
 // PLAIN (FAST only) = the epilogue is a bare store of the accumulator (alpha 1, no bias / activation / residual):
 // a short, fully unrolled store sequence instead of the general epilogue, whose straight-line code costs
 // microseconds per tile.
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST, bool PLAIN, bool SEQ = false>
+// LOOP selects the k-loop of the fast path: 1 = ring of four 32-wide slabs, fragments read one sub-step ahead
+// (the loop described above); 2 = stages of 64 k, the fragments of a whole stage read into registers while the
+// matrix cores work on the registers of the stage before it (see the loop).
+template <int BM, int BN>
+struct Loop2 {
+  // three stages where one workgroup owns the CU anyway (the 384-row tiles: 144 KiB); two stages otherwise, which is the
+  // LDS footprint of the four-slab ring, so that as many workgroups share a CU as with it
+  static constexpr int NST = (BM + BN == 384) ? 3 : 2;
+  static constexpr int RING32 = 2 * NST;                                        // the same space in 32-wide slabs
+};
+
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST, bool PLAIN, bool SEQ = false, int LOOP = 1>
 __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gemm_mfma_kernel(const KArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
   static_assert(!SEQ || (FAST && !PLAIN), "the range-wise accumulation exists on the fast path with the full epilogue");
+  static_assert(LOOP == 1 || FAST, "the register-staged loop exists on the fast path");
   using T = Tile<BM, BN, WM, WN>;
   constexpr int THREADS = T::THREADS, NW = T::NW;
   constexpr int TM = T::TM, TN = T::TN, MI = T::MI, NI = T::NI;
   // one ring of four slabs per operand (see read_frag_ring); the ragged path uses the first two slabs as two stages
-  constexpr int RING = FAST ? NSTAGE : 2;
+  constexpr int RING = FAST ? (LOOP == 2 ? Loop2<BM, BN>::RING32 : NSTAGE) : 2;
   constexpr int LDS_BYTES = RING * (T::A_ELEMS + T::B_ELEMS) * 2;
   __shared__ __attribute__((aligned(1024))) bf16_t lds_all[RING * (T::A_ELEMS + T::B_ELEMS)];
   bf16_t* const ldsA = lds_all;
@@ -521,7 +544,194 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
   if (t_lo < t_hi) {
     // slab index -> (panel l, offset k0 inside the panel); advanced incrementally
     int l = t_lo / tpp, k0 = (t_lo - l * tpp) * BK;
-    if constexpr (FAST) {
+    if constexpr (FAST && LOOP == 2) {
+      // ---- stages of 64 k ----
+      // LDS holds NST stages of [BM x 64] + [64 x BN].  An iteration (one stage, four 16-wide sub-steps) has two halves:
+      //   first half:  matrix-core instructions of sub-steps 0, 1 (registers h0) | LDS reads of sub-steps 2, 3 (-> h1)
+      //   wait + barrier: my reads of stage i are done (nobody reads it any more), my share of stage i+1 has landed
+      //   second half: matrix-core instructions of sub-steps 2, 3 (h1) | LDS reads of sub-steps 0, 1 of stage i+1 (-> h0)
+      //                | the loads of stage i+NST into the space stage i has left
+      // One wait and one barrier per 64 k; the reads have had half an iteration to complete and the loads NST-1
+      // iterations, so neither wait is normally exposed.  The memory instructions of a half are spread between its
+      // matrix-core instructions: issued in one burst they fill the CU's LDS and memory-instruction queues, and a
+      // wavefront that waits for queue space issues no matrix-core instruction either.
+      constexpr int NST = Loop2<BM, BN>::NST;
+      constexpr int PA1 = DirectPlan<BM, NW>::PER, PB1 = DirectPlan<BN, NW>::PER;   // KiB chunks per wavefront per 32 k
+      constexpr int NOA = AKC ? 2 * PA1 : PA1, NOB = BKC ? 2 * PB1 : PB1;             // distinct lane offsets
+      constexpr int LP = 2 * PA1 + 2 * PB1;                                          // loads per wavefront per stage
+      constexpr int A_ST = BM * 64, B_ST = BN * 64;                                  // elements per stage
+      unsigned offA[NOA], offB[NOB];
+      direct_offsets<BM, AKC, NW, NOA>(offA, a.lda, wave, lane);
+      direct_offsets<BN, BKC, NW, NOB>(offB, a.ldb, wave, lane);
+      bf16_t* const stA = lds_all;
+      bf16_t* const stB = lds_all + NST * A_ST;
+      const unsigned stepA = (unsigned)(AKC ? 64 : 64 * a.lda) * 2u, stepB = (unsigned)(BKC ? 64 : 64 * a.ldb) * 2u;
+      const unsigned halfA = (unsigned)(32 * a.lda) * 2u, halfB = (unsigned)(32 * a.ldb) * 2u;   // 32 k-rows of a k-strided operand
+      int lq = l, kq = k0;
+      i32x4 ra = make_rsrc(Atile + lq * a.sAl), rb = make_rsrc(Btile + lq * a.sBl);
+      unsigned sa = (unsigned)(AKC ? kq : kq * a.lda) * 2u, sb = (unsigned)(BKC ? kq : kq * a.ldb) * 2u;
+      const int n64 = (t_hi - t_lo) >> 1;
+      // load g (0 .. LP-1) of the stage that goes into LDS stage st: A's chunks first, then B's
+      auto load_item = [&](int st, int g) {
+        if (g < 2 * PA1) {
+          if constexpr (AKC) direct_issue_one(ra, sa, offA[g], stA + st * A_ST, wave * NOA + g);
+          else direct_issue_one(ra, sa + (unsigned)(g / PA1) * halfA, offA[g % PA1], stA + st * A_ST + (g / PA1) * 32 * BM, wave * PA1 + g % PA1);
+        } else {
+          const int h = g - 2 * PA1;
+          if constexpr (BKC) direct_issue_one(rb, sb, offB[h], stB + st * B_ST, wave * NOB + h);
+          else direct_issue_one(rb, sb + (unsigned)(h / PB1) * halfB, offB[h % PB1], stB + st * B_ST + (h / PB1) * 32 * BN, wave * PB1 + h % PB1);
+        }
+      };
+      auto advance = [&]() {
+        kq += 64;
+        if (kq >= a.Kp) { kq = 0; ++lq; sa = 0; sb = 0; ra = make_rsrc(Atile + lq * a.sAl); rb = make_rsrc(Btile + lq * a.sBl); }
+        else { sa += stepA; sb += stepB; }
+      };
+      auto issue_stage = [&](int st) {
+#pragma unroll
+        for (int g = 0; g < LP; ++g) load_item(st, g);
+        advance();
+      };
+      // fragments of one whole stage: four 16-wide sub-steps; item r = fragment (r % NF) of sub-step (r / NF).
+      // Every LDS address is a per-lane base computed once (the swizzles depend on the lane only) plus the stage's
+      // offset plus a constant, so that a read costs no address arithmetic inside the loop:
+      //   k-contiguous operand: one base per sub-step (chunk index XOR row term), fragment row blocks 32 * 128 bytes apart;
+      //   k-strided operand:    one base per fragment (column granule XOR row term), sub-steps 16 k-rows apart.
+      constexpr int NF = MI + NI, NRD = 4 * NF, NMF = 4 * MI * NI;
+      typedef __attribute__((address_space(3))) char lds_char;
+      lds_char* const lds3 = (lds_char*)lds_all;
+      unsigned fbaseA[AKC ? 4 : MI], fbaseB[BKC ? 4 : NI];
+      if constexpr (AKC) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) fbaseA[ks] = (unsigned)lds_off_kc2(wm * TM + (lane & 31), ks * 2 + (lane >> 5)) * 2u;
+      } else {
+        const int lg = lane & 15;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+          fbaseA[mi] = (unsigned)lds_off_ks<BM>(((lane >> 5) << 3) + (lg >> 2), wm * TM + mi * 32 + (((lane >> 4) & 1) << 4) + ((lg & 3) << 2)) * 2u;
+      }
+      if constexpr (BKC) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) fbaseB[ks] = (unsigned)(NST * A_ST + lds_off_kc2(wn * TN + (lane & 31), ks * 2 + (lane >> 5))) * 2u;
+      } else {
+        const int lg = lane & 15;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          fbaseB[ni] = (unsigned)(NST * A_ST + lds_off_ks<BN>(((lane >> 5) << 3) + (lg >> 2), wn * TN + ni * 32 + (((lane >> 4) & 1) << 4) + ((lg & 3) << 2))) * 2u;
+      }
+      bf16x8 ha[4][MI], hb[4][NI];   // [sub-step][fragment]: sub-steps 0, 1 = h0, sub-steps 2, 3 = h1
+      auto read_kc = [&](unsigned off) { return *(const __attribute__((address_space(3))) bf16x8*)(lds3 + off); };
+      auto read_ks = [&](unsigned off, int rows) {   // two transposing reads: k-rows r .. r+3 and r+4 .. r+7 of the lane's column group
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds3 + off));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds3 + off + 4 * rows * 2));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      };
+      auto read_item = [&](unsigned stoffA, unsigned stoffB, int ks, int f) {
+        if (f < MI) {
+          if constexpr (AKC) ha[ks][f] = read_kc(fbaseA[ks] + stoffA + (unsigned)(f * 32 * 128));
+          else ha[ks][f] = read_ks(fbaseA[f] + stoffA + (unsigned)(ks * 16 * BM * 2), BM);
+        } else {
+          const int n = f - MI;
+          if constexpr (BKC) hb[ks][n] = read_kc(fbaseB[ks] + stoffB + (unsigned)(n * 32 * 128));
+          else hb[ks][n] = read_ks(fbaseB[n] + stoffB + (unsigned)(ks * 16 * BN * 2), BN);
+        }
+      };
+      // one half of an iteration: the matrix-core instructions of sub-steps 2*HH, 2*HH+1; in front of each its share of
+      // the reads of the other two sub-steps (of stage st_rd) and, in the second half, of the loads into stage st_ld
+      constexpr int HM = 2 * MI * NI, HR = 2 * NF;
+      auto half = [&](auto hh_, auto with_reads, auto with_loads, int st_rd, int st_ld) {
+        constexpr int HH = decltype(hh_)::value;
+        const unsigned offA_rd = (unsigned)(st_rd * A_ST * 2), offB_rd = (unsigned)(st_rd * B_ST * 2);
+#pragma unroll
+        for (int m = 0; m < HM; ++m) {
+          if constexpr (decltype(with_reads)::value && !(OPTIMUS_LAB_DBG & 4)) {
+            // all reads in front of the first half of the matrix-core instructions: the wait that follows the last
+            // of them must not expose the latency of a read issued just before it
+            constexpr int RS = HM / 2 > 0 ? HM / 2 : 1;
+#pragma unroll
+            for (int r = m * HR / RS; r < (m + 1) * HR / RS && r < HR; ++r) read_item(offA_rd, offB_rd, 2 * (1 - HH) + r / NF, r % NF);
+          }
+          if constexpr (decltype(with_loads)::value && !(OPTIMUS_LAB_DBG & 1)) {
+#pragma unroll
+            for (int g = m * LP / HM; g < (m + 1) * LP / HM; ++g) load_item(st_ld, g);
+          }
+          if constexpr (!(OPTIMUS_LAB_DBG & 8)) {
+            const int ks = 2 * HH + m / (MI * NI), mi = (m / NI) % MI, ni = m % NI;
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hb[ks][ni], ha[ks][mi], acc[mi][ni], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (decltype(with_loads)::value) advance();
+      };
+      // prologue: the first NST stages, then the fragments of sub-steps 0, 1 of stage 0
+      issue_stage(0);
+      if (n64 > 1) issue_stage(1);
+      if (NST > 2 && n64 > 2) issue_stage(2);
+      {
+        const int younger = (n64 > NST ? NST : n64) - 1;
+        if (younger >= 2) OPTIMUS_WAIT_VMCNT(2 * LP);
+        else if (younger == 1) OPTIMUS_WAIT_VMCNT(LP);
+        else OPTIMUS_WAIT_VMCNT(0);
+      }
+      OPTIMUS_BARRIER();
+#pragma unroll
+      for (int r = 0; r < HR; ++r) read_item(0u, 0u, r / NF, r % NF);
+      int seq_next64 = seq_next >> 1;
+      const int seq_per64 = seq_per >> 1;
+      constexpr std::true_type yes{};
+      constexpr std::false_type no{};
+      constexpr std::integral_constant<int, 0> first{};
+      constexpr std::integral_constant<int, 1> second{};
+      int st_cur = 0, st_nxt = NST > 1 ? 1 : 0;
+      auto range_end = [&](int i) {   // SEQ: a range of the emulated panel split ends in front of stage i
+        if constexpr (SEQ) {
+          if (i == seq_next64 && i > 0) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+              for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                  tot[mi][ni][e] += acc[mi][ni][e];
+                  acc[mi][ni][e] = 0.f;
+                }
+            seq_next64 += seq_per64;
+          }
+        }
+      };
+      auto next_stage = [&]() {
+        st_cur = st_nxt;
+        st_nxt = st_nxt + 1 == NST ? 0 : st_nxt + 1;
+      };
+      // steady state: every iteration reads the next stage and refills the stage it leaves (straight-line body, constant
+      // wait counts: with branches inside the loop the compiler copies the accumulators between the paths)
+      int i = 0;
+      for (; i + NST < n64; ++i) {
+        range_end(i);
+        half(first, yes, no, st_cur, 0);
+        // stage i+1 has landed (stage i+2's loads stay in flight); my reads of stage i are done
+        if constexpr (!(OPTIMUS_LAB_DBG & 16)) OPTIMUS_WAIT_VMCNT_LGKM0(NST > 2 ? LP : 0);
+        if constexpr (!(OPTIMUS_LAB_DBG & 2)) OPTIMUS_BARRIER();
+        half(second, yes, yes, st_nxt, st_cur);
+        next_stage();
+      }
+      // the last stages: nothing left to load
+      for (; i + 1 < n64; ++i) {
+        range_end(i);
+        half(first, yes, no, st_cur, 0);
+        if (NST > 2 && i + 2 < n64) OPTIMUS_WAIT_VMCNT_LGKM0(LP);
+        else OPTIMUS_WAIT_VMCNT_LGKM0(0);
+        OPTIMUS_BARRIER();
+        half(second, yes, no, st_nxt, st_cur);
+        next_stage();
+      }
+      range_end(i);
+      half(first, yes, no, st_cur, 0);
+      half(second, no, no, st_nxt, st_cur);
+      // the results leave through LDS (see the epilogue): nobody may still be reading the last stage
+      OPTIMUS_WAIT_VMCNT_LGKM0(0);
+      OPTIMUS_BARRIER();
+    } else if constexpr (FAST) {
       // Loads per wavefront: a k-strided operand moves one slab per step; a k-contiguous operand moves a pair of
       // slabs (whole 128-byte lines per row) every second step.  The slab count of a workgroup is even (host).
       constexpr int PA1 = DirectPlan<BM, NW>::PER, PB1 = DirectPlan<BN, NW>::PER;
@@ -1033,8 +1243,10 @@ static const Variant kVariants[] = {
     {128, 128, 2, 2, false},  // 5: bounds-checked (ragged shapes)
     {128, 64, 2, 2, true},    // 6: 4 waves, wave tile 64x32: narrow outputs (attention with 64-wide heads)
     {64, 64, 2, 2, true},     // 7: 4 waves, wave tile 32x32: small blocks that need every CU (least bytes per CU)
+    {256, 128, 2, 2, true},   // 8: 4 waves, wave tile 128x64 (a quarter fewer LDS bytes per flop than variant 1)
+    {128, 256, 2, 2, true},   // 9: 4 waves, wave tile 64x128
 };
-constexpr int kNumVariants = 8;
+constexpr int kNumVariants = 10;
 constexpr int kGuardVariant = 5;
 
 template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool FAST>
@@ -1042,6 +1254,13 @@ static int launch_one(const KArgs& ka, long long nwg, hipStream_t stream) {
   const EpiArgs& e = ka.epi;
   if constexpr (FAST && BM * BN < 256 * 256) {  // (the 256x256 tile has no registers for a second accumulator)
     if (ka.seq_splits > 1) {
+      if constexpr (BM + BN >= 384) {
+        if (g_loop == 2) {
+          hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, AKC, BKC, true, false, true, 2>), dim3((unsigned)nwg), dim3(WM * WN * 64),
+                             0, stream, ka);
+          return hip_launch_status();
+        }
+      }
       hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, AKC, BKC, true, false, true>), dim3((unsigned)nwg), dim3(WM * WN * 64), 0,
                          stream, ka);
       return hip_launch_status();
@@ -1049,6 +1268,19 @@ static int launch_one(const KArgs& ka, long long nwg, hipStream_t stream) {
   }
   if (ka.seq_splits > 1) return OPTIMUS_EINVAL;
   const bool plain = FAST && ka.splits == 1 && e.alpha == 1.0f && !e.bias && !e.pre_act && !e.act && !e.gelu_grad_of && !e.residual;
+  // The 64-wide stages are measured 2-6 % faster than the four-slab ring on the tiles that own a CU (256x256, 256x128,
+  // 128x256, 8 or 4 wavefronts) and slower or equal on the tiles that share one (128x128, 128x64, 64x64: several
+  // workgroups per CU fill each other's gaps, and the finer ring refills sooner), so each keeps its own loop.
+  constexpr bool HAS_LOOP2 = FAST && (BM + BN >= 384);
+  if constexpr (HAS_LOOP2) {
+    if (g_loop == 2) {
+      if (plain)
+        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, AKC, BKC, true, true, false, 2>), dim3((unsigned)nwg), dim3(WM * WN * 64), 0, stream, ka);
+      else
+        hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, AKC, BKC, true, false, false, 2>), dim3((unsigned)nwg), dim3(WM * WN * 64), 0, stream, ka);
+      return hip_launch_status();
+    }
+  }
   if (plain) {
     if constexpr (FAST)
       hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, AKC, BKC, true, true>), dim3((unsigned)nwg), dim3(WM * WN * 64), 0, stream, ka);
@@ -1099,7 +1331,10 @@ struct Plan {
   int seq;  // 1: the split is emulated inside each workgroup (KArgs::seq_splits): same bits, no partial tiles, no combine
 };
 
-static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
+// have_ws: the caller's workspace holds the partial tiles of the planned split.  Without it the same split is
+// emulated inside each workgroup (identical bits, see KArgs::seq_splits), so a result never depends on the workspace.
+static Plan make_plan(const GemmDesc& d, bool vec_ok, bool have_ws) {
+  const bool allow_split = true;
   Plan best = {kGuardVariant, 1, 0};
   if (!vec_ok || g_variant == kGuardVariant) return best;  // the fast kernels only have the vector epilogue
   // per candidate: variant id, workgroups resident per CU, fixed cost (launch, prologue, epilogue: us and us per MiB
@@ -1107,12 +1342,15 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
   // workgroup (t_full: all CUs' loads share the L2 fabric; the rise is steep only near full occupancy, hence the
   // square), and the increment per further workgroup resident on the same CU (t_more).  Measured on MI355X.
   struct Cand { int v, per_cu; float fixed_us, out_us_per_mib, t_lone, t_full, t_more; };
-  static const Cand cand[6] = {{0, 1, 12.0f, 0.15f, 0.54f, 0.64f, 0.00f},
-                               {1, 1, 8.0f, 0.30f, 0.31f, 0.42f, 0.00f},
-                               {2, 1, 8.0f, 0.30f, 0.31f, 0.42f, 0.00f},
+  constexpr int kCands = 8;
+  static const Cand cand[kCands] = {{0, 1, 12.0f, 0.15f, 0.54f, 0.64f, 0.00f},
+                               {1, 1, 8.0f, 0.30f, 0.30f, 0.40f, 0.00f},
+                               {2, 1, 8.0f, 0.30f, 0.30f, 0.405f, 0.00f},
                                {3, 2, 5.5f, 0.45f, 0.20f, 0.25f, 0.21f},
                                {6, 4, 4.5f, 0.50f, 0.19f, 0.30f, 0.16f},
-                               {7, 5, 4.0f, 0.50f, 0.14f, 0.155f, 0.20f}};
+                               {7, 5, 4.0f, 0.50f, 0.14f, 0.155f, 0.20f},
+                               {8, 1, 8.0f, 0.30f, 0.30f, 0.41f, 0.00f},
+                               {9, 1, 8.0f, 0.30f, 0.30f, 0.415f, 0.00f}};
   const long long slabs = (long long)d.nl * (d.Kp / BK);
   const bool splittable = allow_split && d.nl > 1 && !d.skip_upper && !d.k_hi_diag && !d.k_lo_diag;
   const float out_mib = (float)d.Mb * (float)d.Nb * 2.0f / 1048576.0f;
@@ -1126,7 +1364,7 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
   for (int pass = 0; pass < (batch > 1 ? 2 : 1); ++pass) {
   const int fixed_sp = pass == 0 ? 0 : best.splits;
   if (pass == 1) found = false;
-  for (int ci = 0; ci < 6; ++ci) {
+  for (int ci = 0; ci < kCands; ++ci) {
     const Cand& c = cand[ci];
     const int v = c.v;
     if (g_variant >= 0 && g_variant != kGuardVariant && v != (g_variant == 4 ? 0 : g_variant)) continue;
@@ -1176,6 +1414,14 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool allow_split) {
     }
   }
   }
+  if (best.splits > 1 && !best.seq && !have_ws) {
+    best.seq = 1;
+    if (kVariants[best.variant].BM * kVariants[best.variant].BN >= 256 * 256) {   // no registers for a second accumulator set
+      static const int order[7] = {1, 2, 8, 9, 3, 6, 7};
+      for (int k = 0; k < 7; ++k)
+        if (variant_fits(kVariants[order[k]], d)) { best.variant = order[k]; break; }
+    }
+  }
   return best;
 }
 
@@ -1190,16 +1436,19 @@ size_t gemm_partials_bytes(const GemmDesc& d, int splits) {
   return (size_t)splits * (size_t)d.nz0 * d.nz1 * (size_t)d.Mb * d.Nb * sizeof(float);
 }
 
-int gemm_pick_splits(const GemmDesc& d) {
-  if (!gemm_mfma_supported(d)) return 1;
-  return make_plan(d, epilogue_vec_ok(d), true).splits;
+// Workspace the planned launch wants for its partial tiles: 0 when there is no split or when the split is emulated
+// inside the workgroups anyway.
+size_t gemm_plan_bytes(const GemmDesc& d) {
+  if (!gemm_mfma_supported(d)) return 0;
+  const Plan p = make_plan(d, epilogue_vec_ok(d), true);
+  return p.seq ? 0 : gemm_partials_bytes(d, p.splits);
 }
 
 int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
   if (!gemm_mfma_supported(d)) return OPTIMUS_EINVAL;
   const bool vec_ok = epilogue_vec_ok(d);
-  // d.splits > 1 means the caller provided the workspace that the planned split asked for
-  const Plan plan = make_plan(d, vec_ok, d.splits > 1 && d.partials != nullptr);
+  // d.partials != nullptr means the caller provided the workspace that the planned split asked for
+  const Plan plan = make_plan(d, vec_ok, d.partials != nullptr);
   const int vi = plan.variant;
   g_last_plan = plan.variant | (plan.splits << 8) | (plan.seq << 16);
   const Variant& v = kVariants[vi];
@@ -1241,6 +1490,8 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
     case 4: rc = launch_layout<256, 256, 2, 4, true>(d, ka, nwg, stream); break;
     case 6: rc = launch_layout<128, 64, 2, 2, true>(d, ka, nwg, stream); break;
     case 7: rc = launch_layout<64, 64, 2, 2, true>(d, ka, nwg, stream); break;
+    case 8: rc = launch_layout<256, 128, 2, 2, true>(d, ka, nwg, stream); break;
+    case 9: rc = launch_layout<128, 256, 2, 2, true>(d, ka, nwg, stream); break;
     default: rc = launch_layout<128, 128, 2, 2, false>(d, ka, nwg, stream); break;
   }
   if (rc != OPTIMUS_OK) return rc;

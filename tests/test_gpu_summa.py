@@ -125,7 +125,8 @@ def test_fp32_random_ragged(form):
     _check_blocks(dC, summa.product(form, A, B), M, N, q, TOL["fp32"])
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7])
+# tile variants 0-9; 1000 + v = the same tile with the other of the two k-loops the tiles that own a CU are compiled with
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 1000, 1001, 1002, 1008, 1009])
 @pytest.mark.parametrize("form", FORMS)
 def test_every_tile_variant(form, variant):
     # 32 slabs of 32 per block: first cycle, steady-state cycles and last cycle of the k-loop all run
@@ -159,20 +160,23 @@ def test_tile_variants_give_identical_bits_and_grid_equals_device(form, q, mb, k
         ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
     ref = None
     plans = set()
-    if not with_ws:   # (a forced variant plans its own split: compare the variants without one)
+    by_split = {}
+    if not with_ws:   # (a forced variant plans its own panel split: the variants that plan the same one are compared)
         try:
-            for variant in (0, 1, 2, 3, 6, 7):
+            for variant in (0, 1, 2, 3, 6, 7, 8, 9, 1000, 1001, 1002, 1008, 1009):   # 1000 + v: the tile's other k-loop
                 opt.debug_set_gemm_variant(variant)
                 dC = _run(form, A, B, M, K, N, q, "bf16")
-                plans.add(opt.binding.debug_last_gemm_plan()[0])
-                ref = dC if ref is None else ref
-                assert torch.equal(dC.view(torch.int16), ref.view(torch.int16)), variant
+                plan = opt.binding.debug_last_gemm_plan()
+                plans.add(plan[0])
+                same = by_split.setdefault(plan[1], dC)
+                assert torch.equal(dC.view(torch.int16), same.view(torch.int16)), (variant, plan)
         finally:
             opt.debug_set_gemm_variant(-1)
-        assert len(plans) == 6          # six different tile shapes were really used
+        assert len(plans) == 8          # eight different tile shapes were really used
+        print("panel splits planned by the forced variants:", sorted(by_split))
     grid = _run(form, A, B, M, K, N, q, "bf16", ws=ws)
     grid_plan = opt.binding.debug_last_gemm_plan()
-    ref = grid if ref is None else ref
+    ref = by_split.get(grid_plan[1], grid)
     dev = empty(M * N, "bf16")
     dev_plans = set()
     for i in range(q):
@@ -185,6 +189,29 @@ def test_tile_variants_give_identical_bits_and_grid_equals_device(form, q, mb, k
     assert all(p[2] == 0 for p in dev_plans)              # one device: the real split
     if q == 4 and form == "ab":
         assert grid_plan[1] > 1 and grid_plan[2] == 1     # 16 blocks of [1024 x 4096 x 256]: emulated in the workgroups
+    if with_ws:
+        # the same with the large tiles forced (each with both of its k-loops): a forced tile plans its own split, so
+        # each is compared with itself: whole grid (split emulated in the workgroups where there are enough of them)
+        # against the single-device launches (real split, partial tiles, combine)
+        try:
+            big = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")   # room for any forced tile's partial tiles
+            for variant in (1, 2, 8, 1001, 1002):
+                opt.debug_set_gemm_variant(variant)
+                g2 = _run(form, A, B, M, K, N, q, "bf16", ws=big)
+                gp = opt.binding.debug_last_gemm_plan()
+                d2 = empty(M * N, "bf16")
+                for i in range(q):
+                    for j in range(q):
+                        _run(form, A, B, M, K, N, q, "bf16", i, j, ws=big, out=d2)
+                assert torch.equal(g2.view(torch.int16), d2.view(torch.int16)), (variant, gp)
+                # and without any workspace: the split is emulated inside the workgroups, the bits stay
+                d3 = empty(M * N, "bf16")
+                _run(form, A, B, M, K, N, q, "bf16", 0, 1, out=d3)
+                blk = slice(1 * (M // q) * (N // q), 2 * (M // q) * (N // q))
+                assert torch.equal(d3.view(torch.int16)[blk], d2.view(torch.int16)[blk]), (variant, "no workspace")
+                print("forced", variant, "grid plan", gp)
+        finally:
+            opt.debug_set_gemm_variant(-1)
 
 
 def test_closed_forms_and_identities():
