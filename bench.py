@@ -355,6 +355,31 @@ def time_model_ends(opt, torch, b, s, h, q, i, j, v, reps, seed):
     return out
 
 
+def mfma_ceiling(opt, torch):
+    """What the matrix cores deliver with nothing else going on: a loop of MFMA instructions only (register operands,
+    no LDS, no memory) on 64 / 128 / 256 workgroups (one per CU), with all-zero and with pseudo-random bf16 operands.
+    With every CU busy on operands that toggle like real data the chip's power management keeps the rate well below
+    the nominal peak: that, not 2.5 PFLOP/s, is the ceiling a product kernel on such data works under."""
+    out = torch.empty(256 * 512, dtype=torch.float32, device="cuda:0")
+    iters = 20000
+    rows = []
+    for wgs in (64, 128, 256):
+        for rnd in (0, 1):
+            opt.debug_mfma_rate(out, wgs, 2000, rnd)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            opt.debug_mfma_rate(out, wgs, iters, rnd)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            tf = wgs * 8 * iters * 8 * 32768 / (ms * 1e-3) / 1e12
+            rows.append({"workgroups": wgs, "operands": "pseudo-random bf16" if rnd else "zeros", "ms": round(ms, 3),
+                         "tflops": round(tf, 1), "frac_of_2500": round(tf / PEAK_BF16_TFLOPS, 3),
+                         "frac_of_these_cus_nominal": round(tf / (PEAK_BF16_TFLOPS * wgs / 256), 3)})
+    return rows
+
+
 def time_layer_step(opt, torch, harness, name, steps, warmup):
     """The layer step (device mode, HIP graph replay) of another configuration, timed like the main workload's:
     reported beside it so that one default run also carries the whole-step figures of the larger layers."""
@@ -546,6 +571,7 @@ def main():
                           "hardware": "64x Quadro RTX 5000, TACC Frontera (other machine: context, not a target)"},
     }
 
+    out["mfma_ceiling"] = mfma_ceiling(opt, torch)
     if not args.no_sweep:
         out["model_ends"] = time_model_ends(opt, torch, b, s, h, q, di, dj, 32768, args.gemm_reps, 9)
     if not args.no_sweep and args.workload == "config4":

@@ -392,9 +392,17 @@ int optimus_cross_entropy2d_bwd(const void* logits, const int32_t* labels, const
 int64_t optimus_gemm_flops(int64_t M, int64_t K, int64_t N, int q);
 int64_t optimus_layer_flops(const optimus_layer_cfg* cfg, int what);
 
+/* Measurement aid: a loop of matrix-core instructions only (v_mfma_f32_32x32x16_bf16 on register operands, no LDS,
+ * no memory) on `workgroups` workgroups of eight wavefronts, `iters` times eight instructions per wavefront, with
+ * all-zero (random_data = 0) or pseudo-random bf16 operands.  Timed by the caller; flops = workgroups * 8 * iters *
+ * 8 * 32768.  out: device memory for workgroups * 512 floats (written, never read back by the library). */
+int optimus_debug_mfma_rate(float* out, int workgroups, int iters, int random_data, void* stream);
+
 /* ---- tuning hooks for benchmark sweeps (no effect on results beyond summation order) ----
  * Force the matrix-core tile variant used by bf16 products: 0 = 256x256, 1 = 256x128, 2 = 128x256,
- * 3 = 128x128, 4 = alias of 0, 5 = bounds-checked 128x128, 6 = 128x64, 7 = 64x64; -1 = automatic.
+ * 3 = 128x128, 4 = alias of 0, 5 = bounds-checked 128x128, 6 = 128x64, 7 = 64x64, 8 = 256x128 and 9 = 128x256 with
+ * four wavefronts; -1 = automatic.  1000 + v selects, for the tiles compiled with two k-loops (0, 1, 2, 8, 9), the
+ * four-slab ring instead of the 64-wide stages (identical bits); 1255 = automatic tile with that loop.
  * A variant whose tile does not divide the block falls back to the bounds-checked kernel. */
 void optimus_debug_set_gemm_variant(int v);
 /* The same for the products optimus_layer_bwd runs side by side on two streams only: chain_v for the

@@ -125,6 +125,7 @@ SIGNATURES = {
     "optimus_debug_set_gemm_variant": (None, [_INT]),
     "optimus_debug_set_corun_variants": (None, [_INT, _INT]),
     "optimus_debug_last_gemm_plan": (_INT, []),
+    "optimus_debug_mfma_rate": (_INT, [_P, _INT, _INT, _INT, _P]),
 }
 
 
@@ -413,6 +414,10 @@ def debug_set_gemm_variant(v: int):
 
 def debug_set_corun_variants(chain_v: int, branch_v: int) -> None:
     lib().optimus_debug_set_corun_variants(chain_v, branch_v)
+
+
+def debug_mfma_rate(out, workgroups, iters, random_data, stream=None):
+    _check(lib().optimus_debug_mfma_rate(_ptr(out), workgroups, iters, int(random_data), _stream(stream)), "optimus_debug_mfma_rate")
 
 
 def debug_last_gemm_plan():

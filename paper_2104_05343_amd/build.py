@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liboptimus.so")
-SOURCES = ["api.hip", "gemm_mfma.hip", "gemm_generic.hip", "layernorm.hip", "softmax.hip", "attention_fused.hip", "blocks.hip", "stack.hip", "model_ends.hip"]
+SOURCES = ["api.hip", "gemm_mfma.hip", "gemm_generic.hip", "layernorm.hip", "softmax.hip", "attention_fused.hip", "blocks.hip", "stack.hip", "model_ends.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

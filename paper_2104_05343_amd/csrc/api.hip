@@ -877,6 +877,12 @@ int64_t optimus_layer_flops(const optimus_layer_cfg* c, int what) {
   return what == 0 ? fwd : 2 * fwd;
 }
 
+int optimus_debug_mfma_rate(float* out, int workgroups, int iters, int random_data, void* stream) {
+  if (!out) return OPTIMUS_EINVAL;
+  if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24)) return OPTIMUS_ESHAPE;
+  return launch_mfma_rate(out, workgroups, iters, random_data ? 1 : 0, as_stream(stream));
+}
+
 // ---- tuning hook used by the benchmark (not part of the method): force a matrix-core tile variant, -1 = automatic ----
 void optimus_debug_set_gemm_variant(int v) { gemm_set_variant(v); }
 void optimus_debug_set_corun_variants(int chain_v, int branch_v) { gemm_set_corun_variants(chain_v, branch_v); }

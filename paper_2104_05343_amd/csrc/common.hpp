@@ -96,6 +96,7 @@ int launch_gemm(const GemmDesc& d, hipStream_t stream);           // picks MFMA 
 int launch_gemm_generic(const GemmDesc& d, hipStream_t stream);    // scalar FMA kernel, any shape
 int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream);       // bf16 matrix-core kernel
 bool gemm_mfma_supported(const GemmDesc& d);
+int launch_mfma_rate(float* out, int workgroups, int iters, int random_data, hipStream_t stream);   // probe.hip
 size_t gemm_plan_bytes(const GemmDesc& d);                         // workspace the planned launch wants (0: none)
 size_t gemm_partials_bytes(const GemmDesc& d, int splits);
 // force a specific kernel variant (benchmark sweeps); -1 = automatic

@@ -1333,6 +1333,19 @@ struct Plan {
 
 // have_ws: the caller's workspace holds the partial tiles of the planned split.  Without it the same split is
 // emulated inside each workgroup (identical bits, see KArgs::seq_splits), so a result never depends on the workspace.
+// compute units of the current device (the planner's unit of parallelism); 256 when there is no device to ask
+static int num_cus() {
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return 256; }
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) { (void)hipGetLastError(); n = 256; }
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 static Plan make_plan(const GemmDesc& d, bool vec_ok, bool have_ws) {
   const bool allow_split = true;
   Plan best = {kGuardVariant, 1, 0};
@@ -1340,58 +1353,67 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool have_ws) {
   // per candidate: variant id, workgroups resident per CU, fixed cost (launch, prologue, epilogue: us and us per MiB
   // of output), and the time per slab of one workgroup: alone on the chip (t_lone), with every CU holding one
   // workgroup (t_full: all CUs' loads share the L2 fabric; the rise is steep only near full occupancy, hence the
-  // square), and the increment per further workgroup resident on the same CU (t_more).  Measured on MI355X.
+  // square), and the increment per further workgroup resident on the same CU (t_more).  Measured on MI355X with the
+  // kernels as of the commit that last touched this table (one forced-variant sweep over the products of the
+  // benchmark configurations 3-5); tests/test_gpu_planner.py fails when the kernels drift away from it.
   struct Cand { int v, per_cu; float fixed_us, out_us_per_mib, t_lone, t_full, t_more; };
   constexpr int kCands = 8;
   static const Cand cand[kCands] = {{0, 1, 12.0f, 0.15f, 0.54f, 0.64f, 0.00f},
-                               {1, 1, 8.0f, 0.30f, 0.30f, 0.40f, 0.00f},
-                               {2, 1, 8.0f, 0.30f, 0.30f, 0.405f, 0.00f},
+                               {1, 1, 8.0f, 0.30f, 0.24f, 0.40f, 0.00f},
+                               {2, 1, 8.0f, 0.30f, 0.24f, 0.405f, 0.00f},
                                {3, 2, 5.5f, 0.45f, 0.20f, 0.25f, 0.21f},
-                               {6, 4, 4.5f, 0.50f, 0.19f, 0.30f, 0.16f},
-                               {7, 5, 4.0f, 0.50f, 0.14f, 0.155f, 0.20f},
-                               {8, 1, 8.0f, 0.30f, 0.30f, 0.41f, 0.00f},
-                               {9, 1, 8.0f, 0.30f, 0.30f, 0.415f, 0.00f}};
+                               {6, 4, 4.5f, 0.50f, 0.19f, 0.21f, 0.133f},
+                               {7, 5, 4.0f, 0.50f, 0.14f, 0.155f, 0.045f},
+                               {8, 1, 8.0f, 0.30f, 0.24f, 0.41f, 0.00f},
+                               {9, 1, 8.0f, 0.30f, 0.24f, 0.415f, 0.00f}};
   const long long slabs = (long long)d.nl * (d.Kp / BK);
+  const long long ncu = num_cus();
   const bool splittable = allow_split && d.nl > 1 && !d.skip_upper && !d.k_hi_diag && !d.k_lo_diag;
   const float out_mib = (float)d.Mb * (float)d.Nb * 2.0f / 1048576.0f;
   float best_cost = 0.f;
   bool found = false;
   // Two passes.  The panel split changes the order in which a result is added up, so it is chosen from ONE block's
-  // shape (pass 0).  The tile shape does not (every element walks the same slabs in the same order whatever tile it
+  // shape alone, as if the product ran by itself (pass 0): a product has the same bits wherever it is launched from.
+  // The tile shape does not change them (every element walks the same slabs in the same order whatever tile it
   // lies in: the variants give identical bits, which the tests check), so a launch that covers several blocks
-  // (the whole grid, the matrices of a batch of heads) then picks its tile for the workgroups it really has (pass 1).
+  // (the whole grid, the matrices of a batch of heads) or that shares the chip with a second product then picks
+  // its tile, for that split, for the workgroups and the company it really has (pass 1).
   const long long batch = d.plan_for_batch ? (long long)(d.nz0 > 0 ? d.nz0 : 1) * (d.nz1 > 0 ? d.nz1 : 1) : 1;
-  for (int pass = 0; pass < (batch > 1 ? 2 : 1); ++pass) {
+  for (int pass = 0; pass < (batch > 1 || d.corun > 0 ? 2 : 1); ++pass) {
   const int fixed_sp = pass == 0 ? 0 : best.splits;
   if (pass == 1) found = false;
   for (int ci = 0; ci < kCands; ++ci) {
     const Cand& c = cand[ci];
     const int v = c.v;
     if (g_variant >= 0 && g_variant != kGuardVariant && v != (g_variant == 4 ? 0 : g_variant)) continue;
-    if (d.corun > 0 && g_corun_variant[d.corun - 1] >= 0 && v != g_corun_variant[d.corun - 1]) continue;
+    if (pass == 1 && d.corun > 0 && g_corun_variant[d.corun - 1] >= 0 && v != g_corun_variant[d.corun - 1]) continue;
     if (!variant_fits(kVariants[v], d)) continue;
     const long long tiles = (long long)(d.Mb / kVariants[v].BM) * (d.Nb / kVariants[v].BN) * (pass == 0 ? 1 : batch);
     for (int sp = fixed_sp ? fixed_sp : 1; sp <= (fixed_sp ? fixed_sp : 8); ++sp) {
       if (!fixed_sp && sp > 1 && (!splittable || slabs / sp < 8)) break;
       const long long wgs = tiles * sp;
-      const long long cap = 256LL * c.per_cu;
+      const long long cap = ncu * c.per_cu;
       const long long rounds = (wgs + cap - 1) / cap;
       const long long in_round = wgs < cap ? wgs : cap;
-      const int resident = (int)((in_round + 255) / 256);             // workgroups on the fullest CU
-      const float busy = in_round >= 256 ? 1.0f : (float)in_round / 256.0f;  // share of the CUs in use
-      const float t_slab = c.t_lone + (c.t_full - c.t_lone) * busy * busy + c.t_more * (float)(resident - 1);
+      const int resident = (int)((in_round + ncu - 1) / ncu);             // workgroups on the fullest CU
+      const float busy = in_round >= ncu ? 1.0f : (float)in_round / (float)ncu;  // share of the CUs in use
+      float t_slab = c.t_lone + (c.t_full - c.t_lone) * busy * busy + c.t_more * (float)(resident - 1);
+      // the 128x128 tile depends on the operand layouts: both k-contiguous (A B^T) is its slowest form, one of each its fastest
+      if (v == 3) t_slab *= d.a_kcontig && d.b_kcontig ? 1.14f : (d.a_kcontig ? 0.92f : 1.04f);
+      if (v == 6 && d.a_kcontig && d.b_kcontig) t_slab *= 1.18f;
+      if (v == 7 && !d.a_kcontig) t_slab *= 1.25f;   // both operands through the transposing LDS reads
       const float per_wg = (float)((((slabs + sp - 1) / sp) + 1) & ~1LL) * t_slab;
       // split: the combine launch, and the fp32 partial tiles read back by it (their writes overlap the products)
       const float traffic_us =
           sp > 1 ? 4.0f + (float)sp * (float)d.Mb * (float)d.Nb * 4.0f / 3.0e6f * (pass == 0 ? 1.0f : (float)batch) : 0.f;
       float cost = c.fixed_us + c.out_us_per_mib * out_mib * (pass == 0 ? 1.0f : (float)batch) + (float)rounds * per_wg + traffic_us;
-      // Two products that run side by side on two streams (the pairs of the layer's backward pass) overlap only if
-      // workgroups of both fit on one CU: the 8-wavefront tiles take a CU's LDS and registers alone, so such a pair
-      // runs one after the other, while the 4-wavefront tiles of the two kernels share the CUs.  Measured on the
-      // backward pass of the 4096-wide layers: 128x128 tiles for the chain 0.69 -> 0.57 ms and 0.71 -> 0.62 ms,
-      // although each product alone is faster with 256x128 tiles; no difference for the small layer.  A whole-grid
-      // launch (pass 1) fills the chip by itself, and there the larger tiles win (4-layer stack backward 3.17 -> 3.06 ms).
-      if (d.corun > 0 && c.per_cu >= 2 && pass == 0) cost *= 0.78f;
+      // Two products that run side by side on two streams (the pairs of the layer's backward pass): the tiles of 8
+      // wavefronts, which take a CU's LDS and registers alone, are the better partners, also where such a tile leaves
+      // half the CUs idle when the product runs by itself (the other product's workgroups take those).  Measured on
+      // the backward pass of the 4096-wide layers (one device of the q = 4 / q = 8 grids): 256x128 tiles for both
+      // products 0.55 / 0.61 ms, 128x128 tiles for both 0.64 / 0.72 ms, 256x128 for the chain and 128x128 for the
+      // branch 0.65 / 0.69 ms, the reverse 0.58 / 0.63 ms.
+      if (d.corun > 0 && c.per_cu >= 2 && pass == 1 && batch == 1) cost *= 1.25f;
       if (!found || cost < best_cost) {
         found = true;
         best_cost = cost;
@@ -1399,11 +1421,11 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool have_ws) {
       }
       // A launch with many blocks has workgroups enough without the split: one workgroup then walks all the slabs of
       // its tile and adds them up range by range as the split workgroups and their combine would (identical bits).
-      if (pass == 1 && sp > 1 && kVariants[v].BM * kVariants[v].BN < 256 * 256) {
+      if (pass == 1 && batch > 1 && sp > 1 && kVariants[v].BM * kVariants[v].BN < 256 * 256) {
         const long long rounds1 = (tiles + cap - 1) / cap;
         const long long in1 = tiles < cap ? tiles : cap;
-        const int res1 = (int)((in1 + 255) / 256);
-        const float busy1 = in1 >= 256 ? 1.0f : (float)in1 / 256.0f;
+        const int res1 = (int)((in1 + ncu - 1) / ncu);
+        const float busy1 = in1 >= ncu ? 1.0f : (float)in1 / (float)ncu;
         const float t1 = c.t_lone + (c.t_full - c.t_lone) * busy1 * busy1 + c.t_more * (float)(res1 - 1);
         const float cost1 = c.fixed_us + c.out_us_per_mib * out_mib * (float)batch + (float)rounds1 * (float)slabs * t1;
         if (cost1 < best_cost) {

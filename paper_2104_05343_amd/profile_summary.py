@@ -75,22 +75,25 @@ def trace(trace_csv, bench_json, out_md, cmd, title):
 
 
 def _counter_medians(path, counter):
-    agg = collections.defaultdict(list)
+    """({(kernel, grid): median counter value}, {(kernel, grid): first dispatch id}) of one counter file."""
+    agg, first = collections.defaultdict(list), {}
     for r in csv.DictReader(open(path)):
         if r["Counter_Name"] == counter:
-            agg[(_short(r["Kernel_Name"]), r.get("Grid_Size", r.get("Grid_Size_X", "")))].append(float(r["Counter_Value"]))
-    return {k: statistics.median(v) for k, v in agg.items()}
+            k = (_short(r["Kernel_Name"]), r.get("Grid_Size", r.get("Grid_Size_X", "")))
+            agg[k].append(float(r["Counter_Value"]))
+            first[k] = min(first.get(k, 1 << 62), int(r["Dispatch_Id"]))
+    return {k: statistics.median(v) for k, v in agg.items()}, first
 
 
 def pmc(fetch_csv, write_csv, probe_json, workload, commit, out_json):
-    fetch = _counter_medians(fetch_csv, "FETCH_SIZE")
-    write = _counter_medians(write_csv, "WRITE_SIZE")
+    fetch, first = _counter_medians(fetch_csv, "FETCH_SIZE")
+    write, _ = _counter_medians(write_csv, "WRITE_SIZE")
 
     def copy_scale(table):
-        c = [v for k, v in table.items() if "copyBuffer" in k[0] or "copy" in k[0].lower()]
+        c = [v for k, v in table.items() if k[0] == "__amd_rocclr_copyBuffer"]
         if not c:
-            raise SystemExit("no copy kernel in the counter file: cannot scale the counter")
-        return COPY_BYTES / max(c)       # bytes per counter unit
+            raise SystemExit("no __amd_rocclr_copyBuffer dispatch in the counter file: cannot scale the counter")
+        return COPY_BYTES / max(c)       # bytes per counter unit (the probe's copy moves 256 MiB each way)
     fs, ws = copy_scale(fetch), copy_scale(write)
     probe = _last_json(probe_json)
     g = probe["gemm"][0]
@@ -102,8 +105,8 @@ def pmc(fetch_csv, write_csv, probe_json, workload, commit, out_json):
             continue
         f, w = fetch.get(k, 0.0), write.get(k, 0.0)
         print(f"| `{k[0]}` | {k[1]} | {f:.1f} | {w:.1f} | {f * fs / 2**20:.2f} | {w * ws / 2**20:.2f} |")
-        if "gemm_mfma_kernel" in k[0] and (dom is None or f > fetch.get(dom, 0.0)):
-            dom = k
+        if "gemm_mfma_kernel" in k[0] and (dom is None or first[k] < first[dom]):
+            dom = k      # the probe launches the dominant product before every other product
     if dom is None:
         raise SystemExit("no product kernel in the counter files")
     try:
