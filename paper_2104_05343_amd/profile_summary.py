@@ -1,9 +1,10 @@
 """Turns rocprofv3 output of bench.py runs into the short text summaries kept under profiles/.
 
-  python -m paper_2104_05343_amd.profile_summary trace  TRACE.csv BENCH.json OUT.md "COMMAND" "TITLE"
+  python -m paper_2104_05343_amd.profile_summary trace  TRACE.csv BENCH.json OUT.md "COMMAND" "TITLE" TRAFFIC.json
       per-kernel table (calls, average, min, max) of a `rocprofv3 --kernel-trace` run of bench.py, the runs of
       consecutive launches of the dominant product kernel (one run = one graph replay of bench.py's per-product
       timing: first the warm replays, then the replays over rotating buffer sets), and the bench JSON (abridged).
+      The dominant product's kernel is the one TRAFFIC.json (written by `pmc` below) names for the workload.
 
   python -m paper_2104_05343_amd.profile_summary pmc  FETCH.csv WRITE.csv PROBE.json WORKLOAD COMMIT OUT.json
       FETCH_SIZE / WRITE_SIZE per dispatch of `bench.py --workload W --pmc-probe` (two runs: one counter each),
@@ -29,7 +30,7 @@ def _last_json(path):
     return json.loads(lines[-1])
 
 
-def trace(trace_csv, bench_json, out_md, cmd, title):
+def trace(trace_csv, bench_json, out_md, cmd, title, traffic_json):
     rows = list(csv.DictReader(open(trace_csv)))
     rows.sort(key=lambda r: int(r["Start_Timestamp"]))
     d = _last_json(bench_json)
@@ -45,10 +46,15 @@ def trace(trace_csv, bench_json, out_md, cmd, title):
             continue
         lines.append(f"| `{k}` | {grid} | {len(v)} | {sum(v) / 1e6:.3f} | {statistics.mean(v) / 1e3:.2f} | {min(v) / 1e3:.2f} | "
                      f"{max(v) / 1e3:.2f} | {100 * sum(v) / total:.2f} |")
-    # dominant product: the kernel/grid pair with the longest single launches among the product kernels
-    gemm = {k: v for k, v in per.items() if "gemm_mfma_kernel" in k[0] and len(v) >= 20}
+    # dominant product: the kernel the counter summary names for this workload (largest grid of that name)
+    workload = d["config"]["workload"].split(":")[0]
+    try:
+        named = [_short(v["kernel"]) for v in json.load(open(traffic_json)).get(workload, {}).values()]
+    except (OSError, ValueError):
+        named = []
+    gemm = {k: v for k, v in per.items() if k[0] in named and len(v) >= 20}
     if gemm:
-        dom = max(gemm, key=lambda k: statistics.median(gemm[k]))
+        dom = max(gemm, key=lambda k: int(k[1]))
         runs, cur = [], []
         for r in rows:
             if _short(r["Kernel_Name"]) == dom[0] and r["Grid_Size_X"] == dom[1]:
@@ -122,8 +128,8 @@ def pmc(fetch_csv, write_csv, probe_json, workload, commit, out_json):
 
 
 if __name__ == "__main__":
-    if len(sys.argv) >= 2 and sys.argv[1] == "trace" and len(sys.argv) == 7:
-        trace(*sys.argv[2:7])
+    if len(sys.argv) >= 2 and sys.argv[1] == "trace" and len(sys.argv) == 8:
+        trace(*sys.argv[2:8])
     elif len(sys.argv) >= 2 and sys.argv[1] == "pmc" and len(sys.argv) == 8:
         pmc(*sys.argv[2:8])
     else:
