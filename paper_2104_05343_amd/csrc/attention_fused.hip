@@ -327,15 +327,27 @@ __global__ __launch_bounds__(NRG * 128) void attn_fused_fwd_kernel(FusedArgs a) 
 }
 
 // ---------------------------------------------------------------- backward, dQ (and rowsum(dO * O))
-template <int D, bool CAUSAL, int NRG>
-__global__ __launch_bounds__(NRG * 128) void attn_fused_bwd_dq_kernel(FusedArgs a) {
+// One lane's share of rowsum(dO * O): 8 products of one 16-byte chunk pair, added in element order.
+__device__ __forceinline__ float delta_piece(const bf16x8& dof, const bf16x8& of) {
+  const u32x4 gw = __builtin_bit_cast(u32x4, dof), ow = __builtin_bit_cast(u32x4, of);
+  float d = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {  // explicit fused multiply-adds: every caller rounds alike
+    d = fmaf(__uint_as_float(gw[w] << 16), __uint_as_float(ow[w] << 16), d);
+    d = fmaf(__uint_as_float(gw[w] & 0xffff0000u), __uint_as_float(ow[w] & 0xffff0000u), d);
+  }
+  return d;
+}
+
+// OWN_DELTA: the workgroup computes rowsum(dO * O) of its rows itself and stores it for the dK/dV kernel of a later
+// launch; otherwise it reads what attn_fused_delta_kernel stored.  lds: [stage][K, V][pair tile].
+template <int D, bool CAUSAL, int NRG, bool OWN_DELTA>
+__device__ __forceinline__ void bwd_dq_body(const FusedArgs& a, bf16_t (*lds)[2][PAIR * D], int tile, int mat, int dev) {
   constexpr int KS = D / 16, DT = D / 32, BQ = NRG * 32;
-  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];  // [stage][K, V][pair tile]
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int rg = wave % NRG, par = wave / NRG;
-  const int tile = gridDim.x - 1 - blockIdx.x;
-  const int mat = blockIdx.y, dev = blockIdx.z, s = a.s;
+  const int s = a.s;
   const int seq = mat / a.nh, head = mat % a.nh;
   const bf16_t* Qp = a.qkv + dev * a.dev_qkv + (long long)seq * s * a.ld + head * 3 * D;
   const bf16_t* Kp = Qp + D;
@@ -351,15 +363,14 @@ __global__ __launch_bounds__(NRG * 128) void attn_fused_bwd_dq_kernel(FusedArgs 
   for (int ks = 0; ks < KS; ++ks) {
     qf[ks] = *(const bf16x8*)(Qp + (long long)qrow * a.ld + ks * 16 + g * 8);
     dof[ks] = *(const bf16x8*)(a.d_attn + orow + ks * 16 + g * 8);
-    const bf16x8 of = *(const bf16x8*)(a.attn + orow + ks * 16 + g * 8);
-    const u32x4 gw = __builtin_bit_cast(u32x4, dof[ks]), ow = __builtin_bit_cast(u32x4, of);
-#pragma unroll
-    for (int w = 0; w < 4; ++w)
-      delta += __uint_as_float(gw[w] << 16) * __uint_as_float(ow[w] << 16) +
-               __uint_as_float(gw[w] & 0xffff0000u) * __uint_as_float(ow[w] & 0xffff0000u);
+    if (OWN_DELTA) delta += delta_piece(dof[ks], *(const bf16x8*)(a.attn + orow + ks * 16 + g * 8));
   }
-  delta = halfwave_sum(delta);
-  if (par == 0 && g == 0 && query < s) a.delta[vrow] = delta;
+  if (OWN_DELTA) {
+    delta = halfwave_sum(delta);
+    if (par == 0 && g == 0 && query < s) a.delta[vrow] = delta;
+  } else {
+    delta = a.delta[vrow];
+  }
   const float lse2 = a.lse[vrow] * LOG2E;
   const int wg_hi = min(tile * BQ + BQ, s) - 1;
   const int nkb = CAUSAL ? wg_hi / BLK + 1 : (s + BLK - 1) / BLK;
@@ -448,19 +459,40 @@ __global__ __launch_bounds__(NRG * 128) void attn_fused_bwd_dq_kernel(FusedArgs 
   }
 }
 
+template <int D, bool CAUSAL, int NRG>
+__global__ __launch_bounds__(NRG * 128) void attn_fused_bwd_dq_kernel(FusedArgs a) {
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];
+  bwd_dq_body<D, CAUSAL, NRG, true>(a, lds, gridDim.x - 1 - blockIdx.x, blockIdx.y, blockIdx.z);  // longest causal rows first
+}
+
+// rowsum(dO * O) for every query row of the launch: a wavefront takes 32 rows, lane pair (l, l ^ 32) one row.
+template <int D>
+__global__ __launch_bounds__(256) void attn_fused_delta_kernel(FusedArgs a) {
+  const int lane = threadIdx.x & 63, g = lane >> 5, wave = threadIdx.x >> 6;
+  const int mat = blockIdx.y, dev = blockIdx.z, s = a.s;
+  const int seq = mat / a.nh, head = mat % a.nh;
+  const int query = blockIdx.x * 128 + wave * 32 + (lane & 31);
+  const int qrow = min(query, s - 1);
+  const long long orow = dev * a.dev_attn + ((long long)seq * s + qrow) * a.ldo + head * D;
+  float delta = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks)
+    delta += delta_piece(*(const bf16x8*)(a.d_attn + orow + ks * 16 + g * 8), *(const bf16x8*)(a.attn + orow + ks * 16 + g * 8));
+  delta = halfwave_sum(delta);
+  if (g == 0 && query < s) a.delta[dev * a.dev_vec + (long long)mat * s + qrow] = delta;
+}
+
 // ---------------------------------------------------------------- backward, dK and dV
 // A wavefront owns 32 keys and every second block of 64 queries (from the diagonal on when causal).
+// lds: [stage][Q, dO][pair tile]; ldsL: lse * log2(e) of the pair's queries; ldsD: their rowsum(dO * O).
 template <int D, bool CAUSAL, int NRG>
-__global__ __launch_bounds__(NRG * 128) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
+__device__ __forceinline__ void bwd_dkv_body(const FusedArgs& a, bf16_t (*lds)[2][PAIR * D], float (*ldsL)[PAIR], float (*ldsD)[PAIR],
+                                             int tile, int mat, int dev) {
   constexpr int KS = D / 16, DT = D / 32, BKW = NRG * 32;
-  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];  // [stage][Q, dO][pair tile]
-  __shared__ __attribute__((aligned(16))) float ldsL[2][PAIR];           // lse * log2(e) of the pair's queries
-  __shared__ __attribute__((aligned(16))) float ldsD[2][PAIR];           // rowsum(dO * O)
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int rg = wave % NRG, par = wave / NRG;
-  const int tile = blockIdx.x;  // early key tiles have the longest causal loops
-  const int mat = blockIdx.y, dev = blockIdx.z, s = a.s;
+  const int s = a.s;
   const int seq = mat / a.nh, head = mat % a.nh;
   const bf16_t* Qp = a.qkv + dev * a.dev_qkv + (long long)seq * s * a.ld + head * 3 * D;
   const bf16_t* Kp = Qp + D;
@@ -596,6 +628,32 @@ __global__ __launch_bounds__(NRG * 128) void attn_fused_bwd_dkv_kernel(FusedArgs
   }
 }
 
+template <int D, bool CAUSAL, int NRG>
+__global__ __launch_bounds__(NRG * 128) void attn_fused_bwd_dkv_kernel(FusedArgs a) {
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];
+  __shared__ __attribute__((aligned(16))) float ldsL[2][PAIR];
+  __shared__ __attribute__((aligned(16))) float ldsD[2][PAIR];
+  bwd_dkv_body<D, CAUSAL, NRG>(a, lds, ldsL, ldsD, blockIdx.x, blockIdx.y, blockIdx.z);  // early key tiles: longest causal loops
+}
+
+// dQ and dK/dV of one launch side by side.  A causal launch of either kernel alone is as long as its longest row or
+// column tile while the average tile is half as long, and one workgroup fills a compute unit (registers), so with
+// about one workgroup per compute unit half the chip idles.  Here the workgroups of both are one grid, ordered by loop
+// length (longest first, the two kinds alternating): a compute unit that finishes a short tile picks up the next one
+// of either kind.  rowsum(dO * O) comes from attn_fused_delta_kernel (launched before), so no workgroup waits for
+// another.  Same arithmetic per workgroup as the two separate kernels: same bits.
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_fused_bwd_kernel(FusedArgs a, int ntiles, int nmat) {
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2][2][PAIR * D];
+  __shared__ __attribute__((aligned(16))) float ldsL[2][PAIR];
+  __shared__ __attribute__((aligned(16))) float ldsD[2][PAIR];
+  const unsigned per_rank = 2u * (unsigned)nmat;   // grid: x = (rank of the loop length, matrix, kind), y = device
+  const unsigned rank = blockIdx.x / per_rank, rem = blockIdx.x % per_rank;
+  const int mat = (int)(rem >> 1), dev = (int)blockIdx.y;
+  if (rem & 1) bwd_dq_body<D, CAUSAL, 2, false>(a, lds, ntiles - 1 - (int)rank, mat, dev);
+  else bwd_dkv_body<D, CAUSAL, 2>(a, lds, ldsL, ldsD, (int)rank, mat, dev);
+}
+
 FusedArgs make_args(const AttnFusedDesc& d) {
   FusedArgs a = {};
   a.qkv = (const bf16_t*)d.qkv; a.attn = (bf16_t*)d.attn; a.lse = d.lse;
@@ -637,6 +695,13 @@ void bwd_launch_c(const FusedArgs& a, const AttnFusedDesc& d, hipStream_t st) {
   // kernel at head width 128 does not: it would spill a hundred registers)
   const bool big = (long long)((d.s + 127) / 128) * d.nb * d.nh * d.ndev >= 512;
   const dim3 grid_big((d.s + 127) / 128, d.nb * d.nh, d.ndev), block_big(512);
+  const long long ntiles = (d.s + BLK - 1) / BLK, nmat = (long long)d.nb * d.nh;
+  if (!big && 2 * ntiles * nmat < (1ll << 30)) {
+    // small launches (about a workgroup per compute unit or less): both kinds of workgroup in one grid
+    attn_fused_delta_kernel<D><<<dim3((d.s + 127) / 128, d.nb * d.nh, d.ndev), 256, 0, st>>>(a);
+    attn_fused_bwd_kernel<D, CAUSAL><<<dim3((unsigned)(2 * ntiles * nmat), d.ndev), 256, 0, st>>>(a, (int)ntiles, (int)nmat);
+    return;
+  }
   if (big) attn_fused_bwd_dq_kernel<D, CAUSAL, 4><<<grid_big, block_big, 0, st>>>(a);
   else attn_fused_bwd_dq_kernel<D, CAUSAL, 2><<<grid, block, 0, st>>>(a);
   if constexpr (D == 64) {
