@@ -63,6 +63,28 @@ constexpr int NSTAGE = 4;
 #ifndef OPTIMUS_LAB_DBG
 #define OPTIMUS_LAB_DBG 0
 #endif
+// bit 32 (timing studies only): thread 0 of every workgroup stores the 100 MHz wall clock at four points of the kernel
+// (entry, first matrix instruction, end of the k-loop, last store retired)
+#if OPTIMUS_LAB_DBG & 32
+__device__ unsigned long long g_lab_stamps[4 * 4096];
+extern "C" int optimus_lab_read_stamps(unsigned long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_lab_stamps), sizeof(g_lab_stamps));
+}
+__device__ unsigned long long g_lab_stall[8 * 2048];
+extern "C" int optimus_lab_read_stall(unsigned long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_lab_stall), sizeof(g_lab_stall));
+}
+#define OPTIMUS_LAB_STAMP(n)                                                                         \
+  do {                                                                                               \
+    if ((n) == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                   \
+    if (threadIdx.x == 0 && blockIdx.x < 2048) {                                                      \
+      g_lab_stamps[blockIdx.x * 8 + (n)] = wall_clock64();                                           \
+      g_lab_stamps[blockIdx.x * 8 + 4 + (n)] = clock64();                                            \
+    }                                                                                                \
+  } while (0)
+#else
+#define OPTIMUS_LAB_STAMP(n) do {} while (0)
+#endif
 
 struct KArgs {
   const bf16_t* A;
@@ -464,6 +486,7 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
+  OPTIMUS_LAB_STAMP(0);
 
   // ---- which tile: XCD-aware remap of the linear workgroup id ----
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles so that
@@ -674,6 +697,7 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
         else OPTIMUS_WAIT_VMCNT(0);
       }
       OPTIMUS_BARRIER();
+      OPTIMUS_LAB_STAMP(1);
 #pragma unroll
       for (int r = 0; r < HR; ++r) read_item(0u, 0u, r / NF, r % NF);
       int seq_next64 = seq_next >> 1;
@@ -706,15 +730,30 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
       // steady state: every iteration reads the next stage and refills the stage it leaves (straight-line body, constant
       // wait counts: with branches inside the loop the compiler copies the accumulators between the paths)
       int i = 0;
+#if OPTIMUS_LAB_DBG & 64
+      unsigned long long lab_sum_a = 0, lab_sum_b = 0, lab_tb = 0;
+#endif
       for (; i + NST < n64; ++i) {
         range_end(i);
         half(first, yes, no, st_cur, 0);
+#if OPTIMUS_LAB_DBG & 64
+        const unsigned long long lab_ta = clock64();
+#endif
         // stage i+1 has landed (stage i+2's loads stay in flight); my reads of stage i are done
         if constexpr (!(OPTIMUS_LAB_DBG & 16)) OPTIMUS_WAIT_VMCNT_LGKM0(NST > 2 ? LP : 0);
         if constexpr (!(OPTIMUS_LAB_DBG & 2)) OPTIMUS_BARRIER();
+#if OPTIMUS_LAB_DBG & 64
+        lab_sum_a += lab_ta;
+        lab_sum_b += lab_tb;
+        lab_tb = clock64();
+#endif
         half(second, yes, yes, st_nxt, st_cur);
         next_stage();
       }
+#if OPTIMUS_LAB_DBG & 64
+      lab_sum_b += lab_tb;
+      if (lane == 0 && blockIdx.x < 2048) g_lab_stall[blockIdx.x * 8 + wave] = lab_sum_b - lab_sum_a;
+#endif
       // the last stages: nothing left to load
       for (; i + 1 < n64; ++i) {
         range_end(i);
@@ -731,6 +770,7 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
       // the results leave through LDS (see the epilogue): nobody may still be reading the last stage
       OPTIMUS_WAIT_VMCNT_LGKM0(0);
       OPTIMUS_BARRIER();
+      OPTIMUS_LAB_STAMP(2);
     } else if constexpr (FAST) {
       // Loads per wavefront: a k-strided operand moves one slab per step; a k-contiguous operand moves a pair of
       // slabs (whole 128-byte lines per row) every second step.  The slab count of a workgroup is even (host).
@@ -1191,6 +1231,7 @@ __global__ __launch_bounds__(WM* WN * 64, (Occ<BM, BN, WM, WN>::value)) void gem
           epilogue_store4<false>(e, coff, m, n, v, min(4, a.Nb - n));
         }
   }
+  OPTIMUS_LAB_STAMP(3);
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
