@@ -409,6 +409,13 @@ void optimus_debug_set_gemm_variant(int v);
  * activation-gradient chain (the four A B^T products), branch_v for the parameter-gradient branch (the four A^T B
  * products); -1 = automatic. */
 void optimus_debug_set_corun_variants(int chain_v, int branch_v);
+/* The tile plan a bf16 product of this shape would be launched with: out3 = {tile variant, panel split, 1 if the
+ * split is walked inside the workgroups (no partial tiles in memory)}.  Host arithmetic only, nothing is enqueued and
+ * no GPU is needed.  corun: 0 = the product runs alone, 1 / 2 = it is the chain / branch product of a pair that
+ * optimus_layer_bwd runs side by side; have_ws: whether the caller would pass the workspace the plan asks for.
+ * The panel split (the only part of a plan that changes bits) depends on the block shape alone: not on (i, j) versus
+ * grid mode, not on corun.  OPTIMUS_EDTYPE when the matrix-core kernels do not take the shape (ragged sizes). */
+int optimus_debug_plan_summa(int form, int64_t M, int64_t K, int64_t N, int q, int i, int j, int corun, int have_ws, int* out3);
 /* The plan of the most recent matrix-core product launched by this process: variant | (panel splits << 8) |
  * (1 << 16 if the split is emulated inside each workgroup);
  * -1 before the first one.  Host state only, not synchronised between threads. */

@@ -125,6 +125,7 @@ SIGNATURES = {
     "optimus_debug_set_gemm_variant": (None, [_INT]),
     "optimus_debug_set_corun_variants": (None, [_INT, _INT]),
     "optimus_debug_last_gemm_plan": (_INT, []),
+    "optimus_debug_plan_summa": (_INT, [_INT, _I64, _I64, _I64, _INT, _INT, _INT, _INT, _INT, C.POINTER(C.c_int)]),
     "optimus_debug_mfma_rate": (_INT, [_P, _INT, _INT, _INT, _P]),
 }
 
@@ -418,6 +419,15 @@ def debug_set_corun_variants(chain_v: int, branch_v: int) -> None:
 
 def debug_mfma_rate(out, workgroups, iters, random_data, stream=None):
     _check(lib().optimus_debug_mfma_rate(_ptr(out), workgroups, iters, int(random_data), _stream(stream)), "optimus_debug_mfma_rate")
+
+
+def debug_plan_summa(form, M, K, N, q, i, j, corun=0, have_ws=True):
+    """(variant, panel splits, walked inside the workgroups) a bf16 product of this shape would be launched with; host
+    arithmetic only (works without a GPU)."""
+    out = (C.c_int * 3)()
+    f = FORMS[form] if isinstance(form, str) else form
+    _check(lib().optimus_debug_plan_summa(f, M, K, N, q, i, j, corun, 1 if have_ws else 0, out), "optimus_debug_plan_summa")
+    return out[0], out[1], out[2]
 
 
 def debug_last_gemm_plan():

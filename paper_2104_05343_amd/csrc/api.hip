@@ -886,6 +886,18 @@ int optimus_debug_mfma_rate(float* out, int workgroups, int iters, int random_da
 // ---- tuning hook used by the benchmark (not part of the method): force a matrix-core tile variant, -1 = automatic ----
 void optimus_debug_set_gemm_variant(int v) { gemm_set_variant(v); }
 void optimus_debug_set_corun_variants(int chain_v, int branch_v) { gemm_set_corun_variants(chain_v, branch_v); }
+int optimus_debug_plan_summa(int form, int64_t M, int64_t K, int64_t N, int q, int i, int j, int corun, int have_ws, int* out3) {
+  if (!out3 || form < 0 || form > 2 || corun < 0 || corun > 2) return OPTIMUS_EINVAL;
+  int rc = check_mkn(M, K, N, q);
+  if (rc) return rc;
+  rc = check_coords(q, i, j);
+  if (rc) return rc;
+  // the plan depends on shapes, strides and 16-byte alignment only: a fixed aligned address stands in for the tensors
+  void* const fake = (void*)(uintptr_t)4096;
+  GemmDesc d = summa_desc(form, fake, fake, fake, M, K, N, q, i, j, OPTIMUS_BF16, nullptr);
+  d.corun = corun;
+  return gemm_plan_of(d, have_ws != 0, out3) ? OPTIMUS_OK : OPTIMUS_EDTYPE;
+}
 int optimus_debug_last_gemm_plan(void) { return gemm_last_plan(); }
 
 }  // extern "C"

@@ -98,6 +98,7 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream);       // bf16 matri
 bool gemm_mfma_supported(const GemmDesc& d);
 int launch_mfma_rate(float* out, int workgroups, int iters, int random_data, hipStream_t stream);   // probe.hip
 size_t gemm_plan_bytes(const GemmDesc& d);                         // workspace the planned launch wants (0: none)
+bool gemm_plan_of(const GemmDesc& d, bool have_ws, int out[3]);
 size_t gemm_partials_bytes(const GemmDesc& d, int splits);
 // force a specific kernel variant (benchmark sweeps); -1 = automatic
 void gemm_set_variant(int v);

@@ -1507,6 +1507,15 @@ size_t gemm_plan_bytes(const GemmDesc& d) {
   return p.seq ? 0 : gemm_partials_bytes(d, p.splits);
 }
 
+// The plan a launch of d would use (host arithmetic only; nothing is enqueued): {tile variant, panel split,
+// 1 if the split is walked inside the workgroups}.  False when the matrix-core kernels do not take the product.
+bool gemm_plan_of(const GemmDesc& d, bool have_ws, int out[3]) {
+  if (!gemm_mfma_supported(d)) return false;
+  const Plan p = make_plan(d, epilogue_vec_ok(d), have_ws);
+  out[0] = p.variant; out[1] = p.splits; out[2] = p.seq;
+  return true;
+}
+
 int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
   if (!gemm_mfma_supported(d)) return OPTIMUS_EINVAL;
   const bool vec_ok = epilogue_vec_ok(d);
