@@ -5,8 +5,10 @@
 //
 // Forward keeps one fp32 number per query row, L = log sum_u exp(S_tu); backward rebuilds P = exp(S - L) tile by tile
 // and uses rowsum(dO * O) in place of rowsum(dP * P).
+// Backward is two bodies (dQ; dK and dV), each recomputing S; small launches run them as one grid ordered by loop
+// length (attn_fused_bwd_kernel), large ones as two kernels.
 //
-// Work layout (all three kernels).  A workgroup of four wavefronts owns 64 rows (queries in the forward and dQ
+// Work layout (forward and both backward bodies).  A workgroup of four wavefronts owns 64 rows (queries in the forward and dQ
 // kernels, keys in the dK/dV kernel).  Wavefront w works on rows 32*(w & 1).. and on every second 64-wide block of the
 // other index (blocks of parity w >> 1): the loop over the other index is the critical path of these launches (the
 // configurations this library is built for give at most two wavefronts per compute unit), so it is cut in two and
