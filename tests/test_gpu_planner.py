@@ -47,6 +47,15 @@ def test_automatic_plan_is_close_to_the_best_forced_variant(name):
                 f"best forced {times[best_v][1]} {t_best * 1e3:6.1f} us ({t_auto / t_best:.2f}x)")
         print(line, flush=True)
         if t_auto > SLACK * t_best:
-            bad.append(line)
+            # near the limit a single timing decides nothing: time the two contenders again, keep each one's best
+            for _ in range(3):
+                try:
+                    opt.debug_set_gemm_variant(best_v)
+                    t_best = min(t_best, event_time_ms(run, 20))
+                finally:
+                    opt.debug_set_gemm_variant(-1)
+                t_auto = min(t_auto, event_time_ms(run, 20))
+            if t_auto > SLACK * t_best:
+                bad.append(line + f"; again: {t_auto * 1e3:.1f} against {t_best * 1e3:.1f} us")
         del A, B, C
     assert not bad, "\n".join(bad)
