@@ -66,9 +66,10 @@ def trace(trace_csv, bench_json, out_md, cmd, title, traffic_json):
             runs.append(cur)
         runs = [x for x in runs if len(x) >= 10]
         lines += ["", f"## dominant product kernel `{dom[0]}` (grid {dom[1]}): runs of consecutive launches", "",
-                  "One run = one graph replay of bench.py's per-product timing.  In order: untimed and timed replays with the same",
-                  "buffers (`roofline.avg_us_warm`), then untimed and timed replays cycling through independent buffer sets",
-                  "(`roofline.avg_us`, the figure `roofline.achieved` is computed from).", "",
+                  "One run = the launches of bench.py's per-product timing that the trace shows back to back.  In order: the replays",
+                  "with the same buffers (`roofline.avg_us_warm`), then the replays cycling through independent buffer sets",
+                  "(`roofline.avg_us`, the figure `roofline.achieved` is computed from).  The HIP-event figures of the JSON below",
+                  "also contain the few microseconds between two launches of a graph.", "",
                   "| run | launches | avg us | min us | max us |", "|---|---|---|---|---|"]
         for k, x in enumerate(runs[:12]):
             lines.append(f"| {k} | {len(x)} | {statistics.mean(x) / 1e3:.2f} | {min(x) / 1e3:.2f} | {max(x) / 1e3:.2f} |")
