@@ -75,7 +75,9 @@ def trace(trace_csv, bench_json, out_md, cmd, title, traffic_json):
             lines.append(f"| {k} | {len(x)} | {statistics.mean(x) / 1e3:.2f} | {min(x) / 1e3:.2f} | {max(x) / 1e3:.2f} |")
     keep = ("metric", "value", "unit", "ms_per_step", "config", "roofline", "step_detail", "step_fused_attention", "gemms",
             "bandwidth_kernels", "cpu_baseline")
-    lines += ["", "The run also contains torch's random-number and copy kernels that build the synthetic inputs (not listed).", "",
+    lines += ["", "The run also contains torch's random-number and copy kernels that build the synthetic inputs (not listed).",
+              "With kernel tracing on every launch carries the profiler's overhead, so `ms_per_step` and `value` of this run are a",
+              "few percent worse than those of the same command without the profiler; the per-kernel durations are what this file is for.", "",
               "## bench.py JSON line of the same run (abridged)", "", "```json",
               json.dumps({k: d[k] for k in keep if k in d}, indent=1, ensure_ascii=False), "```", ""]
     open(out_md, "w").write("\n".join(lines) + "\n")
