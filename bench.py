@@ -572,6 +572,11 @@ def main():
     }
 
     out["mfma_ceiling"] = mfma_ceiling(opt, torch)
+    # the dominant product against what the matrix cores of THIS box sustain on toggling operands with every CU busy
+    sustained = [r["tflops"] for r in out["mfma_ceiling"] if r["workgroups"] == 256 and r["operands"] != "zeros"]
+    if sustained and out.get("roofline"):
+        out["roofline"]["mfma_only_sustained_tflops"] = sustained[0]
+        out["roofline"]["frac_of_mfma_only_sustained"] = round(out["roofline"]["achieved"] / sustained[0], 4)
     if not args.no_sweep:
         out["model_ends"] = time_model_ends(opt, torch, b, s, h, q, di, dj, 32768, args.gemm_reps, 9)
     if not args.no_sweep and args.workload == "config4":
