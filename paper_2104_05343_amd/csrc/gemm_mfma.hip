@@ -31,6 +31,7 @@
 // The two MFMA operands are swapped (D^T = B^T A^T) so that every lane ends up with four
 // consecutive columns of one output row; results leave through wavefront-private LDS chunks as
 // whole rows of the tile (see ChunkBf16).
+#include <atomic>
 #include <type_traits>
 
 #include "common.hpp"
@@ -44,17 +45,20 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
-static int g_variant = -1;
-static int g_loop = 2;   // k-loop of the fast path where both exist (see gemm_mfma_kernel); 1 or 2
+// Tuning hooks of the benchmark and the tests (process-wide; atomics, so that a hook set from one thread while
+// another launches is a race on WHICH setting a launch sees, never on memory).  They select tiles and the k-loop, and
+// a forced tile plans its own panel split; nothing else in the library is process-global state.
+static std::atomic<int> g_variant{-1};
+static std::atomic<int> g_loop{2};   // k-loop of the fast path where both exist (see gemm_mfma_kernel); 1 or 2
 void gemm_set_variant(int v) {
   // v >= 1000: the older k-loop with variant v - 1000 (1000 + 255 = automatic tile); otherwise the default k-loop
   if (v >= 1000) { g_loop = 1; v -= 1000; if (v == 255) v = -1; } else g_loop = 2;
   g_variant = v;
 }
 int gemm_get_variant() { return g_variant; }
-static int g_corun_variant[2] = {-1, -1};
+static std::atomic<int> g_corun_variant[2] = {{-1}, {-1}};
 void gemm_set_corun_variants(int chain_v, int branch_v) { g_corun_variant[0] = chain_v; g_corun_variant[1] = branch_v; }
-static int g_last_plan = -1;
+static std::atomic<int> g_last_plan{-1};
 int gemm_last_plan() { return g_last_plan; }
 
 
@@ -1390,7 +1394,9 @@ static int num_cus() {
 static Plan make_plan(const GemmDesc& d, bool vec_ok, bool have_ws) {
   const bool allow_split = true;
   Plan best = {kGuardVariant, 1, 0};
-  if (!vec_ok || g_variant == kGuardVariant) return best;  // the fast kernels only have the vector epilogue
+  const int forced = g_variant.load();                       // one consistent view of the hooks per plan
+  const int forced_corun = d.corun > 0 ? g_corun_variant[d.corun - 1].load() : -1;
+  if (!vec_ok || forced == kGuardVariant) return best;  // the fast kernels only have the vector epilogue
   // per candidate: variant id, workgroups resident per CU, fixed cost (launch, prologue, epilogue: us and us per MiB
   // of output), and the time per slab of one workgroup: alone on the chip (t_lone), with every CU holding one
   // workgroup (t_full: all CUs' loads share the L2 fabric; the rise is steep only near full occupancy, hence the
@@ -1426,8 +1432,8 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool have_ws) {
   for (int ci = 0; ci < kCands; ++ci) {
     const Cand& c = cand[ci];
     const int v = c.v;
-    if (g_variant >= 0 && g_variant != kGuardVariant && v != (g_variant == 4 ? 0 : g_variant)) continue;
-    if (pass == 1 && d.corun > 0 && g_corun_variant[d.corun - 1] >= 0 && v != g_corun_variant[d.corun - 1]) continue;
+    if (forced >= 0 && v != (forced == 4 ? 0 : forced)) continue;
+    if (pass == 1 && forced_corun >= 0 && v != forced_corun) continue;
     if (!variant_fits(kVariants[v], d)) continue;
     const long long tiles = (long long)(d.Mb / kVariants[v].BM) * (d.Nb / kVariants[v].BN) * (pass == 0 ? 1 : batch);
     for (int sp = fixed_sp ? fixed_sp : 1; sp <= (fixed_sp ? fixed_sp : 8); ++sp) {
