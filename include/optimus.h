@@ -32,8 +32,9 @@
  *   ECOORD / EDTYPE / EWORKSPACE nothing has been enqueued.  OPTIMUS_EHIP (the
  *   runtime refused a launch) can come from a later kernel of a call that
  *   enqueues several.  No exceptions.  Process state: the tuning hooks at the
- *   end of this file, and per device one stream with its events that
- *   optimus_layer_bwd creates on first use (see there).
+ *   end of this file (process-wide, atomic), per device one stream with its
+ *   events that optimus_layer_bwd creates on first use (see there), and per
+ *   device the fixed scratch array of optimus_attention_fused_bwd_static.
  * Determinism.  No floating-point atomics: the same call on the same inputs
  *   gives bitwise identical output.
  */
