@@ -188,7 +188,9 @@ int optimus_layernorm2d_bwd(const void* dY, const void* xhat, const float* rstd,
  * ws must hold optimus_attention_workspace_bytes(...) bytes (scratch for one
  * device's scores); a whole-grid call (i = j = -1) takes g devices per launch
  * when ws holds g times that (same bits, fewer and larger launches). bf16 only.
- * Requires q | b, q | n, n | h, d % 8 == 0, s % 8 == 0. */
+ * Requires q | b, q | n, n | h, d % 8 == 0, s % 8 == 0, s <= 4096 (a row of
+ * scores is held by one wavefront; longer sequences: optimus_attention_fused_*);
+ * OPTIMUS_ESHAPE otherwise. */
 int optimus_attention_fwd(const void* qkv, void* probs, void* attn, int b, int s, int h, int n, int q,
                           int i, int j, int causal, int dtype, void* ws, size_t ws_bytes, void* stream);
 int optimus_attention_bwd(const void* qkv, const void* probs, const void* d_attn, void* d_qkv, int b,
