@@ -174,6 +174,12 @@ def time_gemms(opt, torch, gemms, q, i, j, reps, seed, rotating=True):
         row = {"name": name, "form": form, "block": [M // q, K, N // q], "panel": K // q, "us": round(ms * 1e3, 2),
                "tflops": round(tf, 1), "pct_peak": round(100 * tf / PEAK_BF16_TFLOPS, 1), "split_ws_bytes": int(nbytes),
                "plan": list(plan) if plan else None}
+        if nbytes > 0:
+            # the same product without workspace: the split is walked inside the workgroups, no partial tile reaches
+            # memory, no combine launch, same bits -- what keeping every partial sum on the CU costs for this shape
+            ms_n = event_time_ms(lambda: opt.summa(form, A, B, C, M, K, N, q, i, j, opt.BF16), reps)
+            row["us_without_partials_in_memory"] = round(ms_n * 1e3, 2)
+            row["plan_without_workspace"] = list(opt.debug_last_gemm_plan())
         if rotating:
             dev_ws = 2 * ((M // q) * K + K * (N // q) + (M // q) * (N // q))   # bytes one device touches per launch
             nsets = max(2, min(64, -(-ROTATE_BYTES // dev_ws)))

@@ -1484,8 +1484,28 @@ static Plan make_plan(const GemmDesc& d, bool vec_ok, bool have_ws) {
   }
   }
   if (best.splits > 1 && !best.seq && !have_ws) {
+    // No workspace: the same split, walked inside the workgroups (same bits).  One workgroup then owns all slabs of its
+    // tile, so the tile is picked again for that walk: the tile with the least estimated time among those that have
+    // registers for the second accumulator set (not 256x256).
     best.seq = 1;
-    if (kVariants[best.variant].BM * kVariants[best.variant].BN >= 256 * 256) {   // no registers for a second accumulator set
+    float seq_best = 0.f;
+    int seq_v = -1;
+    for (int ci = 0; ci < kCands; ++ci) {
+      const Cand& c = cand[ci];
+      if (kVariants[c.v].BM * kVariants[c.v].BN >= 256 * 256 || !variant_fits(kVariants[c.v], d)) continue;
+      if (forced >= 0 && c.v != forced) continue;
+      const long long tiles = (long long)(d.Mb / kVariants[c.v].BM) * (d.Nb / kVariants[c.v].BN) * batch;
+      const long long cap = ncu * c.per_cu;
+      const long long rounds = (tiles + cap - 1) / cap;
+      const long long in_round = tiles < cap ? tiles : cap;
+      const int resident = (int)((in_round + ncu - 1) / ncu);
+      const float busy = in_round >= ncu ? 1.0f : (float)in_round / (float)ncu;
+      const float t = c.t_lone + (c.t_full - c.t_lone) * busy * busy + c.t_more * (float)(resident - 1);
+      const float cost = c.fixed_us + c.out_us_per_mib * out_mib * (float)batch + (float)rounds * (float)slabs * t;
+      if (seq_v < 0 || cost < seq_best) { seq_best = cost; seq_v = c.v; }
+    }
+    if (seq_v >= 0) best.variant = seq_v;
+    else if (kVariants[best.variant].BM * kVariants[best.variant].BN >= 256 * 256) {
       static const int order[7] = {1, 2, 8, 9, 3, 6, 7};
       for (int k = 0; k < 7; ++k)
         if (variant_fits(kVariants[order[k]], d)) { best.variant = order[k]; break; }
